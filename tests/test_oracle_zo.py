@@ -1,0 +1,146 @@
+"""Pins for the SPSA scalar and the sparse update (Definitions 1, 2, 4 and
+the fixed-parameter update rule of Section 3.4)."""
+import numpy as np
+
+from oracle import layer, quant, philox, zo
+from helpers import make_oracle_matrix, clone
+
+
+def _two_mats():
+    a = make_oracle_matrix(seed=1, M=8, N=64, K=128, group=32, nnz=21, nnz_base=0)
+    b = make_oracle_matrix(seed=2, M=8, N=96, K=64, group=32, nnz=10, nnz_base=24)
+    return [a, b]
+
+
+def test_eps_zero_gives_zero_g_and_no_update():
+    mats = _two_mats()
+    before = [m.sp_val.copy() for m in mats]
+    r = zo.zo_step(mats, seed=3, step=0, eps=0.0, lr=1e-2)
+    assert r["g"] == 0.0 and r["loss_plus"] == r["loss_minus"]
+    for m, b in zip(mats, before):
+        assert np.array_equal(m.sp_val, b)
+
+
+def test_linear_loss_closed_form():
+    # loss = sum a[m,n] y[m,n]  =>  d loss / d W[n,k] = sum_m a[m,n] x[m,k] =: c,
+    # and g = c . z exactly for any eps (the loss is linear in w).
+    mats = _two_mats()
+    rng = np.random.default_rng(5)
+    a = [rng.standard_normal((8, 64)), rng.standard_normal((8, 96))]
+    it = iter(a * 2)
+    r = zo.zo_step([clone(m) for m in mats], seed=9, step=4, eps=1e-3, lr=0.0,
+                   loss_fn=lambda y, t: float(np.sum(next(it) * y)))
+    want = 0.0
+    for m, ai in zip(mats, a):
+        x = quant.bf16_bits_to_f64(m.x_bits)
+        K = x.shape[1]
+        idx = m.sp_idx.astype(np.int64)
+        c = np.einsum("mj,mj->j", ai[:, idx // K], x[:, idx % K])
+        want += float(c @ philox.zbar(9, 4, m.nnz_base, idx.size))
+    assert abs(r["g"] - want) < 1e-9 * max(1.0, abs(want))
+
+
+def test_quadratic_loss_g_equals_directional_derivative():
+    # MSE is quadratic in W, so the central difference is exact:
+    # g = z . grad L on the mask, for any eps.
+    mats = _two_mats()
+    for eps in (1e-3, 1e-1):
+        ms = [clone(m) for m in mats]
+        r = zo.zo_step(ms, seed=1, step=2, eps=eps, lr=0.0)
+        want = 0.0
+        for m in mats:
+            y0 = layer.linear_fwd(m.x_bits, m.codes, m.scales, m.group, m.sp_idx, m.sp_val)
+            grad = layer.mse_grad_on_mask(m.x_bits, y0, m.target_bits, m.sp_idx, m.codes.shape[1])
+            want += float(grad @ philox.zbar(1, 2, m.nnz_base, m.sp_idx.size))
+        assert abs(r["g"] - want) < 1e-7 * max(1.0, abs(want)) / eps * 1e-3 + 1e-9
+
+
+def test_bruteforce_dense_spsa_tiny():
+    # Definition 1 + Definition 2 on the dense reconstruction with z = z_bar
+    # scattered into a d-vector; triple-loop forward.
+    m = make_oracle_matrix(seed=7, M=2, N=8, K=64, group=32, nnz=6, nnz_base=4)
+    seed, step, eps, lr = 11, 3, 1e-3, 0.05
+    K = 64
+    e = float(np.float32(eps))
+    w = layer.effective_weight(m.codes, m.scales, 32, m.sp_idx, m.sp_val).reshape(-1)
+    zd = np.zeros_like(w)
+    zd[m.sp_idx.astype(np.int64)] = philox.zbar(seed, step, 4, 6)
+    x = quant.bf16_bits_to_f64(m.x_bits)
+    t = quant.bf16_bits_to_f64(m.target_bits)
+
+    def f(wv):
+        W = wv.reshape(8, K)
+        tot = 0.0
+        for mm in range(2):
+            for n in range(8):
+                acc = 0.0
+                for k in range(K):
+                    acc += x[mm, k] * W[n, k]
+                tot += (acc - t[mm, n]) ** 2
+        return tot / 16.0
+
+    g = (f(w + e * zd) - f(w - e * zd)) / (2 * e)
+    w_new = w - float(np.float32(lr)) * g * zd
+    mm = clone(m)
+    r = zo.zo_step([mm], seed, step, eps, lr)
+    assert abs(r["g"] - g) < 1e-9 * max(1.0, abs(g))
+    idx = m.sp_idx.astype(np.int64)
+    assert np.allclose(mm.sp_val, w_new[idx], rtol=3e-7, atol=0)       # fp32 storage
+    rest = np.ones(w.size, bool)
+    rest[idx] = False
+    assert np.array_equal(w_new[rest], w[rest])                        # dense part frozen
+
+
+def test_plus_minus_two_plus_restores_and_matches_functional_form():
+    mats = _two_mats()
+    a = [clone(m) for m in mats]
+    b = [clone(m) for m in mats]
+    ra = zo.zo_step(a, seed=8, step=1, eps=1e-3, lr=1e-3)
+    rb = zo.zo_step_inplace(b, seed=8, step=1, eps=1e-3, lr=1e-3)
+    for m, rest in zip(mats, rb["restored"]):
+        ulp = np.spacing(np.abs(m.sp_val) + np.float32(1e-2))
+        assert np.all(np.abs(rest - m.sp_val) <= 2 * ulp)
+    # in-place arithmetic rounds the perturbed value to fp32; g agrees to that
+    sigma = 0.0
+    for m in mats:
+        y0 = layer.linear_fwd(m.x_bits, m.codes, m.scales, m.group, m.sp_idx, m.sp_val)
+        sigma += float(np.sum(layer.mse_grad_on_mask(m.x_bits, y0, m.target_bits, m.sp_idx, m.codes.shape[1]) ** 2))
+    assert abs(ra["g"] - rb["g"]) < 1e-3 * max(abs(ra["g"]), np.sqrt(sigma))
+    assert np.isfinite(rb["g"])
+
+
+def test_update_rule_and_sign():
+    m = make_oracle_matrix(seed=9, M=4, N=32, K=64, group=32, nnz=8)
+    z = philox.zbar(0, 0, 0, 8)
+    before = m.sp_val.copy()
+    zo.sparse_update([m], [z], g=2.0, lr=0.25)
+    assert np.allclose(m.sp_val, before.astype(np.float64) - 0.5 * z, rtol=1e-6)
+    assert m.sp_val.dtype == np.float32
+
+
+def test_descent_on_average():
+    # ZO-SGD with a small step lowers the quadratic loss in expectation
+    m = make_oracle_matrix(seed=10, M=16, N=64, K=64, group=32, nnz=64)
+    def L(mm):
+        return layer.mse_loss(layer.linear_fwd(mm.x_bits, mm.codes, mm.scales, 32, mm.sp_idx, mm.sp_val), mm.target_bits)
+    l0 = L(m)
+    for step in range(200):
+        zo.zo_step([m], seed=4, step=step, eps=1e-3, lr=2e-3)
+    assert L(m) < l0
+
+
+def test_resume_is_exact():
+    a = _two_mats()
+    b = [clone(m) for m in a]
+    for s in range(6):
+        zo.zo_step(a, 5, s, 1e-3, 1e-3)
+    for s in range(3):
+        zo.zo_step(b, 5, s, 1e-3, 1e-3)
+    saved = [m.sp_val.copy() for m in b]
+    c = [clone(m) for m in _two_mats()]
+    for m, v in zip(c, saved):
+        m.sp_val = v
+    for s in range(3, 6):
+        zo.zo_step(c, 5, s, 1e-3, 1e-3)
+    for x, y in zip(a, c):
+        assert np.array_equal(x.sp_val, y.sp_val)
