@@ -1,0 +1,198 @@
+#!/usr/bin/env python3
+"""Benchmark of the sensitive-sparse ZO step on one MI355X.
+
+A "step" is one pass of the whole hot path over the whole stack of the chosen
+workload: for every matrix a +eps and a -eps forward (int4 dequant + sparse
+scatter with the Gaussian regenerated in-kernel + MFMA product), the MSE loss
+of each, the SPSA scalar g, and the sparse update of every matrix.  Inputs are
+seeded, synthetic and already resident in HBM when the clock starts.
+
+Prints ONE JSON line (see README for the fields).
+"""
+import argparse
+import json
+import os
+import platform
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_MFMA_16BIT_TFLOPS = 2500.0      # MI355X dense fp16/bf16 matrix peak
+PEAK_HBM_GBS = 8000.0                # MI355X HBM3E
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes_fwd(m):
+    """Bytes one forward must move: codes + scales + sparse (idx, val) + x + y."""
+    return (m.N * m.K // 2 + 2 * m.N * (m.K // m.group) + 8 * m.nnz + 2 * m.M * m.K + 4 * m.M * m.N)
+
+
+def cpu_baseline(cfg, args, total_flops_per_step):
+    """The oracle, as it stands, on a bounded sample of the same workload."""
+    import numpy as np
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from helpers import make_oracle_matrix
+    from oracle import zo as ozo
+    from paper_2406_02913_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count()
+    M = args.m or cfg["M"]
+    done_flops, t_spent, used = 0.0, 0.0, []
+    for i, (name, N, K) in enumerate(cfg["block"]):
+        m = make_oracle_matrix(synth.matrix_seed(args.data_seed, 0, i), M, N, K, cfg["group"],
+                               cfg["density"], cfg["mask"])
+        t0 = time.perf_counter()
+        ozo.zo_step([m], args.seed, 0, cfg["eps"], cfg["lr"])
+        t_spent += time.perf_counter() - t0
+        done_flops += 2 * 2.0 * M * N * K
+        used.append(name)
+        if t_spent >= args.cpu_seconds:
+            break
+    frac = done_flops / total_flops_per_step
+    est_step_s = t_spent / frac
+    return {"value": 1.0 / est_step_s, "unit": "ZO steps/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"full oracle ZO step (fp64) on matrices {used} of layer 0 at M={M}: {t_spent:.2f} s for "
+                      f"{100 * frac:.3f}% of one step's FLOPs, extrapolated by FLOPs",
+            "cpu": platform.processor() or platform.machine(), "os_cpu_count": os.cpu_count()}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c3", help="c1|c2|c3|c4|c5|c3m16 (see synth.WORKLOADS)")
+    ap.add_argument("--layers", type=int, default=None, help="override the number of decoder blocks")
+    ap.add_argument("--m", type=int, default=None, help="override the token count")
+    ap.add_argument("--density", type=float, default=None)
+    ap.add_argument("--tile", default="f16", choices=["f16", "bf16"])
+    ap.add_argument("--unfused-loss", action="store_true", help="write y and run the separate loss kernel")
+    ap.add_argument("--seed", type=int, default=2024)
+    ap.add_argument("--data-seed", type=int, default=0)
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle baseline leg (0 = skip)")
+    ap.add_argument("--kernel-reps", type=int, default=3, help="passes over the stack when timing the forward kernel alone")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        log("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
+        sys.exit(2)
+
+    import torch
+    from paper_2406_02913_amd import stack, synth, szo
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dt = szo.TILE_F16 if args.tile == "f16" else szo.TILE_BF16
+    flags = 0 if args.unfused_loss else szo.STEP_FUSED_LOSS
+
+    t0 = time.perf_counter()
+    count = [0]
+
+    def progress(lin):
+        count[0] += 1
+        if count[0] % 28 == 0:
+            log(f"[bench] built {count[0]} matrices ({time.perf_counter() - t0:.1f} s)")
+
+    mats, cfg = stack.build_stack(args.workload, args.data_seed, "cuda", M=args.m, layers=args.layers,
+                                  density=args.density, progress=progress)
+    if args.density is not None:
+        cfg["density"] = args.density
+    torch.cuda.synchronize()
+    log(f"[bench] {len(mats)} matrices resident after {time.perf_counter() - t0:.1f} s, "
+        f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB")
+
+    descs = szo.desc_array([m.desc(dt, with_y=bool(args.unfused_loss)) for m in mats])
+    ws = szo.new_workspace()
+    scal = torch.zeros(3, dtype=torch.float64, device="cuda")
+    eps, lr = cfg["eps"], cfg["lr"]
+    stream = torch.cuda.current_stream()
+
+    def one_step(s):
+        szo.szo_zo_step(descs, args.seed, s, eps, lr, scal, ws, flags, stream.cuda_stream)
+
+    for s in range(args.warmup):
+        one_step(s)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    w0 = time.perf_counter()
+    ev0.record(stream)
+    for s in range(args.warmup, args.warmup + args.steps):
+        one_step(s)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - w0
+    ms_per_step = ev0.elapsed_time(ev1) / args.steps
+    lp, lm, g = scal.cpu().tolist()
+    log(f"[bench] {ms_per_step:.3f} ms/step (events), {1e3 * wall / args.steps:.3f} ms/step (wall); "
+        f"last step L+={lp:.6f} L-={lm:.6f} g={g:.4e}")
+
+    # ---- the dominant kernel alone: every forward launch of the stack, bracketed by events ----
+    fwd_flops = sum(2.0 * m.M * m.N * m.K for m in mats)
+    fwd_bytes = sum(algorithmic_bytes_fwd(m) for m in mats)
+    acc = torch.zeros(1, dtype=torch.float64, device="cuda")
+
+    def fwd_pass(sign):
+        for i, m in enumerate(mats):
+            if args.unfused_loss:
+                szo.szo_linear_fwd(descs[i], args.seed, 0, sign, eps, stream.cuda_stream)
+            else:
+                szo.szo_linear_fwd_mse(descs[i], args.seed, 0, sign, eps, 1.0 / (m.M * m.N), acc, ws, stream.cuda_stream)
+
+    fwd_pass(+1)
+    torch.cuda.synchronize()
+    k0, k1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    k0.record(stream)
+    for r in range(args.kernel_reps):
+        fwd_pass(+1 if r % 2 == 0 else -1)
+    k1.record(stream)
+    torch.cuda.synchronize()
+    launches = args.kernel_reps * len(mats)
+    k_ms = k0.elapsed_time(k1) / launches
+    tflops = fwd_flops / len(mats) / (k_ms * 1e-3) / 1e12
+    gbs = fwd_bytes / len(mats) / (k_ms * 1e-3) / 1e9
+    mfma_bound = (fwd_flops / fwd_bytes) > (PEAK_MFMA_16BIT_TFLOPS * 1e12) / (PEAK_HBM_GBS * 1e9)
+    if mfma_bound:
+        roof = {"bound": "mfma", "achieved": round(tflops, 2), "peak": PEAK_MFMA_16BIT_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(tflops / PEAK_MFMA_16BIT_TFLOPS, 4), "traffic": None}
+    else:
+        roof = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None}
+    roof.update({"kernel": "linear_fwd_kernel", "avg_launch_us": round(1e3 * k_ms, 2), "launches_timed": launches,
+                 "flops_per_launch": fwd_flops / len(mats), "bytes_per_launch": fwd_bytes / len(mats)})
+    step_flops = 2 * fwd_flops
+    log(f"[bench] forward kernel: {1e3 * k_ms:.1f} us/launch avg, {tflops:.1f} TFLOP/s, {gbs:.1f} GB/s algorithmic")
+
+    base = None
+    if args.cpu_seconds > 0:
+        base = cpu_baseline(cfg, args, step_flops)
+        log(f"[bench] oracle baseline: {base['value']:.3e} steps/s on {base['cores']} threads")
+
+    M = mats[0].M
+    out = {
+        "metric": "ZO steps/sec + % bf16 MFMA peak, int4+0.1%-sparse linears, Llama-2-7B shapes",
+        "value": round(1e3 / ms_per_step, 4), "unit": "ZO steps/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16" if dt == szo.TILE_F16 else "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {len(mats)} matrices ({len(mats) // len(cfg['block'])} block(s) of "
+                               f"{[b[0] for b in cfg['block']]}), M={M} tokens, int4 group {cfg['group']}, "
+                               f"mask {cfg['density']:g} {cfg['mask']}, eps={eps}, lr={lr}",
+                   "loss": "fused into the forward epilogue" if flags else "separate kernel",
+                   "tile": args.tile, "accumulate": "f32", "loss_accumulate": "f64"},
+        "step_tflops": round(step_flops / (ms_per_step * 1e-3) / 1e12, 2),
+        "step_frac_of_mfma_peak": round(step_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_MFMA_16BIT_TFLOPS, 4),
+        "roofline": roof,
+        "cpu_baseline": base,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

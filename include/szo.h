@@ -1,0 +1,183 @@
+/*
+ * szo.h -- C ABI of libszo: the hot path of sensitive-sparse zeroth-order
+ * fine-tuning (arXiv 2406.02913) for AMD MI355X (gfx950).
+ *
+ * One ZO-SGD step over a stack of linear layers whose frozen dense weights are
+ * 4-bit group-quantised and whose "sensitive" weights (a static mask of about
+ * 0.1% of the coordinates) are kept as fp32 sparse values:
+ *
+ *   two forwards at  w_sparse + eps*z  and  w_sparse - eps*z   (Definition 1, Definition 4)
+ *   g = (L+ - L-) / (2 eps)                                    (Definition 1)
+ *   w_sparse <- w_sparse - lr * g * z                          (Section 3.4, fixed-parameter update rule)
+ *
+ * where each forward is  y = x (Dequantize(Q(w_dense)) + w_sparse)^T  evaluated
+ * as ONE dense product after the sparse part has been added to the dequantised
+ * tile (Appendix C.5, the SparseAdd-then-DenseMM form), and z is a Gaussian
+ * regenerated from (seed, step, entry index) and never stored (Section 3.5,
+ * random-seed trick).
+ *
+ * Conventions
+ *   - Every function returns SZO_OK (0) or a negative error code.  Nothing
+ *     throws, exits or prints.  SZO_ELAUNCH means a HIP call failed; the HIP
+ *     error code is then available from szo_last_hip_error().
+ *   - "device" pointers are HIP device memory owned by the caller (e.g. PyTorch
+ *     tensors); the library never frees or keeps them.  "host" pointers are
+ *     ordinary process memory, read or written before the call returns.
+ *   - Calls that take a `stream` only enqueue work on that hipStream_t (passed
+ *     as void*; NULL = the default stream).  They do not allocate and do not
+ *     synchronise with the host.
+ *   - Row-major everywhere.  x is [M,K], the weight is [N,K] (out x in),
+ *     y = x W^T is [M,N].
+ */
+#ifndef SZO_H_
+#define SZO_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SZO_OK            0
+#define SZO_EINVAL       (-1)   /* null pointer, bad shape, misalignment, bad enum */
+#define SZO_EUNSUPPORTED (-2)   /* valid but outside what the kernels handle       */
+#define SZO_ELAUNCH      (-3)   /* a HIP runtime call failed                        */
+
+/* Sparse layout constants ("TCSR"): rows are cut into groups of 128, each group
+ * into four bands of 32 rows; columns into tiles of 64.
+ *   tile(n,k) = ((n/128) * (K/64) + k/64) * 4 + (n%128)/32
+ * Entries are ordered by (tile, (n%32)*64 + k%64); tile_ptr[t]..tile_ptr[t+1]
+ * is the range of tile t.  The position j of an entry in this order is its
+ * entry index: together with nnz_base it selects the entry's Gaussian. */
+#define SZO_TILE_ROWS   32
+#define SZO_GROUP_ROWS  128
+#define SZO_TILE_COLS   64
+
+/* 16-bit type the dequantised weight tile and the activations are staged in
+ * before the matrix-core product. */
+#define SZO_TILE_F16   0   /* default: keeps eps*z within the estimator's error budget */
+#define SZO_TILE_BF16  1
+
+/* One linear layer.  Plain data; filled by the caller for every call. */
+typedef struct szo_linear_desc {
+  int64_t  M, N, K;        /* tokens, out features, in features; K % 64 == 0           */
+  int32_t  group;          /* quantisation group along K: 32, 64 or 128; divides K      */
+  int32_t  tile_dtype;     /* SZO_TILE_F16 or SZO_TILE_BF16                             */
+  int64_t  nnz;            /* number of sensitive entries of this matrix (may be 0)     */
+  uint64_t nnz_base;       /* global index of entry 0; multiple of 4                    */
+  const void*     x;        /* device, bf16  [M,K]                                      */
+  const uint8_t*  qweight;  /* device, u4x2  [N,K/2]; low nibble = even k; code = q + 8 */
+  const void*     scales;   /* device, fp16  [N,K/group]                                */
+  const uint32_t* tile_ptr; /* device, u32   [szo_num_tiles(N,K) + 1]                   */
+  const uint32_t* sp_idx;   /* device, u32   [nnz] flat n*K+k in TCSR order             */
+  float*          sp_val;   /* device, fp32  [nnz] same order; read-only in forwards    */
+  float*          y;        /* device, fp32  [M,N] output (may be NULL in szo_linear_fwd_mse) */
+  const void*     target;   /* device, bf16  [M,N]; only read by the loss-fusing calls  */
+} szo_linear_desc;
+
+/* ---- hot calls (device work, enqueued on `stream`) ------------------------------------- */
+
+/* Perturbed forward of one layer (Appendix C.5, SparseAdd then DenseMM; perturbation of
+ * Definition 4):  y = x (dq + S)^T with dq[n,k] = (code-8)*scale[n,k/group] and
+ * S[n_j,k_j] = sp_val[j] + sign*eps*z_j.  sign in {-1,0,+1}; sign 0 or eps 0 = unperturbed.
+ * z_j is the Gaussian of global entry nnz_base + j for (seed, step).
+ * Errors: SZO_EINVAL on null/misaligned pointers (x, qweight 16-byte; others natural), bad
+ * shape, bad sign/dtype; SZO_EUNSUPPORTED if K % 64 != 0, group not in {32,64,128} or N*K
+ * does not fit 32 bits.  M == 0 or N == 0 is a no-op. */
+int szo_linear_fwd(const szo_linear_desc* desc /* host */, uint64_t seed, uint64_t step,
+                   int sign, float eps, void* stream);
+
+/* Stand-in loss of the workloads: loss_acc += scale * sum_i (y[i] - target[i])^2, i < count
+ * (Definition 1 only needs a scalar f).  Accumulates in fp64 in a fixed order: results are
+ * bit-reproducible run to run.  y: device fp32; target: device bf16; loss_acc: device
+ * double; workspace: device, at least szo_workspace_bytes() bytes, 8-byte aligned, not shared
+ * with a call running concurrently on another stream.  count == 0 adds nothing. */
+int szo_mse_loss(const float* y, const void* target, int64_t count, double scale,
+                 double* loss_acc, void* workspace, void* stream);
+
+/* Forward with the loss folded into the product's epilogue: same y as szo_linear_fwd (written
+ * only if desc->y is not NULL) and loss_acc += scale * sum (y - desc->target)^2 without
+ * re-reading y from memory.  Same determinism and workspace rules as szo_mse_loss. */
+int szo_linear_fwd_mse(const szo_linear_desc* desc /* host */, uint64_t seed, uint64_t step,
+                       int sign, float eps, double scale, double* loss_acc, void* workspace,
+                       void* stream);
+
+/* SPSA scalar (Definition 1): *g = (*loss_plus - *loss_minus) / (2 eps); eps == 0 gives 0.
+ * All three pointers: device double. */
+int szo_spsa_g(const double* loss_plus, const double* loss_minus, float eps, double* g,
+               void* stream);
+
+/* Sparse ZO-SGD update (Section 3.4, fixed-parameter update rule):
+ * sp_val[j] -= lr * g * z_j, j < nnz, with exactly the z of the forwards for (seed, step).
+ * g: device double.  sp_idx is accepted for symmetry with the forward and may be NULL (the
+ * Gaussian is keyed by position j, not by matrix coordinates). */
+int szo_sparse_update(float* sp_val, const uint32_t* sp_idx, int64_t nnz, uint64_t nnz_base,
+                      uint64_t seed, uint64_t step, const double* g, float lr, void* stream);
+
+/* One whole step over `n` layers: for every layer a +eps forward and a -eps forward, each
+ * followed by its loss with scale 1/(M*N); then g; then the update of every layer.
+ * scalars: device double[3], overwritten with (L+, L-, g).  flags: bit 0 set = use the
+ * loss-fusing forward and never write y (desc->y may then be NULL).
+ * descs: host array.  Everything is enqueued on `stream`; no host synchronisation. */
+#define SZO_STEP_FUSED_LOSS 1
+int szo_zo_step(const szo_linear_desc* descs /* host */, int n, uint64_t seed, uint64_t step,
+                float eps, float lr, double* scalars, void* workspace, int flags, void* stream);
+
+/* Bytes of device workspace the loss-accumulating calls need (a constant). */
+size_t szo_workspace_bytes(void);
+
+/* Puts a freshly allocated workspace into its idle state (zeroes its header).  Needed once per
+ * workspace; every loss-accumulating call leaves the workspace idle again when it completes. */
+int szo_workspace_init(void* workspace, void* stream);
+
+/* ---- one-time set-up on the host (no GPU needed; deterministic) ------------------------- */
+
+/* Number of TCSR tiles of an [N,K] matrix: ceil(N/128) * (K/64) * 4.  0 if K % 64 != 0. */
+int64_t szo_num_tiles(int64_t N, int64_t K);
+
+/* Synthetic stand-in for the sensitive mask of Definition 3 (the real one needs gradients of
+ * a trained model).  kind 0: nnz distinct positions uniform over the matrix.  kind 1: heavy
+ * tail -- ceil(N/100) hot rows hold floor(nnz/2) entries, the rest is uniform.  Draw d of
+ * stream s is Philox-4x32-10(key = mask_seed, counter = (lo32 d, hi32 d, s, 0)), value
+ * (r0*2^32 + r1) mod range, duplicates dropped in draw order.  flat_out: host u32 [nnz],
+ * ascending flat positions n*K+k. */
+int szo_mask_generate(int64_t N, int64_t K, int64_t nnz, int kind, uint64_t mask_seed,
+                      uint32_t* flat_out);
+
+/* Tile-ordered layout from ascending unique flat positions.  Outputs (host): tile_ptr
+ * [szo_num_tiles+1], sp_idx [nnz], perm [nnz] with sp_idx[j] == flat_sorted[perm[j]] (perm may
+ * be NULL).  SZO_EINVAL if positions are not strictly ascending or out of range. */
+int szo_tcsr_build(int64_t N, int64_t K, const uint32_t* flat_sorted, int64_t nnz,
+                   uint32_t* tile_ptr_out, uint32_t* sp_idx_out, uint32_t* perm_out);
+
+/* Decomposition w = w_sparse + w_dense (Section 3.4) and 4-bit quantisation of w_dense
+ * (Section 3.5): masked weights are copied to sp_val_out (in the order of mask_flat) and set
+ * to zero; then per row and per group of `group` columns scale = fp16(max|w|/7),
+ * code = clamp(rint(w/scale),-8,7)+8 (scale 0 -> code 8).  W: host fp32 [N,K];
+ * q_out: host [N,K/2]; scales_out: host fp16 bit patterns [N,K/group]. */
+int szo_quantize_pack(const float* W, int64_t N, int64_t K, int group, const uint32_t* mask_flat,
+                      int64_t nnz, uint8_t* q_out, uint16_t* scales_out, float* sp_val_out);
+
+/* ---- inspection ----------------------------------------------------------------------- */
+
+/* Host evaluation of Philox-4x32-10 (ten rounds; multipliers 0xD2511F53, 0xCD9E8D57; key
+ * increments 0x9E3779B9, 0xBB67AE85). */
+int szo_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
+
+/* Device: for j < nnz write the four Philox words behind entry nnz_base + j to
+ * words_out[4*j..4*j+3] (device u32, may be NULL) and its Gaussian to z_out[j] (device fp32,
+ * may be NULL) -- the same device routine the forward and the update use. */
+int szo_debug_zbar(uint64_t nnz_base, int64_t nnz, uint64_t seed, uint64_t step,
+                   uint32_t* words_out, float* z_out, void* stream);
+
+/* HIP error code of the most recent SZO_ELAUNCH on this thread (0 if none). */
+int szo_last_hip_error(void);
+
+/* ABI version; bumped when a signature or the descriptor changes. */
+int szo_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SZO_H_ */

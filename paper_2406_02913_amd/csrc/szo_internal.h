@@ -1,0 +1,81 @@
+// Shared by the translation units of libszo: error bookkeeping and the layout of the
+// loss workspace.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "szo.h"
+
+namespace szo {
+
+extern thread_local int g_last_hip_error;
+
+inline int hip_failed(hipError_t e) {
+  if (e == hipSuccess) return 0;
+  g_last_hip_error = (int)e;
+  return 1;
+}
+
+#define SZO_HIP(expr) do { if (::szo::hip_failed((expr))) return SZO_ELAUNCH; } while (0)
+#define SZO_LAUNCH_CHECK() SZO_HIP(hipGetLastError())
+
+// Loss workspace: a ticket counter (first 64 bytes) followed by one fp64 partial per
+// workgroup.  The last workgroup to finish adds the partials in index order, which makes
+// the sum independent of scheduling.
+constexpr int kMaxLossPartials = 1 << 16;
+constexpr size_t kWorkspaceHeader = 64;
+constexpr size_t kWorkspaceBytes = kWorkspaceHeader + sizeof(double) * (size_t)kMaxLossPartials;
+
+struct LossSink {
+  unsigned int* ticket;   // device; zero between calls
+  double* partials;       // device; [kMaxLossPartials]
+  double* loss_acc;       // device; += scale * total
+  double scale;
+};
+
+inline LossSink make_sink(void* workspace, double* loss_acc, double scale) {
+  return LossSink{(unsigned int*)workspace, (double*)((char*)workspace + kWorkspaceHeader), loss_acc, scale};
+}
+
+// Sets n 32-bit words to zero with a small kernel (defined in szo_kernels.hip).
+int zero_words(void* p, int n, hipStream_t stream);
+
+// Wave-wide sum in a fixed order (64 lanes), result valid in every lane.
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+// Called by every thread of every workgroup exactly once, with the thread's partial sum.
+// `scratch` is LDS for one double per wave.  Grid is 1-D or flattened to `block_linear` of
+// `nblocks`.
+__device__ __forceinline__ void block_loss_commit(double local, double* scratch, const LossSink& sink,
+                                                  unsigned int block_linear, unsigned int nblocks) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = (blockDim.x + 63) >> 6;
+  const double w = wave_sum(local);
+  if (lane == 0) scratch[wave] = w;
+  __syncthreads();
+  __shared__ unsigned int s_last;
+  if (threadIdx.x == 0) {
+    double b = 0.0;
+    for (int i = 0; i < nwaves; ++i) b += scratch[i];
+    __hip_atomic_store(&sink.partials[block_linear], b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __threadfence();
+    const unsigned int t = __hip_atomic_fetch_add(sink.ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    s_last = (t == nblocks - 1u);
+  }
+  __syncthreads();
+  if (s_last && wave == 0) {
+    __threadfence();
+    double acc = 0.0;
+    for (unsigned int i = lane; i < nblocks; i += 64)
+      acc += __hip_atomic_load(&sink.partials[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    acc = wave_sum(acc);
+    if (lane == 0) {
+      *sink.loss_acc += sink.scale * acc;
+      __hip_atomic_store(sink.ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+}
+
+}  // namespace szo

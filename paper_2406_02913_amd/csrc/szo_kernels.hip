@@ -1,0 +1,164 @@
+// Small kernels of the step: the Gaussian inspection kernel, the stand-in MSE loss, the SPSA
+// scalar (Definition 1) and the sparse ZO-SGD update (Section 3.4, fixed-parameter update rule).
+#include "szo_internal.h"
+#include "szo_rng.cuh"
+
+namespace szo {
+
+thread_local int g_last_hip_error = 0;
+
+// ---- inspection: words and Gaussian of entries nnz_base + j ---------------------------------
+__global__ void __launch_bounds__(256) debug_zbar_kernel(uint64_t nnz_base, int64_t nnz, uint64_t seed,
+                                                         uint64_t step, uint32_t* words, float* z) {
+  const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= nnz) return;
+  const uint64_t J = nnz_base + (uint64_t)j;
+  if (words) {
+    const Words4 w = zbar_words(J >> 2, seed, step);
+    words[4 * j + 0] = w.w0; words[4 * j + 1] = w.w1; words[4 * j + 2] = w.w2; words[4 * j + 3] = w.w3;
+  }
+  if (z) {
+    float q[4];
+    zbar_quad(J >> 2, seed, step, q);
+    z[j] = q[J & 3];
+  }
+}
+
+// ---- sparse update: one thread per counter = four consecutive entries ------------------------
+// nnz_base is a multiple of 4, so thread t owns entries 4t..4t+3 and one 16-byte access.
+__global__ void __launch_bounds__(256) sparse_update_kernel(float* __restrict__ sp_val, int64_t nnz,
+                                                            uint64_t nnz_base, uint64_t seed, uint64_t step,
+                                                            const double* __restrict__ g, float lr) {
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t j0 = 4 * t;
+  if (j0 >= nnz) return;
+  const float c = (float)((double)lr * *g);     // lr * g, rounded once
+  float z[4];
+  zbar_quad((nnz_base >> 2) + (uint64_t)t, seed, step, z);
+  if (j0 + 4 <= nnz) {
+    float4 v = *reinterpret_cast<float4*>(sp_val + j0);
+    v.x = fmaf(-c, z[0], v.x);
+    v.y = fmaf(-c, z[1], v.y);
+    v.z = fmaf(-c, z[2], v.z);
+    v.w = fmaf(-c, z[3], v.w);
+    *reinterpret_cast<float4*>(sp_val + j0) = v;
+  } else {
+    for (int i = 0; j0 + i < nnz; ++i) sp_val[j0 + i] = fmaf(-c, z[i], sp_val[j0 + i]);
+  }
+}
+
+// ---- MSE: sum (y - t)^2 in fp64, fixed order ---------------------------------------------------
+constexpr int kMseBlocks = 2048;
+constexpr int kMseThreads = 256;
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+__global__ void __launch_bounds__(kMseThreads) mse_kernel(const float* __restrict__ y,
+                                                          const uint16_t* __restrict__ t, int64_t count,
+                                                          LossSink sink, int vec_ok) {
+  __shared__ double scratch[kMseThreads / 64];
+  double acc = 0.0;
+  const int64_t tid = (int64_t)blockIdx.x * kMseThreads + threadIdx.x;
+  const int64_t nthreads = (int64_t)gridDim.x * kMseThreads;
+  if (vec_ok) {
+    const int64_t n4 = count >> 2;
+    for (int64_t i = tid; i < n4; i += nthreads) {
+      const float4 yv = reinterpret_cast<const float4*>(y)[i];
+      const uint2 tv = reinterpret_cast<const uint2*>(t)[i];
+      const double d0 = (double)yv.x - (double)bf16_bits_to_f32(tv.x & 0xFFFFu);
+      const double d1 = (double)yv.y - (double)bf16_bits_to_f32(tv.x >> 16);
+      const double d2 = (double)yv.z - (double)bf16_bits_to_f32(tv.y & 0xFFFFu);
+      const double d3 = (double)yv.w - (double)bf16_bits_to_f32(tv.y >> 16);
+      acc = fma(d0, d0, acc); acc = fma(d1, d1, acc); acc = fma(d2, d2, acc); acc = fma(d3, d3, acc);
+    }
+    for (int64_t i = (n4 << 2) + tid; i < count; i += nthreads) {
+      const double d = (double)y[i] - (double)bf16_bits_to_f32(t[i]);
+      acc = fma(d, d, acc);
+    }
+  } else {
+    for (int64_t i = tid; i < count; i += nthreads) {
+      const double d = (double)y[i] - (double)bf16_bits_to_f32(t[i]);
+      acc = fma(d, d, acc);
+    }
+  }
+  block_loss_commit(acc, scratch, sink, blockIdx.x, gridDim.x);
+}
+
+__global__ void spsa_g_kernel(const double* lp, const double* lm, float eps, double* g) {
+  *g = (eps == 0.0f) ? 0.0 : (*lp - *lm) / (2.0 * (double)eps);
+}
+
+__global__ void zero_words_kernel(uint32_t* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+
+int zero_words(void* p, int n, hipStream_t stream) {
+  if (n <= 0) return SZO_OK;
+  zero_words_kernel<<<(n + 255) / 256, 256, 0, stream>>>((uint32_t*)p, n);
+  SZO_LAUNCH_CHECK();
+  return SZO_OK;
+}
+
+}  // namespace szo
+
+using namespace szo;
+
+extern "C" {
+
+int szo_last_hip_error(void) { return g_last_hip_error; }
+int szo_version(void) { return 1; }
+size_t szo_workspace_bytes(void) { return kWorkspaceBytes; }
+
+int szo_workspace_init(void* workspace, void* stream) {
+  if (!workspace || ((uintptr_t)workspace & 7)) return SZO_EINVAL;
+  return zero_words(workspace, (int)(kWorkspaceHeader / 4), (hipStream_t)stream);
+}
+
+int szo_debug_zbar(uint64_t nnz_base, int64_t nnz, uint64_t seed, uint64_t step, uint32_t* words_out,
+                   float* z_out, void* stream) {
+  if (nnz < 0) return SZO_EINVAL;
+  if (nnz == 0 || (!words_out && !z_out)) return SZO_OK;
+  const int64_t blocks = (nnz + 255) / 256;
+  if (blocks > 0x7FFFFFFF) return SZO_EUNSUPPORTED;
+  debug_zbar_kernel<<<(unsigned)blocks, 256, 0, (hipStream_t)stream>>>(nnz_base, nnz, seed, step, words_out, z_out);
+  SZO_LAUNCH_CHECK();
+  return SZO_OK;
+}
+
+int szo_sparse_update(float* sp_val, const uint32_t* sp_idx, int64_t nnz, uint64_t nnz_base, uint64_t seed,
+                      uint64_t step, const double* g, float lr, void* stream) {
+  (void)sp_idx;
+  if (nnz < 0 || !g || (nnz_base & 3)) return SZO_EINVAL;
+  if (nnz == 0) return SZO_OK;
+  if (!sp_val || ((uintptr_t)sp_val & 15)) return SZO_EINVAL;
+  const int64_t quads = (nnz + 3) / 4;
+  const int64_t blocks = (quads + 255) / 256;
+  if (blocks > 0x7FFFFFFF) return SZO_EUNSUPPORTED;
+  sparse_update_kernel<<<(unsigned)blocks, 256, 0, (hipStream_t)stream>>>(sp_val, nnz, nnz_base, seed, step, g, lr);
+  SZO_LAUNCH_CHECK();
+  return SZO_OK;
+}
+
+int szo_mse_loss(const float* y, const void* target, int64_t count, double scale, double* loss_acc,
+                 void* workspace, void* stream) {
+  if (count < 0 || !loss_acc || !workspace || ((uintptr_t)workspace & 7)) return SZO_EINVAL;
+  if (count == 0) return SZO_OK;
+  if (!y || !target || ((uintptr_t)y & 3) || ((uintptr_t)target & 1)) return SZO_EINVAL;
+  const int vec_ok = (((uintptr_t)y & 15) == 0) && (((uintptr_t)target & 7) == 0);
+  int64_t blocks = (count / 4 + kMseThreads - 1) / kMseThreads;
+  blocks = blocks < 1 ? 1 : (blocks > kMseBlocks ? kMseBlocks : blocks);
+  mse_kernel<<<(unsigned)blocks, kMseThreads, 0, (hipStream_t)stream>>>(
+      y, (const uint16_t*)target, count, make_sink(workspace, loss_acc, scale), vec_ok);
+  SZO_LAUNCH_CHECK();
+  return SZO_OK;
+}
+
+int szo_spsa_g(const double* loss_plus, const double* loss_minus, float eps, double* g, void* stream) {
+  if (!loss_plus || !loss_minus || !g) return SZO_EINVAL;
+  spsa_g_kernel<<<1, 1, 0, (hipStream_t)stream>>>(loss_plus, loss_minus, eps, g);
+  SZO_LAUNCH_CHECK();
+  return SZO_OK;
+}
+
+}  // extern "C"

@@ -20,24 +20,32 @@ _BLOCK = 1 << 20
 TAG_X, TAG_W, TAG_T = 1, 2, 3
 
 
-def _normal_f32(seed, tag, count, sigma=1.0, threads=None):
-    out = np.empty(count, dtype=np.float32)
+def _threads(threads=None):
+    return threads or min(16, os.cpu_count() or 1)
+
+
+def _fill_blocks(count, fill, threads=None):
     nblk = (count + _BLOCK - 1) // _BLOCK
-
-    def fill(b):
-        lo, hi = b * _BLOCK, min(count, (b + 1) * _BLOCK)
-        rng = np.random.default_rng([int(seed), int(tag), b])
-        rng.standard_normal(hi - lo, dtype=np.float32, out=out[lo:hi])
-
-    threads = threads or min(16, os.cpu_count() or 1)
+    threads = _threads(threads)
     if nblk <= 1 or threads <= 1:
         for b in range(nblk):
             fill(b)
     else:
         with ThreadPoolExecutor(max_workers=threads) as ex:
             list(ex.map(fill, range(nblk)))
-    if sigma != 1.0:
-        out *= np.float32(sigma)
+
+
+def _normal_f32(seed, tag, count, sigma=1.0, threads=None):
+    out = np.empty(count, dtype=np.float32)
+
+    def fill(b):
+        lo, hi = b * _BLOCK, min(count, (b + 1) * _BLOCK)
+        rng = np.random.default_rng([int(seed), int(tag), b])
+        rng.standard_normal(hi - lo, dtype=np.float32, out=out[lo:hi])
+        if sigma != 1.0:
+            out[lo:hi] *= np.float32(sigma)
+
+    _fill_blocks(count, fill, threads)
     return out
 
 
@@ -47,9 +55,21 @@ def to_bf16_bits(v):
     return ((u + (((u >> np.uint32(16)) & np.uint32(1)) + np.uint32(0x7FFF))) >> np.uint32(16)).astype(np.uint16)
 
 
+def _normal_bf16_bits(seed, tag, count, threads=None):
+    out = np.empty(count, dtype=np.uint16)
+
+    def fill(b):
+        lo, hi = b * _BLOCK, min(count, (b + 1) * _BLOCK)
+        rng = np.random.default_rng([int(seed), int(tag), b])
+        out[lo:hi] = to_bf16_bits(rng.standard_normal(hi - lo, dtype=np.float32))
+
+    _fill_blocks(count, fill, threads)
+    return out
+
+
 def activations(seed, M, K):
     """x ~ N(0, 1), bf16 bit patterns [M, K]."""
-    return to_bf16_bits(_normal_f32(seed, TAG_X, M * K)).reshape(M, K)
+    return _normal_bf16_bits(seed, TAG_X, M * K).reshape(M, K)
 
 
 def dense_weight(seed, N, K, sigma=0.02):
@@ -59,7 +79,7 @@ def dense_weight(seed, N, K, sigma=0.02):
 
 def target(seed, M, N):
     """t ~ N(0, 1), bf16 bit patterns [M, N]."""
-    return to_bf16_bits(_normal_f32(seed, TAG_T, M * N)).reshape(M, N)
+    return _normal_bf16_bits(seed, TAG_T, M * N).reshape(M, N)
 
 
 # (name, N = out features, K = in features) of one decoder block's linears.

@@ -30,3 +30,35 @@ def clone(m):
         if hasattr(m, a):
             setattr(c, a, getattr(m, a))
     return c
+
+
+def make_pair(seed, M, N, K, group, density=1e-3, kind="uniform", nnz=None, nnz_base=0, device="cuda"):
+    """The same layer twice: oracle-side (numpy) and device-side (libszo host
+    set-up + torch memory).  Asserts that mask, tile order, codes, scales and
+    sparse values agree bit for bit before anything is computed."""
+    from paper_2406_02913_amd import stack
+    o = make_oracle_matrix(seed, M, N, K, group, density, kind, nnz, nnz_base)
+    d = stack.build_linear(seed, M, N, K, group, density, kind, nnz, nnz_base, device=device, keep_host=True)
+    h = d.host
+    assert np.array_equal(h["flat"], o.flat_sorted.astype(np.uint32))
+    assert np.array_equal(h["tile_ptr"], o.tile_ptr) and np.array_equal(h["sp_idx"], o.sp_idx)
+    assert np.array_equal(h["qweight"], oquant.pack_codes(o.codes))
+    assert np.array_equal(h["scales"].view(np.uint16), o.scales.view(np.uint16))
+    assert np.array_equal(h["sp_val"], o.sp_val)
+    return o, d
+
+
+def rel_fro(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+def sigma_g(mats):
+    """sqrt(sum |grad L on the mask|^2): the natural scale of g = z . grad L."""
+    from oracle import layer
+    tot = 0.0
+    for m in mats:
+        y0 = layer.linear_fwd(m.x_bits, m.codes, m.scales, m.group, m.sp_idx, m.sp_val)
+        tot += float(np.sum(layer.mse_grad_on_mask(m.x_bits, y0, m.target_bits, m.sp_idx, m.codes.shape[1]) ** 2))
+    return float(np.sqrt(tot))

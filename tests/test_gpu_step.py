@@ -1,0 +1,111 @@
+"""GPU parity of whole ZO steps (two forwards, losses, g, update)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import zo as ozo
+from paper_2406_02913_amd import szo
+from helpers import make_pair, clone, sigma_g
+
+pytestmark = pytest.mark.gpu
+
+
+def _gpu_steps(devs, steps, seed, eps, lr, flags, dt=szo.TILE_F16, first=0):
+    ws = szo.new_workspace()
+    scal = torch.zeros(3, dtype=torch.float64, device="cuda")
+    out = []
+    descs = szo.desc_array([d.desc(dt) for d in devs])
+    for s in range(first, first + steps):
+        szo.szo_zo_step(descs, seed, s, eps, lr, scal, ws, flags)
+        out.append(scal.cpu().numpy().copy())
+    return out
+
+
+@pytest.mark.parametrize("flags", [0, szo.STEP_FUSED_LOSS])
+def test_tiny_configuration_ten_steps(flags):
+    # 64 tokens, 256x256, group 32, 66 sensitive entries, eps 1e-3, lr 1e-6, 10 steps
+    o, d = make_pair(1, 64, 256, 256, 32, 1e-3)
+    assert o.sp_idx.size == 66
+    seed, eps, lr = 42, 1e-3, 1e-6
+    got = _gpu_steps([d], 10, seed, eps, lr, flags)
+    om = clone(o)
+    sg = sigma_g([o])
+    for s in range(10):
+        r = ozo.zo_step([om], seed, s, eps, lr)
+        lp, lm, g = got[s]
+        assert abs(lp - r["loss_plus"]) <= 5e-3 * r["loss_plus"]
+        assert abs(lm - r["loss_minus"]) <= 5e-3 * r["loss_minus"]
+        assert abs(g - r["g"]) <= 1e-2 * max(abs(r["g"]), sg), (s, g, r["g"], sg)
+    v = d.sp_val.cpu().numpy()
+    # ten updates of ~1e-8 each on fp32 values of ~1e-2: allow the accumulated update 1% plus two ulps
+    assert np.all(np.abs(v - om.sp_val) <= 1e-2 * np.abs(om.sp_val - o.sp_val) + 2 * np.spacing(np.abs(om.sp_val)))
+    assert np.allclose(v, om.sp_val, rtol=1e-2, atol=0)
+
+
+def test_larger_lr_update_direction_and_size():
+    # with a visible step size the update itself is compared, not just the values
+    o, d = make_pair(2, 96, 256, 320, 64, 5e-3)
+    seed, eps, lr = 7, 1e-3, 1e-2
+    _gpu_steps([d], 1, seed, eps, lr, 0)
+    om = clone(o)
+    r = ozo.zo_step([om], seed, 0, eps, lr)
+    dv_gpu = d.sp_val.cpu().numpy().astype(np.float64) - o.sp_val
+    dv_ref = om.sp_val.astype(np.float64) - o.sp_val
+    sg = sigma_g([o])
+    tol = 1e-2 * max(abs(r["g"]), sg) / max(abs(r["g"]), 1e-300)
+    assert np.linalg.norm(dv_gpu - dv_ref) <= tol * np.linalg.norm(dv_ref) + 1e-9
+
+
+def test_two_matrices_share_one_g_and_distinct_counters():
+    o1, d1 = make_pair(3, 80, 128, 256, 32, 1e-2, nnz_base=0)
+    base2 = (o1.sp_idx.size + 3) // 4 * 4
+    o2, d2 = make_pair(4, 80, 256, 128, 64, 1e-2, nnz_base=base2)
+    seed, eps, lr = 9, 1e-3, 1e-3
+    got = _gpu_steps([d1, d2], 3, seed, eps, lr, szo.STEP_FUSED_LOSS)
+    a, b = clone(o1), clone(o2)
+    sg = sigma_g([o1, o2])
+    for s in range(3):
+        r = ozo.zo_step([a, b], seed, s, eps, lr)
+        assert abs(got[s][2] - r["g"]) <= 1e-2 * max(abs(r["g"]), sg)
+    for om, dd, o in ((a, d1, o1), (b, d2, o2)):
+        dv_gpu = dd.sp_val.cpu().numpy().astype(np.float64) - o.sp_val
+        dv_ref = om.sp_val.astype(np.float64) - o.sp_val
+        assert np.linalg.norm(dv_gpu - dv_ref) <= 3e-2 * np.linalg.norm(dv_ref)
+
+
+def test_eps_zero_is_a_no_op():
+    o, d = make_pair(5, 64, 128, 128, 32, 1e-2)
+    before = d.sp_val.clone()
+    got = _gpu_steps([d], 1, 1, 0.0, 1e-2, 0)
+    assert got[0][2] == 0.0 and got[0][0] == got[0][1]
+    assert torch.equal(before, d.sp_val)
+
+
+def test_steps_are_bit_reproducible_and_resumable():
+    o, da = make_pair(6, 64, 256, 256, 32, 5e-3)
+    _, db = make_pair(6, 64, 256, 256, 32, 5e-3)
+    ga = _gpu_steps([da], 6, 3, 1e-3, 1e-3, szo.STEP_FUSED_LOSS)
+    gb = _gpu_steps([db], 3, 3, 1e-3, 1e-3, szo.STEP_FUSED_LOSS)
+    saved = db.sp_val.cpu()
+    _, dc = make_pair(6, 64, 256, 256, 32, 5e-3)
+    dc.sp_val.copy_(saved)
+    gc = _gpu_steps([dc], 3, 3, 1e-3, 1e-3, szo.STEP_FUSED_LOSS, first=3)
+    assert all(np.array_equal(x, y) for x, y in zip(ga, gb + gc))
+    assert torch.equal(da.sp_val, dc.sp_val)
+
+
+def test_bf16_tile_is_available_and_less_accurate_on_g():
+    # the 8-bit significand cannot hold w + eps*z to the estimator's budget; the fp16 tile can
+    o, d16 = make_pair(1, 64, 256, 256, 32, 1e-3)
+    _, dbf = make_pair(1, 64, 256, 256, 32, 1e-3)
+    sg = sigma_g([o])
+    e16, ebf = [], []
+    for s in range(8):
+        r = ozo.zo_step([clone(o)], 42, s, 1e-3, 0.0)
+        g16 = _gpu_steps([d16], 1, 42, 1e-3, 0.0, 0, szo.TILE_F16, first=s)[0][2]
+        gbf = _gpu_steps([dbf], 1, 42, 1e-3, 0.0, 0, szo.TILE_BF16, first=s)[0][2]
+        e16.append(abs(g16 - r["g"]) / max(abs(r["g"]), sg))
+        ebf.append(abs(gbf - r["g"]) / max(abs(r["g"]), sg))
+    print("g error fp16 tile:", e16, "bf16 tile:", ebf)
+    assert max(e16) <= 1e-2
+    assert np.mean(ebf) > np.mean(e16)
