@@ -44,14 +44,13 @@ extern "C" {
 #define SZO_EUNSUPPORTED (-2)   /* valid but outside what the kernels handle       */
 #define SZO_ELAUNCH      (-3)   /* a HIP runtime call failed                        */
 
-/* Sparse layout constants ("TCSR"): rows are cut into groups of 128, each group
- * into four bands of 32 rows; columns into tiles of 64.
- *   tile(n,k) = ((n/128) * (K/64) + k/64) * 4 + (n%128)/32
- * Entries are ordered by (tile, (n%32)*64 + k%64); tile_ptr[t]..tile_ptr[t+1]
- * is the range of tile t.  The position j of an entry in this order is its
- * entry index: together with nnz_base it selects the entry's Gaussian. */
-#define SZO_TILE_ROWS   32
-#define SZO_GROUP_ROWS  128
+/* Sparse layout constants ("TCSR"): rows are cut into bands of 64, columns into
+ * tiles of 64;  tile(n,k) = (n/64) * (K/64) + k/64, so the tiles of one band
+ * follow each other along K.  Entries are ordered by (tile, (n%64)*64 + k%64);
+ * tile_ptr[t]..tile_ptr[t+1] is the range of tile t.  The position j of an
+ * entry in this order is its entry index: together with nnz_base it selects the
+ * entry's Gaussian. */
+#define SZO_TILE_ROWS   64
 #define SZO_TILE_COLS   64
 
 /* 16-bit type the dequantised weight tile and the activations are staged in
@@ -133,7 +132,7 @@ int szo_workspace_init(void* workspace, void* stream);
 
 /* ---- one-time set-up on the host (no GPU needed; deterministic) ------------------------- */
 
-/* Number of TCSR tiles of an [N,K] matrix: ceil(N/128) * (K/64) * 4.  0 if K % 64 != 0. */
+/* Number of TCSR tiles of an [N,K] matrix: ceil(N/64) * (K/64).  0 if K % 64 != 0. */
 int64_t szo_num_tiles(int64_t N, int64_t K);
 
 /* Synthetic stand-in for the sensitive mask of Definition 3 (the real one needs gradients of
@@ -170,6 +169,11 @@ int szo_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out
  * may be NULL) -- the same device routine the forward and the update use. */
 int szo_debug_zbar(uint64_t nnz_base, int64_t nnz, uint64_t seed, uint64_t step,
                    uint32_t* words_out, float* z_out, void* stream);
+
+/* Tuning/testing hook: which workgroup tile the forward uses.  0 = chosen from the shape
+ * (default), 1 = 128x128 outputs with 4 waves, 2 = 256x256 outputs with 8 waves.  Process-wide,
+ * not thread-safe; results do not depend on it beyond fp32 summation order. */
+int szo_set_tile_config(int config);
 
 /* HIP error code of the most recent SZO_ELAUNCH on this thread (0 if none). */
 int szo_last_hip_error(void);

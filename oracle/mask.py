@@ -14,18 +14,17 @@ Draw d of stream s is Philox-4x32-10 with key = mask seed (lo, hi) and
 counter (lo32(d), hi32(d), s, 0); the value is (r0 * 2**32 + r1) mod range.
 Duplicates are dropped in draw order until enough distinct values exist.
 
-Tile order (TCSR): rows are cut into groups of 128, each group into four
-bands of 32 rows; columns into tiles of 64.  tile id =
-((n // 128) * (K // 64) + k // 64) * 4 + (n % 128) // 32.  Entries are sorted
-by (tile id, (n % 32) * 64 + k % 64); tile_ptr is the exclusive prefix sum of
-the per-tile counts.  Position j in this order is the entry index.
+Tile order (TCSR): rows are cut into bands of 64, columns into tiles of 64;
+tile id = (n // 64) * (K // 64) + k // 64, so the tiles of one band follow
+each other along K.  Entries are sorted by (tile id, (n % 64) * 64 + k % 64);
+tile_ptr is the exclusive prefix sum of the per-tile counts.  Position j in
+this order is the entry index.
 """
 import numpy as np
 
 from .philox import philox4x32_10, MASK32
 
-TILE_ROWS = 32      # rows per band
-GROUP_ROWS = 128    # rows per group of four bands
+TILE_ROWS = 64      # rows per band
 TILE_COLS = 64      # columns per tile
 
 
@@ -81,11 +80,11 @@ def mask_heavy_tail(N, K, nnz, mask_seed):
 def tile_id(n, k, K):
     n = np.asarray(n, dtype=np.int64)
     k = np.asarray(k, dtype=np.int64)
-    return ((n // GROUP_ROWS) * (K // TILE_COLS) + k // TILE_COLS) * 4 + (n % GROUP_ROWS) // TILE_ROWS
+    return (n // TILE_ROWS) * (K // TILE_COLS) + k // TILE_COLS
 
 
 def num_tiles(N, K):
-    return (-(-N // GROUP_ROWS)) * (K // TILE_COLS) * 4
+    return (-(-N // TILE_ROWS)) * (K // TILE_COLS)
 
 
 def tcsr_build(N, K, flat_sorted):

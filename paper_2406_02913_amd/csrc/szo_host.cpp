@@ -93,7 +93,7 @@ inline float f16_bits_to_f32(uint16_t h) {
 }
 
 inline int64_t tile_of(int64_t n, int64_t k, int64_t ktiles) {
-  return ((n / SZO_GROUP_ROWS) * ktiles + k / SZO_TILE_COLS) * 4 + (n % SZO_GROUP_ROWS) / SZO_TILE_ROWS;
+  return (n / SZO_TILE_ROWS) * ktiles + k / SZO_TILE_COLS;
 }
 
 template <class F>
@@ -124,7 +124,7 @@ int szo_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out
 
 int64_t szo_num_tiles(int64_t N, int64_t K) {
   if (N < 0 || K < 0 || K % SZO_TILE_COLS) return 0;
-  return ((N + SZO_GROUP_ROWS - 1) / SZO_GROUP_ROWS) * (K / SZO_TILE_COLS) * 4;
+  return ((N + SZO_TILE_ROWS - 1) / SZO_TILE_ROWS) * (K / SZO_TILE_COLS);
 }
 
 int szo_mask_generate(int64_t N, int64_t K, int64_t nnz, int kind, uint64_t mask_seed,
@@ -186,7 +186,7 @@ int szo_tcsr_build(int64_t N, int64_t K, const uint32_t* flat_sorted, int64_t nn
   for (int64_t j = 0; j < nnz; ++j) {
     const int64_t n = flat_sorted[j] / K, k = flat_sorted[j] % K;
     const uint64_t inner = (uint64_t)((n % SZO_TILE_ROWS) * SZO_TILE_COLS + k % SZO_TILE_COLS);
-    keyed[(size_t)j] = ((uint64_t)tile_of(n, k, ktiles) << 11) | inner;   // inner < 2048
+    keyed[(size_t)j] = ((uint64_t)tile_of(n, k, ktiles) << 12) | inner;   // inner < 4096
   }
   std::sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) { return keyed[a] < keyed[b]; });
   std::fill(tile_ptr_out, tile_ptr_out + ntiles + 1, 0u);
@@ -194,7 +194,7 @@ int szo_tcsr_build(int64_t N, int64_t K, const uint32_t* flat_sorted, int64_t nn
     const uint32_t src = order[(size_t)j];
     sp_idx_out[j] = flat_sorted[src];
     if (perm_out) perm_out[j] = src;
-    tile_ptr_out[(keyed[src] >> 11) + 1] += 1u;
+    tile_ptr_out[(keyed[src] >> 12) + 1] += 1u;
   }
   for (int64_t t = 0; t < ntiles; ++t) tile_ptr_out[t + 1] += tile_ptr_out[t];
   return SZO_OK;

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libszo.so")
 
 OK, EINVAL, EUNSUPPORTED, ELAUNCH = 0, -1, -2, -3
 TILE_F16, TILE_BF16 = 0, 1
-TILE_ROWS, GROUP_ROWS, TILE_COLS = 32, 128, 64
+TILE_ROWS, TILE_COLS = 64, 64
 STEP_FUSED_LOSS = 1
 
 if not os.path.exists(LIB_PATH):
@@ -53,6 +53,7 @@ _SIGS = {
                                      C.c_void_p, C.c_void_p, C.c_void_p]),
     "szo_philox4x32_10": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "szo_debug_zbar": (C.c_int, [C.c_uint64, C.c_int64, C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "szo_set_tile_config": (C.c_int, [C.c_int]),
     "szo_last_hip_error": (C.c_int, []),
     "szo_version": (C.c_int, []),
 }
@@ -201,6 +202,10 @@ def szo_philox4x32_10(ctr, key):
 def szo_debug_zbar(nnz_base, nnz, seed, step, words_out=None, z_out=None, stream=None):
     _check("szo_debug_zbar", lib.szo_debug_zbar(nnz_base, nnz, seed, step, _dev(words_out), _dev(z_out),
                                                 _stream(stream)))
+
+
+def szo_set_tile_config(config):
+    _check("szo_set_tile_config", lib.szo_set_tile_config(config))
 
 
 def szo_last_hip_error():

@@ -17,6 +17,7 @@ SHAPES = [
     (4, 1, 128, 128, 128, 5e-2),        # a single token, dense mask
     (5, 257, 130, 192, 32, 0.0),        # k = 0: plain dequantise-then-matmul
     (6, 129, 513, 512, 128, 2e-2),      # one row past a tile boundary in both
+    (7, 70, 192, 4160, 64, 1e-1),       # 65 column tiles (tile_ptr reload) and > 256 entries per tile
 ]
 DTYPES = [(szo.TILE_F16, "f16", 2e-5), (szo.TILE_BF16, "bf16", 2e-5)]
 
@@ -28,9 +29,17 @@ def _run(d, sign, eps, seed, step, dt):
     return d.y.cpu().numpy()
 
 
+@pytest.fixture(autouse=True)
+def _auto_tile_config():
+    yield
+    szo.szo_set_tile_config(0)
+
+
+@pytest.mark.parametrize("tile_cfg", [1, 2])
 @pytest.mark.parametrize("dt,dtname,tol_d", DTYPES)
 @pytest.mark.parametrize("shape", SHAPES)
-def test_forward_matches_oracle(shape, dt, dtname, tol_d):
+def test_forward_matches_oracle(shape, dt, dtname, tol_d, tile_cfg):
+    szo.szo_set_tile_config(tile_cfg)
     s, M, N, K, G, dens = shape
     o, d = make_pair(s, M, N, K, G, dens, nnz_base=8)
     seed, step, eps = 1234, 3, 1e-3
@@ -71,7 +80,9 @@ def test_forward_is_deterministic_and_leaves_inputs_untouched():
     assert torch.equal(before, d.sp_val)
 
 
-def test_fused_loss_equals_separate_loss():
+@pytest.mark.parametrize("tile_cfg", [1, 2])
+def test_fused_loss_equals_separate_loss(tile_cfg):
+    szo.szo_set_tile_config(tile_cfg)
     o, d = make_pair(9, 200, 384, 512, 128, 1e-2)
     ws = szo.new_workspace()
     seed, step, eps = 2, 2, 1e-3

@@ -21,8 +21,16 @@ def _gpu_steps(devs, steps, seed, eps, lr, flags, dt=szo.TILE_F16, first=0):
     return out
 
 
+@pytest.fixture(autouse=True)
+def _auto_tile_config():
+    yield
+    szo.szo_set_tile_config(0)
+
+
+@pytest.mark.parametrize("tile_cfg", [0, 2])
 @pytest.mark.parametrize("flags", [0, szo.STEP_FUSED_LOSS])
-def test_tiny_configuration_ten_steps(flags):
+def test_tiny_configuration_ten_steps(flags, tile_cfg):
+    szo.szo_set_tile_config(tile_cfg)
     # 64 tokens, 256x256, group 32, 66 sensitive entries, eps 1e-3, lr 1e-6, 10 steps
     o, d = make_pair(1, 64, 256, 256, 32, 1e-3)
     assert o.sp_idx.size == 66

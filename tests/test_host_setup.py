@@ -56,7 +56,7 @@ def test_heavy_tail_mask_bit_exact(N, K, dens, seed):
     assert np.array_equal(szo.szo_mask_generate(N, K, k, 1, seed), omask.mask_heavy_tail(N, K, k, seed).astype(np.uint32))
 
 
-@pytest.mark.parametrize("N,K,k", [(256, 256, 66), (100, 128, 300), (130, 64, 0), (32, 64, 2048), (1000, 1024, 5000)])
+@pytest.mark.parametrize("N,K,k", [(256, 256, 66), (100, 128, 300), (130, 64, 0), (64, 64, 4096), (1000, 1024, 5000)])
 def test_tcsr_bit_exact(N, K, k):
     flat = omask.mask_uniform(N, K, k, 21)
     tp, idx, perm = szo.szo_tcsr_build(N, K, flat)

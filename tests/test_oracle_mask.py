@@ -63,7 +63,7 @@ def test_uniform_mask_is_roughly_uniform():
         assert np.all(np.abs(c - c.mean()) < 5 * np.sqrt(c.mean()))
 
 
-@pytest.mark.parametrize("N,K,k", [(256, 256, 66), (100, 128, 300), (130, 64, 0), (32, 64, 2048)])
+@pytest.mark.parametrize("N,K,k", [(256, 256, 66), (100, 128, 300), (130, 64, 0), (64, 64, 4096), (70, 192, 999)])
 def test_tcsr_invariants_and_bruteforce(N, K, k):
     f = mask.mask_uniform(N, K, k, 21)
     tp, idx, perm = mask.tcsr_build(N, K, f)
@@ -76,8 +76,8 @@ def test_tcsr_invariants_and_bruteforce(N, K, k):
     ents = []
     for v in f.tolist():
         n, kk = divmod(v, K)
-        t = ((n // 128) * (K // 64) + kk // 64) * 4 + (n % 128) // 32
-        ents.append((t, (n % 32) * 64 + kk % 64, v))
+        t = (n // 64) * (K // 64) + kk // 64
+        ents.append((t, (n % 64) * 64 + kk % 64, v))
     ents.sort()
     assert [e[2] for e in ents] == idx.tolist()
     for t in range(nt):
@@ -85,13 +85,11 @@ def test_tcsr_invariants_and_bruteforce(N, K, k):
             assert ents[j][0] == t
 
 
-def test_tcsr_neighbouring_bands_and_k_tiles_are_contiguous():
-    # the four 32-row bands of a 128-row group at one column tile are
-    # consecutive tile ids; the next column tile follows directly
+def test_tcsr_tiles_of_a_band_are_contiguous_along_k():
     K = 256
-    assert mask.tile_id(0, 0, K) == 0 and mask.tile_id(32, 0, K) == 1
-    assert mask.tile_id(127, 63, K) == 3 and mask.tile_id(0, 64, K) == 4
-    assert mask.tile_id(128, 0, K) == 4 * (K // 64)
+    assert mask.tile_id(0, 0, K) == 0 and mask.tile_id(63, 63, K) == 0
+    assert mask.tile_id(0, 64, K) == 1 and mask.tile_id(63, 255, K) == 3
+    assert mask.tile_id(64, 0, K) == K // 64
 
 
 def test_tcsr_rejects_duplicates():
