@@ -23,6 +23,7 @@
 // its tile from the window into the weight tile.
 #include "szo_internal.h"
 #include "szo_rng.cuh"
+#include <type_traits>
 
 namespace szo {
 
@@ -55,7 +56,8 @@ struct FwdParams {
   int div_shift;
   uint64_t nnz_base, seed, step;
   float signed_eps;         // sign * eps; 0 = no perturbation
-  LossSink sink;
+  double* partials;         // fused loss: one scaled partial per workgroup, [grid_m*grid_n]
+  double loss_scale;
 };
 
 // floor(v / d) for 32-bit v with a precomputed multiplier (Granlund-Montgomery, round-up form).
@@ -65,9 +67,9 @@ __device__ __forceinline__ uint32_t fast_div(uint32_t v, uint32_t mul, int shift
 }
 
 // Position of column kk (0..63) of tile row r inside the LDS tile, in 16-bit elements.
-// Rows are 64 elements (128 bytes); the eight 16-byte chunks of a row are XOR-swizzled with
-// the row number so that 32 lanes reading the same chunk of 32 consecutive rows spread over
-// all banks.  In f16 mode the eight elements of a chunk are stored in the order
+// Rows are 64 elements (128 bytes), so two rows span the 64 four-byte banks; the eight
+// 16-byte chunks of a row are XOR-swizzled with (row / 2) so that 16 lanes reading the same
+// chunk of 16 consecutive rows touch every bank exactly once.  In f16 mode the eight elements of a chunk are stored in the order
 // 0,4,1,5,2,6,3,7 -- the order in which two nibbles per 16-bit lane fall out of a packed
 // word -- and the activations are stored in the same order, which leaves the dot product
 // unchanged.
@@ -75,61 +77,59 @@ template <int DT>
 __device__ __forceinline__ int lds_pos(int r, int kk) {
   const int chunk = kk >> 3, w = kk & 7;
   const int p = (DT == SZO_TILE_F16) ? (((w & 3) << 1) | (w >> 2)) : w;
-  return r * BK + (((chunk ^ (r & 7)) << 3) | p);
+  return r * BK + (((chunk ^ ((r >> 1) & 7)) << 3) | p);
 }
 
 __device__ __forceinline__ int chunk_off(int r, int chunk) {   // in 16-bit elements
-  return r * BK + ((chunk ^ (r & 7)) << 3);
+  return r * BK + ((chunk ^ ((r >> 1) & 7)) << 3);
 }
 
-// ---- activations: 8 bf16 (one 16-byte chunk) -> 8 tile elements ------------------------------
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// ---- activations: word w (0..3) of the staged form of one 16-byte chunk of 8 bf16 --------------
+// f16 mode pairs elements (0,4) (1,5) (2,6) (3,7); bf16 -> fp32 is a shift and fp32 -> fp16 is
+// exact for |x| in [2^-14, 65504] (8-bit significand).
 template <int DT>
-__device__ __forceinline__ uint4 stage_x_chunk(uint4 u) {
-  if (DT == SZO_TILE_BF16) return u;
-  // bf16 -> fp32 is a shift; fp32 -> fp16 is exact for |x| in [2^-14, 65504] (8-bit significand)
-  auto lo = [](uint32_t v) { return __uint_as_float(v << 16); };
-  auto hi = [](uint32_t v) { return __uint_as_float(v & 0xFFFF0000u); };
-  auto pk = [](float a, float b) {
-    auto h = __builtin_amdgcn_cvt_pkrtz(a, b);
-    return __builtin_bit_cast(uint32_t, h);
-  };
-  uint4 o;
-  o.x = pk(lo(u.x), lo(u.z));   // elements 0,4
-  o.y = pk(hi(u.x), hi(u.z));   // 1,5
-  o.z = pk(lo(u.y), lo(u.w));   // 2,6
-  o.w = pk(hi(u.y), hi(u.w));   // 3,7
-  return o;
+__device__ __forceinline__ uint32_t stage_x_word(u32x4 u, int w) {
+  if (DT == SZO_TILE_BF16) return u[w];
+#ifdef SZO_EXP_NOXCVT
+  return u[w];
+#endif
+  const uint32_t first = (w < 2) ? u[0] : u[1], second = (w < 2) ? u[2] : u[3];
+  float a, b;
+  if ((w & 1) == 0) { a = __uint_as_float(first << 16); b = __uint_as_float(second << 16); }
+  else              { a = __uint_as_float(first & 0xFFFF0000u); b = __uint_as_float(second & 0xFFFF0000u); }
+  auto h = __builtin_amdgcn_cvt_pkrtz(a, b);
+  return __builtin_bit_cast(uint32_t, h);
 }
 
-// ---- weights: 8 codes (one 32-bit word) -> 8 tile elements ------------------------------------
-// dq = (code - 8) * scale, one rounding to the tile type.
+// ---- weights: word w (0..3) of the 8 dequantised elements of one 32-bit word of codes ----------
+// dq = (code - 8) * scale, one rounding to the tile type.  f16 mode: a nibble in mantissa bits
+// 0..3 under exponent pattern 0x6400 reads 1024 + code, one in bits 4..7 under 0x5400 reads
+// 64 + code; removing the offset is exact and the product with the fp16 scale is rounded once,
+// which is the rounding of the exact (code-8)*scale.  Output pairs are codes (0,4) (1,5) (2,6) (3,7).
 template <int DT>
-__device__ __forceinline__ uint4 dequant_word(uint32_t q, float scale_f32, half2_t scale_h2) {
-  uint4 o;
+__device__ __forceinline__ uint32_t dequant_out(uint32_t q, int w, float scale_f32, half2_t scale_h2) {
   if (DT == SZO_TILE_F16) {
-    // 0x6400 | c is the fp16 number 1024 + c; subtracting 1032 is exact; the product with the
-    // fp16 scale is rounded once, which is the rounding of the exact (code-8)*scale.
-    const half2_t bias = {(_Float16)1032.0f, (_Float16)1032.0f};
-    auto cvt = [&](uint32_t bits) {
-      half2_t h = __builtin_bit_cast(half2_t, bits);
-      h = (h - bias) * scale_h2;
-      return __builtin_bit_cast(uint32_t, h);
-    };
-    o.x = cvt((q & 0x000F000Fu) | 0x64006400u);          // codes 0,4
-    o.y = cvt(((q >> 4) & 0x000F000Fu) | 0x64006400u);   // 1,5
-    o.z = cvt(((q >> 8) & 0x000F000Fu) | 0x64006400u);   // 2,6
-    o.w = cvt(((q >> 12) & 0x000F000Fu) | 0x64006400u);  // 3,7
+    const uint32_t src = (w < 2) ? q : (q >> 8);
+    half2_t h;
+    if ((w & 1) == 0) {
+      h = __builtin_bit_cast(half2_t, (src & 0x000F000Fu) | 0x64006400u);
+      const half2_t off = {(_Float16)1032.0f, (_Float16)1032.0f};
+      h = (h - off) * scale_h2;
+    } else {
+      h = __builtin_bit_cast(half2_t, (src & 0x00F000F0u) | 0x54005400u);
+      const half2_t off = {(_Float16)72.0f, (_Float16)72.0f};
+      h = (h - off) * scale_h2;
+    }
+    return __builtin_bit_cast(uint32_t, h);
   } else {
     const float m8s = -8.0f * scale_f32;
-    auto one = [&](int i) { return fmaf((float)((q >> (4 * i)) & 15u), scale_f32, m8s); };   // exact in fp32
-    auto pk = [&](int i) {
-      float2_t f = {one(i), one(i + 1)};
-      bf16x2_t b = __builtin_convertvector(f, bf16x2_t);     // round to nearest even
-      return __builtin_bit_cast(uint32_t, b);
-    };
-    o.x = pk(0); o.y = pk(2); o.z = pk(4); o.w = pk(6);
+    float2_t f = {fmaf((float)((q >> (8 * w)) & 15u), scale_f32, m8s),          // exact in fp32
+                  fmaf((float)((q >> (8 * w + 4)) & 15u), scale_f32, m8s)};
+    bf16x2_t b = __builtin_convertvector(f, bf16x2_t);                            // round to nearest even
+    return __builtin_bit_cast(uint32_t, b);
   }
-  return o;
 }
 
 template <int DT> struct Frag;
@@ -151,6 +151,16 @@ template <> struct Frag<SZO_TILE_BF16> {
 };
 
 // Workgroup = WAVES_M x WAVES_N waves; each wave computes (32*WMB) x (32*WNB) outputs.
+//
+// Schedule of one K step of one wave.  The wave issues SLOTS = 4*WMB*WNB MFMAs.  Its staging
+// work for the NEXT tile (8 units per lane: 16-byte chunks of x, or 32-bit words of codes) is
+// cut into SLOTS slices of three to four VALU instructions, and one slice is issued behind
+// each MFMA, where it executes in the shadow of the matrix pipeline.  The LDS reads of the
+// next k-step's operands are issued the same way, one behind each of the first MFMAs of a
+// k-step, into a second set of operand registers.  A scheduling fence after every slot keeps
+// the compiler from regrouping the slots.  Global loads are in place: as soon as a unit's
+// registers have been consumed they are reloaded with the same unit of the tile after next,
+// which gives every load one full K step (about a microsecond) to arrive.
 template <int WAVES_M, int WAVES_N, int WMB, int WNB, int DT, bool FUSE_LOSS>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdParams p) {
   constexpr int NWAVES = WAVES_M * WAVES_N;
@@ -159,8 +169,13 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdP
   constexpr int X_WAVES = NWAVES - W_WAVES;
   static_assert(BN % 64 == 0 && X_WAVES > 0, "need whole bands and at least one activation wave");
   constexpr int X_ROWS_PER_PASS = 8 * X_WAVES;     // 8 lanes cover one 128-byte row of x
-  constexpr int XCH = BM / X_ROWS_PER_PASS;        // 16-byte chunks per activation lane per tile
-  static_assert(BM % X_ROWS_PER_PASS == 0 && XCH % 4 == 0, "x staging must split over the four MFMA k-steps");
+  static_assert(BM == 8 * X_ROWS_PER_PASS, "every activation lane stages 8 chunks per tile");
+  constexpr int MPK = WMB * WNB;                   // MFMAs per k-step
+  constexpr int SLOTS = 4 * MPK;                   // MFMAs per K step
+  static_assert(SLOTS % 8 == 0 && SLOTS <= 32, "8 staging units must spread evenly over the slots");
+  constexpr int SPU = SLOTS / 8;                   // slots per staging unit: 1, 2 or 4
+  constexpr int WPS = 4 / SPU;                     // output words produced per slot
+  static_assert(WMB + WNB <= MPK, "operand reads of the next k-step must fit behind this one's MFMAs");
   typedef typename Frag<DT>::type frag_t;
 
   extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
@@ -172,7 +187,20 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdP
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-  const int bm = blockIdx.x / p.grid_n, bn = blockIdx.x - bm * p.grid_n;
+  // Workgroup -> output tile.  Workgroup ids go round-robin over the 8 XCDs, each with its own
+  // L2, so ids with equal (id % 8) are first made consecutive ("logical" id), and logical ids
+  // walk the tile grid in strips of 4 row blocks: the 32 workgroups resident on one XCD then
+  // cover 4 x 8 tiles and share 4 activation strips and 8 weight strips through that L2.
+  int bm, bn;
+  {
+    const int G = p.grid_m * p.grid_n, q = G >> 3, r = G & 7;
+    const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
+    const int L = xcd * q + min(xcd, r) + idx;
+    const int width = 4 * p.grid_n, g = L / width, first_m = 4 * g;
+    const int gsize = min(p.grid_m - first_m, 4), rem = L - g * width;
+    bm = first_m + rem % gsize;
+    bn = rem / gsize;
+  }
   const int m0 = bm * BM, n0 = bn * BN;
   const int nk = p.ktiles;
 
@@ -184,22 +212,36 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdP
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-  // One MFMA k-step (16 of the tile's 64 columns) on LDS buffer `buf`.
-  auto mfma_step = [&](int buf, int ks) {
-    const uint16_t* A = ldsA + buf * BM * BK;
-    const uint16_t* B = ldsB + buf * BN * BK;
+  // Operand t of k-step ks in buffer buf: t < WNB is the B (weight) operand of MFMA column
+  // block t, otherwise the A (activation) operand of row block t - WNB.  B operands come first
+  // because the first MFMAs of a k-step need all of them but only the first A operand.
+  const int fragA_row = wm * 32 * WMB + (lane & 31), fragB_row = wn * 32 * WNB + (lane & 31);
+  auto read_operand = [&](int buf, int ks, int t) -> frag_t {
     const int chunk = 2 * ks + (lane >> 5);
-    frag_t a[WMB], b[WNB];
+    if (t < WNB) return *reinterpret_cast<const frag_t*>(ldsB + buf * BN * BK + chunk_off(fragB_row + 32 * t, chunk));
+    return *reinterpret_cast<const frag_t*>(ldsA + buf * BM * BK + chunk_off(fragA_row + 32 * (t - WNB), chunk));
+  };
+
+  // All MFMAs of one K step on buffer buf, with slice(s) issued behind MFMA s.
+  auto run_tile = [&](int buf, auto&& slice) {
+    frag_t op[2][WMB + WNB];
 #pragma unroll
-    for (int i = 0; i < WMB; ++i)
-      a[i] = *reinterpret_cast<const frag_t*>(A + chunk_off(wm * 32 * WMB + i * 32 + (lane & 31), chunk));
+    for (int t = 0; t < WMB + WNB; ++t) op[0][t] = read_operand(buf, 0, t);
 #pragma unroll
-    for (int j = 0; j < WNB; ++j)
-      b[j] = *reinterpret_cast<const frag_t*>(B + chunk_off(wn * 32 * WNB + j * 32 + (lane & 31), chunk));
+    for (int ks = 0; ks < 4; ++ks) {
 #pragma unroll
-    for (int i = 0; i < WMB; ++i)
-#pragma unroll
-      for (int j = 0; j < WNB; ++j) acc[i][j] = Frag<DT>::mfma(a[i], b[j], acc[i][j]);
+      for (int t = 0; t < MPK; ++t) {
+        const int i = t / WNB, j = t % WNB;
+#if !(defined(SZO_EXP) && (SZO_EXP & 2))
+        acc[i][j] = Frag<DT>::mfma(op[ks & 1][WNB + i], op[ks & 1][j], acc[i][j]);
+        if (ks < 3 && t < WMB + WNB) op[(ks + 1) & 1][t] = read_operand(buf, ks + 1, t);
+#endif
+#if !(defined(SZO_EXP) && (SZO_EXP & 4))
+        slice(ks * MPK + t);
+#endif
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
   };
 
   if (wave < W_WAVES) {
@@ -218,37 +260,45 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdP
     float* const wv = winVal + wave * kWindow;
     uint16_t* const wp = winPos + wave * kWindow;
 
-    uint4 qreg[2][2];
-    uint16_t sreg[2][2];
-
-    auto load_w = [&](int kt, int slot) {
-      const int kq = kt * BK + 32 * wh;
+    // Rows past N re-read row N-1 (their outputs are never stored) and column tiles past the
+    // end re-read the last tile (never consumed): the loads stay unconditional and in order.
+    const uint8_t* qrow[2];
+    const uint16_t* srow[2];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int n = n0 + wr + 32 * i;
-        if (n < p.N) {
-          qreg[slot][i] = *reinterpret_cast<const uint4*>(p.qweight + ((size_t)n * p.K + kq) / 2);
-          sreg[slot][i] = p.scales[(size_t)n * (p.K >> p.group_shift) + (kq >> p.group_shift)];
-        } else {
-          qreg[slot][i] = make_uint4(0x88888888u, 0x88888888u, 0x88888888u, 0x88888888u);
-          sreg[slot][i] = 0;
-        }
-      }
+    for (int i = 0; i < 2; ++i) {
+      const int n = min(n0 + wr + 32 * i, p.N - 1);
+      qrow[i] = p.qweight + ((size_t)n * p.K + 32 * wh) / 2;
+      srow[i] = p.scales + (size_t)n * (p.K >> p.group_shift) + ((32 * wh) >> p.group_shift);
+    }
+    u32x4 qreg[2];
+    uint16_t sreg[2];
+    auto load_w = [&](int kt, int i) {
+      const int k0 = min(kt, nk - 1) * BK;
+      qreg[i] = *reinterpret_cast<const u32x4*>(qrow[i] + k0 / 2);
+      sreg[i] = srow[i][k0 >> p.group_shift];
     };
 
-    // part in 0..3: a quarter of the lane's 8 code words
-    auto store_w_part = [&](int buf, int slot, int part) {
-      uint16_t* B = ldsB + buf * BN * BK;
-      const int i = part >> 1;
-      const int r = wr + 32 * i;
-      const _Float16 sh = __builtin_bit_cast(_Float16, sreg[slot][i]);
-      const half2_t sh2 = {sh, sh};
-      const float sf = (float)sh;
-      const uint32_t q0 = (part & 1) ? qreg[slot][i].z : qreg[slot][i].x;
-      const uint32_t q1 = (part & 1) ? qreg[slot][i].w : qreg[slot][i].y;
-      const int c = 2 * (part & 1);
-      *reinterpret_cast<uint4*>(B + chunk_off(r, 4 * wh + c)) = dequant_word<DT>(q0, sf, sh2);
-      *reinterpret_cast<uint4*>(B + chunk_off(r, 4 * wh + c + 1)) = dequant_word<DT>(q1, sf, sh2);
+    // Slice s of staging the registers into buffer dst while reloading them with tile load_kt.
+    // Unit u = s / SPU is code word u%4 of row half u/4; each slot produces WPS of its 4 words.
+    u32x4 outw;
+    auto make_slice = [&](int dst, int load_kt) {
+      return [&, dst, load_kt](int s) {
+        const int u = s / SPU, i = u >> 2, c = u & 3;
+        const _Float16 sh = __builtin_bit_cast(_Float16, sreg[i]);
+        const half2_t sh2 = {sh, sh};
+        const float sf = (float)sh;
+#pragma unroll
+        for (int o = 0; o < WPS; ++o) {
+          const int w = (s % SPU) * WPS + o;
+          outw[w] = dequant_out<DT>(qreg[i][c], w, sf, sh2);
+        }
+        if (s % SPU == SPU - 1) {
+          *reinterpret_cast<u32x4*>(ldsB + dst * BN * BK + chunk_off(wr + 32 * i, 4 * wh + c)) = outw;
+#if !(defined(SZO_EXP) && (SZO_EXP & 1))
+          if (c == 3) load_w(load_kt, i);
+#endif
+        }
+      };
     };
 
     // Computes entries [s, s+256) of the band (s a multiple of 4) into the window.
@@ -292,7 +342,10 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdP
 
     // Adds the sensitive entries of (band, column tile kt) into LDS buffer `buf`.
     auto scatter = [&](int kt, int buf) {
-      if (!band_ok) return;
+#if defined(SZO_EXP) && (SZO_EXP & 8)
+      if (nk > 0) return;
+#endif
+      if (!band_ok || kt >= nk) return;
       if ((kt & 63) == 0) {
         const uint32_t t = tp_base + (uint32_t)kt + 1u + lane;
         tp_reg = (t <= tp_base + (uint32_t)nk) ? p.tile_ptr[t] : band_end;
@@ -316,99 +369,160 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdP
       }
     };
 
-    auto body = [&](int kt, int buf, int slot_next) {
-      // MFMA on tile kt (buffer buf) while tile kt+1 (registers slot_next) goes to buffer buf^1
-      const bool more = kt + 1 < nk;
-      __syncthreads();
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        mfma_step(buf, ks);
-        if (more) store_w_part(buf ^ 1, slot_next, ks);
-      }
-      if (more) scatter(kt + 1, buf ^ 1);
-      if (kt + 3 < nk) load_w(kt + 3, slot_next);
-    };
-
     load_w(0, 0);
-    if (nk > 1) load_w(1, 1);
+    load_w(0, 1);
+    {
+      auto slice = make_slice(0, 1);
 #pragma unroll
-    for (int part = 0; part < 4; ++part) store_w_part(0, 0, part);
+      for (int s = 0; s < SLOTS; ++s) slice(s);
+    }
     scatter(0, 0);
-    if (nk > 2) load_w(2, 0);
     for (int kt = 0; kt < nk; kt += 2) {
-      body(kt, 0, 1);
-      if (kt + 1 < nk) body(kt + 1, 1, 0);
+      __syncthreads();                       // tile kt complete in buffer 0; buffer 1 no longer read
+      run_tile(0, make_slice(1, kt + 2));
+      scatter(kt + 1, 1);
+      if (kt + 1 < nk) {
+        __syncthreads();
+        run_tile(1, make_slice(0, kt + 3));
+        scatter(kt + 2, 0);
+      }
     }
   } else {
     // =============================== activation wave ===========================================
     const int xt = tid - 64 * W_WAVES;
-    const int xc = xt & 7, xr = xt >> 3;                       // chunk, row (plus X_ROWS_PER_PASS*i)
-    uint4 xreg[2][XCH];
-
-    auto load_x = [&](int kt, int slot) {
-      const int k0 = kt * BK;
+    const int xc = xt & 7, xr = xt >> 3;                       // chunk, row (plus X_ROWS_PER_PASS*u)
+    const uint16_t* xrow[8];
 #pragma unroll
-      for (int i = 0; i < XCH; ++i) {
-        const int m = m0 + xr + X_ROWS_PER_PASS * i;
-        xreg[slot][i] = (m < p.M) ? *reinterpret_cast<const uint4*>(p.x + (size_t)m * p.K + k0 + xc * 8)
-                                  : make_uint4(0, 0, 0, 0);
-      }
+    for (int u = 0; u < 8; ++u)
+      xrow[u] = p.x + (size_t)min(m0 + xr + X_ROWS_PER_PASS * u, p.M - 1) * p.K + xc * 8;
+    u32x4 xreg[8];
+    auto load_x = [&](int kt, int u) {
+      xreg[u] = *reinterpret_cast<const u32x4*>(xrow[u] + min(kt, nk - 1) * BK);
     };
-    auto store_x_part = [&](int buf, int slot, int part) {
-      uint16_t* A = ldsA + buf * BM * BK;
+    u32x4 outw;
+    auto make_slice = [&](int dst, int load_kt) {
+      return [&, dst, load_kt](int s) {
+        const int u = s / SPU;
 #pragma unroll
-      for (int i = part * (XCH / 4); i < (part + 1) * (XCH / 4); ++i) {
-        const int r = xr + X_ROWS_PER_PASS * i;
-        *reinterpret_cast<uint4*>(A + chunk_off(r, xc)) = stage_x_chunk<DT>(xreg[slot][i]);
-      }
-    };
-    auto body = [&](int kt, int buf, int slot_next) {
-      const bool more = kt + 1 < nk;
-      __syncthreads();
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        mfma_step(buf, ks);
-        if (more) store_x_part(buf ^ 1, slot_next, ks);
-      }
-      if (kt + 3 < nk) load_x(kt + 3, slot_next);
+        for (int o = 0; o < WPS; ++o) {
+          const int w = (s % SPU) * WPS + o;
+          outw[w] = stage_x_word<DT>(xreg[u], w);
+        }
+        if (s % SPU == SPU - 1) {
+          *reinterpret_cast<u32x4*>(ldsA + dst * BM * BK + chunk_off(xr + X_ROWS_PER_PASS * u, xc)) = outw;
+#if !(defined(SZO_EXP) && (SZO_EXP & 1))
+          load_x(load_kt, u);
+#endif
+        }
+      };
     };
 
-    load_x(0, 0);
-    if (nk > 1) load_x(1, 1);
 #pragma unroll
-    for (int part = 0; part < 4; ++part) store_x_part(0, 0, part);
-    if (nk > 2) load_x(2, 0);
+    for (int u = 0; u < 8; ++u) load_x(0, u);
+    {
+      auto slice = make_slice(0, 1);
+#pragma unroll
+      for (int s = 0; s < SLOTS; ++s) slice(s);
+    }
     for (int kt = 0; kt < nk; kt += 2) {
-      body(kt, 0, 1);
-      if (kt + 1 < nk) body(kt + 1, 1, 0);
+      __syncthreads();
+      run_tile(0, make_slice(1, kt + 2));
+      if (kt + 1 < nk) {
+        __syncthreads();
+        run_tile(1, make_slice(0, kt + 3));
+      }
     }
   }
 
   // ---- epilogue: accumulator (i,j) register r holds
   //      row  32*i + 8*(r/4) + 4*(lane/32) + r%4 ,  column 32*j + lane%32  of the wave tile ----
+  // Fused loss: the bf16 target tile is first copied into the (now idle) LDS tile buffers with
+  // coalesced 16-byte loads, then every lane picks its own elements from LDS.  Differences and
+  // squares are formed in fp32, summed over the 16 registers of one MFMA block in fp32, and
+  // every such partial is added in fp64 (the loss difference of the two passes is ~1e-6 of the
+  // loss, far below fp32 resolution of a long sum).
+  constexpr int TROW = BN * 2 + 32;               // LDS row stride of the target tile in bytes
+  bool staged = false;
+  if (FUSE_LOSS) {
+    staged = ((p.N & 7) == 0) && ((reinterpret_cast<uintptr_t>(p.target) & 15) == 0);
+    if (staged) {
+      constexpr int CPR = BN / 8;                 // 16-byte chunks per tile row
+      constexpr int ROWS_PER_PASS = 64 * NWAVES / CPR;
+      uint8_t* const T = reinterpret_cast<uint8_t*>(lds);
+      const int c = tid % CPR, r0 = tid / CPR;
+      __syncthreads();                            // every wave is done with the tile buffers
+#pragma unroll
+      for (int i = 0; i < BM / ROWS_PER_PASS; ++i) {
+        const int r = r0 + ROWS_PER_PASS * i;
+        const int m = m0 + r, n = n0 + 8 * c;
+        if (m < p.M && n < p.N)
+          *reinterpret_cast<uint4*>(T + r * TROW + 16 * c) =
+              *reinterpret_cast<const uint4*>(p.target + (size_t)m * p.N + n);
+      }
+      __syncthreads();
+    }
+  }
   double loss = 0.0;
+  // Element (i, j, r) of this lane: tile row ml0 + 32 i + 8 (r/4) + r%4, tile column nl0 + 32 j.
+  const int ml0 = wm * 32 * WMB + 4 * (lane >> 5), nl0 = wn * 32 * WNB + (lane & 31);
+  const uint8_t* const trow = reinterpret_cast<const uint8_t*>(lds) + ml0 * TROW + nl0 * 2;
+  // FULL: whole tile inside the matrix (no bounds checks).  STAGED: targets come from LDS.
+  // STORE: y is written.  The three are compile-time so that the common cases are straight code.
+  auto finish = [&](auto full_tag, auto staged_tag, auto store_tag) {
+    constexpr bool FULL = decltype(full_tag)::value, STAGED = decltype(staged_tag)::value,
+                   STORE = decltype(store_tag)::value;
+    const uint32_t ybase = (uint32_t)(m0 + ml0) * (uint32_t)p.N + (uint32_t)(n0 + nl0);   // M*N < 2^32 checked on the host
 #pragma unroll
-  for (int i = 0; i < WMB; ++i) {
+    for (int i = 0; i < WMB; ++i) {
 #pragma unroll
-    for (int j = 0; j < WNB; ++j) {
-      const int n = n0 + wn * 32 * WNB + j * 32 + (lane & 31);
+      for (int j = 0; j < WNB; ++j) {
+        float part = 0.0f;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * 32 * WMB + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (m < p.M && n < p.N) {
-          const float v = acc[i][j][r];
-          if (p.y) p.y[(size_t)m * p.N + n] = v;
-          if (FUSE_LOSS) {
-            const double d = (double)v - (double)__uint_as_float((uint32_t)p.target[(size_t)m * p.N + n] << 16);
-            loss = fma(d, d, loss);
+        for (int r = 0; r < 16; ++r) {
+          const int dm = 32 * i + 8 * (r >> 2) + (r & 3), dn = 32 * j;
+          if (FULL || (m0 + ml0 + dm < p.M && n0 + nl0 + dn < p.N)) {
+            const float v = acc[i][j][r];
+            const uint32_t off = ybase + (uint32_t)dm * (uint32_t)p.N + (uint32_t)dn;
+            if (STORE) p.y[off] = v;
+            if (FUSE_LOSS) {
+              uint32_t tb;
+              if (STAGED) tb = *reinterpret_cast<const uint16_t*>(trow + dm * TROW + dn * 2);
+              else tb = p.target[off];
+              const float d = v - __uint_as_float(tb << 16);
+              part = fmaf(d, d, part);
+            }
           }
         }
+        loss += (double)part;
       }
+    }
+  };
+  {
+    using T = std::true_type;
+    using F = std::false_type;
+    const bool full = m0 + BM <= p.M && n0 + BN <= p.N;
+    if (FUSE_LOSS) {
+      if (full && staged && !p.y) finish(T{}, T{}, F{});            // the step's path
+      else if (staged) { if (p.y) finish(F{}, T{}, T{}); else finish(F{}, T{}, F{}); }
+      else { if (p.y) finish(F{}, F{}, T{}); else finish(F{}, F{}, F{}); }
+    } else {
+      if (full) finish(T{}, F{}, T{});
+      else finish(F{}, F{}, T{});
     }
   }
   if (FUSE_LOSS) {
+    // One scaled partial per workgroup, plain store: a later kernel on the same stream adds them
+    // up in index order, so the kernel boundary is the only synchronisation needed.
     __shared__ double scratch[NWAVES];
-    block_loss_commit(loss, scratch, p.sink, blockIdx.x, gridDim.x);
+    const double w = wave_sum(loss);
+    if (lane == 0) scratch[wave] = w;
+    __syncthreads();
+    if (tid == 0) {
+      double b = 0.0;
+#pragma unroll
+      for (int i = 0; i < NWAVES; ++i) b += scratch[i];
+      p.partials[blockIdx.x] = b * p.loss_scale;
+    }
   }
 }
 
@@ -433,6 +547,7 @@ static int validate_desc(const szo_linear_desc* d, int sign, bool need_y, bool n
   if (d->K % BK) return SZO_EUNSUPPORTED;
   if ((uint64_t)d->N * (uint64_t)d->K > 0xFFFFFFFFull) return SZO_EUNSUPPORTED;
   if (d->M > 0x7FFFFFFF || d->N > 0x7FFFFFFF || d->nnz > 0xFFFFFFFFll) return SZO_EUNSUPPORTED;
+  if ((uint64_t)d->M * (uint64_t)d->N > 0xFFFFFFFFull) return SZO_EUNSUPPORTED;
   if (d->M == 0 || d->N == 0) return SZO_OK;
   if (!d->x || !d->qweight || !d->scales || !d->tile_ptr) return SZO_EINVAL;
   if (d->nnz > 0 && (!d->sp_idx || !d->sp_val)) return SZO_EINVAL;
@@ -452,8 +567,9 @@ static int launch(FwdParams& p, hipStream_t stream) {
   p.grid_n = (p.N + BN - 1) / BN;
   const int64_t blocks = (int64_t)p.grid_m * p.grid_n;
   if (blocks > 0x7FFFFFFF) return SZO_EUNSUPPORTED;
-  if (FUSE && blocks > kMaxLossPartials) return SZO_EUNSUPPORTED;
-  constexpr size_t lds_bytes = 2 * (size_t)(BM + BN) * BK * sizeof(uint16_t) + (size_t)(BN / 64) * kWindow * 6;
+  constexpr size_t main_bytes = 2 * (size_t)(BM + BN) * BK * sizeof(uint16_t) + (size_t)(BN / 64) * kWindow * 6;
+  constexpr size_t target_bytes = FUSE ? (size_t)BM * (BN * 2 + 32) : 0;      // staged target tile of the fused loss
+  constexpr size_t lds_bytes = main_bytes > target_bytes ? main_bytes : target_bytes;
   auto kern = linear_fwd_kernel<WAVES_M, WAVES_N, WMB, WNB, DT, FUSE>;
   static bool attr_set = false;     // per instantiation
   if (!attr_set) {
@@ -465,22 +581,31 @@ static int launch(FwdParams& p, hipStream_t stream) {
   return SZO_OK;
 }
 
-template <int DT, bool FUSE>
-static int dispatch_tile(FwdParams& p, hipStream_t stream) {
+// Which workgroup tile a shape runs with, and how many workgroups (= loss partials) that makes.
+static int plan_tiles(int M, int N, int* blocks_out) {
   int cfg = g_tile_config;
   if (cfg == 0) {
-    const int64_t big_blocks = (int64_t)((p.M + 255) / 256) * ((p.N + 255) / 256);
+    const int64_t big_blocks = (int64_t)((M + 255) / 256) * ((N + 255) / 256);
     cfg = big_blocks >= 192 ? 2 : 1;
   }
-  if (cfg == 2) return launch<2, 4, 4, 2, DT, FUSE>(p, stream);
+  const int t = cfg == 2 ? 256 : 128;
+  const int64_t blocks = (int64_t)((M + t - 1) / t) * ((N + t - 1) / t);
+  *blocks_out = blocks > 0x7FFFFFFF ? -1 : (int)blocks;
+  return cfg;
+}
+
+template <int DT, bool FUSE>
+static int dispatch_tile(FwdParams& p, hipStream_t stream) {
+  int blocks;
+  if (plan_tiles(p.M, p.N, &blocks) == 2) return launch<2, 4, 4, 2, DT, FUSE>(p, stream);
   return launch<2, 2, 2, 2, DT, FUSE>(p, stream);
 }
 
-static int run_forward(const szo_linear_desc* d, uint64_t seed, uint64_t step, int sign, float eps, bool fuse,
-                       double scale, double* loss_acc, void* workspace, hipStream_t stream) {
-  const int rc = validate_desc(d, sign, !fuse, fuse);
-  if (rc != SZO_OK) return rc;
-  if (fuse && (!loss_acc || !workspace || ((uintptr_t)workspace & 7))) return SZO_EINVAL;
+// Enqueues one forward.  With `partials` set the loss is fused: workgroup b stores
+// scale * sum (y - target)^2 of its tile to partials[b].
+static int run_forward(const szo_linear_desc* d, uint64_t seed, uint64_t step, int sign, float eps,
+                       double* partials, double scale, hipStream_t stream) {
+  const bool fuse = partials != nullptr;
   if (d->M == 0 || d->N == 0) return SZO_OK;
   FwdParams p{};
   p.x = (const uint16_t*)d->x;
@@ -506,11 +631,14 @@ static int run_forward(const szo_linear_desc* d, uint64_t seed, uint64_t step, i
   }
   p.nnz_base = d->nnz_base; p.seed = seed; p.step = step;
   p.signed_eps = (float)sign * eps;
-  if (fuse) p.sink = make_sink(workspace, loss_acc, scale);
+  p.partials = partials;
+  p.loss_scale = scale;
   if (d->tile_dtype == SZO_TILE_F16)
     return fuse ? dispatch_tile<SZO_TILE_F16, true>(p, stream) : dispatch_tile<SZO_TILE_F16, false>(p, stream);
   return fuse ? dispatch_tile<SZO_TILE_BF16, true>(p, stream) : dispatch_tile<SZO_TILE_BF16, false>(p, stream);
 }
+
+static double* partial_area(void* workspace) { return (double*)((char*)workspace + kWorkspaceHeader); }
 
 }  // namespace szo
 
@@ -525,44 +653,68 @@ int szo_set_tile_config(int config) {
 }
 
 int szo_linear_fwd(const szo_linear_desc* desc, uint64_t seed, uint64_t step, int sign, float eps, void* stream) {
-  return run_forward(desc, seed, step, sign, eps, false, 0.0, nullptr, nullptr, (hipStream_t)stream);
+  const int rc = validate_desc(desc, sign, true, false);
+  if (rc != SZO_OK) return rc;
+  return run_forward(desc, seed, step, sign, eps, nullptr, 0.0, (hipStream_t)stream);
 }
 
 int szo_linear_fwd_mse(const szo_linear_desc* desc, uint64_t seed, uint64_t step, int sign, float eps,
                        double scale, double* loss_acc, void* workspace, void* stream) {
-  return run_forward(desc, seed, step, sign, eps, true, scale, loss_acc, workspace, (hipStream_t)stream);
+  int rc = validate_desc(desc, sign, false, true);
+  if (rc != SZO_OK) return rc;
+  if (!loss_acc || !workspace || ((uintptr_t)workspace & 7)) return SZO_EINVAL;
+  if (desc->M == 0 || desc->N == 0) return SZO_OK;
+  int blocks;
+  plan_tiles((int)desc->M, (int)desc->N, &blocks);
+  if (blocks < 0 || blocks > kMaxLossPartials) return SZO_EUNSUPPORTED;
+  rc = run_forward(desc, seed, step, sign, eps, partial_area(workspace), scale, (hipStream_t)stream);
+  if (rc != SZO_OK) return rc;
+  return reduce_partials(partial_area(workspace), blocks, loss_acc, (hipStream_t)stream);
 }
 
 int szo_zo_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t step, float eps, float lr,
                 double* scalars, void* workspace, int flags, void* stream) {
-  if (n < 0 || (n > 0 && !descs) || !scalars || !workspace) return SZO_EINVAL;
+  if (n < 0 || (n > 0 && !descs) || !scalars || !workspace || ((uintptr_t)workspace & 7)) return SZO_EINVAL;
   hipStream_t s = (hipStream_t)stream;
   const bool fuse = flags & SZO_STEP_FUSED_LOSS;
+  int64_t total = 0;                // workgroups = loss partials of one pass
   for (int i = 0; i < n; ++i) {     // reject everything before anything is enqueued
     const int rc = validate_desc(&descs[i], 1, !fuse, true);
     if (rc != SZO_OK) return rc;
+    if (descs[i].nnz > 0 && ((uintptr_t)descs[i].sp_val & 15)) return SZO_EINVAL;
+    if (descs[i].M == 0 || descs[i].N == 0) continue;
+    int blocks;
+    plan_tiles((int)descs[i].M, (int)descs[i].N, &blocks);
+    if (blocks < 0) return SZO_EUNSUPPORTED;
+    total += blocks;
   }
-  {
-    const int rc0 = zero_words(scalars, 6, s);      // a fill kernel, not a memset node: safe under graph capture
-    if (rc0 != SZO_OK) return rc0;
+  if (fuse && 2 * total > kMaxLossPartials) return SZO_EUNSUPPORTED;
+  int rc;
+  if (!fuse) {
+    rc = zero_words(scalars, 6, s);      // a fill kernel, not a memset node: safe under graph capture
+    if (rc != SZO_OK) return rc;
   }
   for (int pass = 0; pass < 2; ++pass) {
     const int sign = pass == 0 ? +1 : -1;
+    double* part = partial_area(workspace) + (size_t)pass * (size_t)total;
     for (int i = 0; i < n; ++i) {
       const szo_linear_desc* d = &descs[i];
       if (d->M == 0 || d->N == 0) continue;
       const double scale = 1.0 / ((double)d->M * (double)d->N);
-      int rc;
       if (fuse) {
-        rc = run_forward(d, seed, step, sign, eps, true, scale, scalars + pass, workspace, s);
+        int blocks;
+        plan_tiles((int)d->M, (int)d->N, &blocks);
+        rc = run_forward(d, seed, step, sign, eps, part, scale, s);
+        part += blocks;
       } else {
-        rc = run_forward(d, seed, step, sign, eps, false, 0.0, nullptr, nullptr, s);
+        rc = run_forward(d, seed, step, sign, eps, nullptr, 0.0, s);
         if (rc == SZO_OK) rc = szo_mse_loss(d->y, d->target, d->M * d->N, scale, scalars + pass, workspace, s);
       }
       if (rc != SZO_OK) return rc;
     }
   }
-  int rc = szo_spsa_g(scalars, scalars + 1, eps, scalars + 2, s);
+  rc = fuse ? reduce_step(partial_area(workspace), (int)total, eps, scalars, s)
+            : szo_spsa_g(scalars, scalars + 1, eps, scalars + 2, s);
   if (rc != SZO_OK) return rc;
   for (int i = 0; i < n; ++i) {
     rc = szo_sparse_update(descs[i].sp_val, descs[i].sp_idx, descs[i].nnz, descs[i].nnz_base, seed, step,

@@ -21,7 +21,7 @@ inline int hip_failed(hipError_t e) {
 // Loss workspace: a ticket counter (first 64 bytes) followed by one fp64 partial per
 // workgroup.  The last workgroup to finish adds the partials in index order, which makes
 // the sum independent of scheduling.
-constexpr int kMaxLossPartials = 1 << 16;
+constexpr int kMaxLossPartials = 1 << 20;
 constexpr size_t kWorkspaceHeader = 64;
 constexpr size_t kWorkspaceBytes = kWorkspaceHeader + sizeof(double) * (size_t)kMaxLossPartials;
 
@@ -35,6 +35,11 @@ struct LossSink {
 inline LossSink make_sink(void* workspace, double* loss_acc, double scale) {
   return LossSink{(unsigned int*)workspace, (double*)((char*)workspace + kWorkspaceHeader), loss_acc, scale};
 }
+
+// loss_acc[0] += sum of partials[0..count) in a fixed order (one workgroup).
+int reduce_partials(const double* partials, int count, double* loss_acc, hipStream_t stream);
+// scalars[0] = sum partials[0..count), scalars[1] = sum partials[count..2*count), scalars[2] = SPSA g.
+int reduce_step(const double* partials, int count, float eps, double* scalars, hipStream_t stream);
 
 // Sets n 32-bit words to zero with a small kernel (defined in szo_kernels.hip).
 int zero_words(void* p, int n, hipStream_t stream);

@@ -88,9 +88,55 @@ __global__ void spsa_g_kernel(const double* lp, const double* lm, float eps, dou
   *g = (eps == 0.0f) ? 0.0 : (*lp - *lm) / (2.0 * (double)eps);
 }
 
+// Sum of v[0..count) by one workgroup of 1024 threads: thread t adds elements t, t+1024, ...
+// in order, then the 1024 thread sums are combined by a fixed tree.  Bit-reproducible.
+__device__ __forceinline__ double block_sum_1024(const double* __restrict__ v, int count, double* scratch) {
+  double a = 0.0;
+  for (int i = threadIdx.x; i < count; i += 1024) a += v[i];
+  a = wave_sum(a);
+  if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = a;
+  __syncthreads();
+  double t = 0.0;
+  for (int i = 0; i < 16; ++i) t += scratch[i];
+  __syncthreads();
+  return t;
+}
+
+__global__ void __launch_bounds__(1024) reduce_partials_kernel(const double* __restrict__ partials, int count,
+                                                               double* loss_acc) {
+  __shared__ double scratch[16];
+  const double t = block_sum_1024(partials, count, scratch);
+  if (threadIdx.x == 0) *loss_acc += t;
+}
+
+// The SPSA scalar of Definition 1 from the two passes' partial losses.
+__global__ void __launch_bounds__(1024) reduce_step_kernel(const double* __restrict__ partials, int count, float eps,
+                                                           double* scalars) {
+  __shared__ double scratch[16];
+  const double lp = block_sum_1024(partials, count, scratch);
+  const double lm = block_sum_1024(partials + count, count, scratch);
+  if (threadIdx.x == 0) {
+    scalars[0] = lp;
+    scalars[1] = lm;
+    scalars[2] = (eps == 0.0f) ? 0.0 : (lp - lm) / (2.0 * (double)eps);
+  }
+}
+
 __global__ void zero_words_kernel(uint32_t* p, int n) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = 0u;
+}
+
+int reduce_partials(const double* partials, int count, double* loss_acc, hipStream_t stream) {
+  reduce_partials_kernel<<<1, 1024, 0, stream>>>(partials, count, loss_acc);
+  SZO_LAUNCH_CHECK();
+  return SZO_OK;
+}
+
+int reduce_step(const double* partials, int count, float eps, double* scalars, hipStream_t stream) {
+  reduce_step_kernel<<<1, 1024, 0, stream>>>(partials, count, eps, scalars);
+  SZO_LAUNCH_CHECK();
+  return SZO_OK;
 }
 
 int zero_words(void* p, int n, hipStream_t stream) {

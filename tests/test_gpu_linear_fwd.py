@@ -95,7 +95,9 @@ def test_fused_loss_equals_separate_loss(tile_cfg):
         torch.cuda.synchronize()
         assert np.array_equal(d.y.cpu().numpy(), y)                 # y still written when requested
         a = acc.cpu().numpy()
-        assert abs(a[0] - a[1]) <= 1e-12 * abs(a[0])
+        # the fused epilogue squares in fp32 and adds 16-term fp32 partials in fp64: per-term relative
+        # rounding 2^-24, random in sign, so the sum of ~77k terms agrees to far better than 1e-8
+        assert abs(a[0] - a[1]) <= 1e-8 * abs(a[0])
         assert abs(a[0] - olayer.mse_loss(y.astype(np.float64), o.target_bits)) <= 1e-12 * abs(a[0])
         acc2 = torch.zeros(1, dtype=torch.float64, device="cuda")
         szo.szo_linear_fwd_mse(d.desc(dt, with_y=False), seed, step, -1, eps, 1.0 / (d.M * d.N), acc2, ws)
