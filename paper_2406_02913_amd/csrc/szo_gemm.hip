@@ -34,6 +34,9 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float float2_t __attribute__((ext_vector_type(2)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
+#ifndef SZO_W_PRIO
+#define SZO_W_PRIO 1
+#endif
 constexpr int BK = 64;                 // K extent of one staged tile = SZO_TILE_COLS
 constexpr int kWindow = 256;           // sensitive entries computed per refill of a wave's window
 
@@ -108,17 +111,28 @@ __device__ __forceinline__ uint32_t stage_x_word(u32x4 u, int w) {
 // 0..3 under exponent pattern 0x6400 reads 1024 + code, one in bits 4..7 under 0x5400 reads
 // 64 + code; removing the offset is exact and the product with the fp16 scale is rounded once,
 // which is the rounding of the exact (code-8)*scale.  Output pairs are codes (0,4) (1,5) (2,6) (3,7).
+// (a & mask) | bits in one VALU instruction.  Written out because the compiler splits the
+// expression in two when both constants are literals; `bits` therefore lives in a VGPR.
+__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t bits_vgpr) {
+  uint32_t r;
+  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(mask), "v"(bits_vgpr));
+  return r;
+}
+
+struct DequantConsts { uint32_t magic_lo, magic_hi; };   // 0x64006400 and 0x54005400 held in VGPRs
+
 template <int DT>
-__device__ __forceinline__ uint32_t dequant_out(uint32_t q, int w, float scale_f32, half2_t scale_h2) {
+__device__ __forceinline__ uint32_t dequant_out(uint32_t q, int w, float scale_f32, half2_t scale_h2,
+                                                const DequantConsts& k) {
   if (DT == SZO_TILE_F16) {
     const uint32_t src = (w < 2) ? q : (q >> 8);
     half2_t h;
     if ((w & 1) == 0) {
-      h = __builtin_bit_cast(half2_t, (src & 0x000F000Fu) | 0x64006400u);
+      h = __builtin_bit_cast(half2_t, and_or(src, 0x000F000Fu, k.magic_lo));
       const half2_t off = {(_Float16)1032.0f, (_Float16)1032.0f};
       h = (h - off) * scale_h2;
     } else {
-      h = __builtin_bit_cast(half2_t, (src & 0x00F000F0u) | 0x54005400u);
+      h = __builtin_bit_cast(half2_t, and_or(src, 0x00F000F0u, k.magic_hi));
       const half2_t off = {(_Float16)72.0f, (_Float16)72.0f};
       h = (h - off) * scale_h2;
     }
@@ -173,8 +187,13 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdP
   constexpr int MPK = WMB * WNB;                   // MFMAs per k-step
   constexpr int SLOTS = 4 * MPK;                   // MFMAs per K step
   static_assert(SLOTS % 8 == 0 && SLOTS <= 32, "8 staging units must spread evenly over the slots");
-  constexpr int SPU = SLOTS / 8;                   // slots per staging unit: 1, 2 or 4
+  constexpr int SPU = SLOTS / 8;                   // slots per activation staging unit: 1, 2 or 4
   constexpr int WPS = 4 / SPU;                     // output words produced per slot
+  // Weight waves of the 32-slot schedule finish their dense staging in the first 24 slots (3 per
+  // unit) and spend the last 8 on the sensitive entries of the tile, so that the dependent LDS
+  // round trips of the scatter also run in the shadow of MFMAs instead of after them.
+  constexpr bool SCATTER_IN_SLOTS = (SLOTS == 32);
+  constexpr int DSPU = SCATTER_IN_SLOTS ? 3 : SPU; // slots per weight staging unit
   static_assert(WMB + WNB <= MPK, "operand reads of the next k-step must fit behind this one's MFMAs");
   typedef typename Frag<DT>::type frag_t;
 
@@ -183,6 +202,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdP
   uint16_t* const ldsB = lds + 2 * BM * BK;                     // [2][BN*BK]
   float* const winVal = reinterpret_cast<float*>(lds + 2 * (BM + BN) * BK);        // [W_WAVES][kWindow]
   uint16_t* const winPos = reinterpret_cast<uint16_t*>(winVal + W_WAVES * kWindow);  // [W_WAVES][kWindow]
+  uint16_t* const sink16 = winPos + W_WAVES * kWindow;                              // [W_WAVES][64] write sink of idle lanes
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -204,6 +224,12 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdP
   const int m0 = bm * BM, n0 = bn * BN;
   const int nk = p.ktiles;
 
+#ifdef SZO_TIMELINE
+  unsigned long long* const tl = reinterpret_cast<unsigned long long*>(p.y) + (size_t)wave * 64 * 8;
+#define SZO_STAMP(it, pt) do { if (blockIdx.x == 8 && lane == 0 && (it) < 64) tl[(it) * 8 + (pt)] = __builtin_readcyclecounter(); } while (0)
+#else
+#define SZO_STAMP(it, pt) do {} while (0)
+#endif
   float16_t acc[WMB][WNB];
 #pragma unroll
   for (int i = 0; i < WMB; ++i)
@@ -266,41 +292,36 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdP
     const uint16_t* srow[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
+#if defined(SZO_EXP) && (SZO_EXP & 16)
+      const int n = min(wr + 32 * i, p.N - 1);
+#else
       const int n = min(n0 + wr + 32 * i, p.N - 1);
+#endif
       qrow[i] = p.qweight + ((size_t)n * p.K + 32 * wh) / 2;
       srow[i] = p.scales + (size_t)n * (p.K >> p.group_shift) + ((32 * wh) >> p.group_shift);
     }
     u32x4 qreg[2];
     uint16_t sreg[2];
-    auto load_w = [&](int kt, int i) {
-      const int k0 = min(kt, nk - 1) * BK;
-      qreg[i] = *reinterpret_cast<const u32x4*>(qrow[i] + k0 / 2);
-      sreg[i] = srow[i][k0 >> p.group_shift];
+    DequantConsts dqk;
+    dqk.magic_lo = 0x64006400u; dqk.magic_hi = 0x54005400u;
+    asm volatile("" : "+v"(dqk.magic_lo), "+v"(dqk.magic_hi));   // keep them in registers, not as literals
+    auto load_q = [&](int kt, int i) {
+#if defined(SZO_EXP) && (SZO_EXP & (1 | 256))
+      if (kt > 1) return;
+#endif
+      qreg[i] = *reinterpret_cast<const u32x4*>(qrow[i] + min(kt, nk - 1) * (BK / 2));
     };
+    auto load_s = [&](int kt, int i) {
+#if defined(SZO_EXP) && (SZO_EXP & (1 | 256 | 512))
+      if (kt > 1) return;
+#endif
+      sreg[i] = srow[i][(min(kt, nk - 1) * BK) >> p.group_shift];
+    };
+    auto load_w = [&](int kt, int i) { load_q(kt, i); load_s(kt, i); };
 
     // Slice s of staging the registers into buffer dst while reloading them with tile load_kt.
     // Unit u = s / SPU is code word u%4 of row half u/4; each slot produces WPS of its 4 words.
-    u32x4 outw;
-    auto make_slice = [&](int dst, int load_kt) {
-      return [&, dst, load_kt](int s) {
-        const int u = s / SPU, i = u >> 2, c = u & 3;
-        const _Float16 sh = __builtin_bit_cast(_Float16, sreg[i]);
-        const half2_t sh2 = {sh, sh};
-        const float sf = (float)sh;
-#pragma unroll
-        for (int o = 0; o < WPS; ++o) {
-          const int w = (s % SPU) * WPS + o;
-          outw[w] = dequant_out<DT>(qreg[i][c], w, sf, sh2);
-        }
-        if (s % SPU == SPU - 1) {
-          *reinterpret_cast<u32x4*>(ldsB + dst * BN * BK + chunk_off(wr + 32 * i, 4 * wh + c)) = outw;
-#if !(defined(SZO_EXP) && (SZO_EXP & 1))
-          if (c == 3) load_w(load_kt, i);
-#endif
-        }
-      };
-    };
-
+    // ---- sensitive entries -------------------------------------------------------------------
     // Computes entries [s, s+256) of the band (s a multiple of 4) into the window.
     auto refill = [&](uint32_t s) {
       const uint32_t j = s + 4u * lane;
@@ -340,23 +361,13 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdP
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // window visible to the other lanes of the wave
     };
 
-    // Adds the sensitive entries of (band, column tile kt) into LDS buffer `buf`.
-    auto scatter = [&](int kt, int buf) {
-#if defined(SZO_EXP) && (SZO_EXP & 8)
-      if (nk > 0) return;
-#endif
-      if (!band_ok || kt >= nk) return;
-      if ((kt & 63) == 0) {
-        const uint32_t t = tp_base + (uint32_t)kt + 1u + lane;
-        tp_reg = (t <= tp_base + (uint32_t)nk) ? p.tile_ptr[t] : band_end;
-      }
-      const uint32_t tile_hi = __builtin_amdgcn_readlane(tp_reg, kt & 63);
+    // General path: adds entries [lo, hi) of the band into LDS buffer `buf`, any count.
+    auto scatter_range = [&](uint32_t lo, uint32_t hi_end, int buf) {
       uint16_t* B = ldsB + buf * BN * BK;
-      uint32_t cur = tile_lo;
-      tile_lo = tile_hi;
-      while (cur < tile_hi) {
+      uint32_t cur = lo;
+      while (cur < hi_end) {
         if (cur >= win_hi || cur < win_lo) refill(cur & ~3u);
-        const uint32_t hi = min(tile_hi, win_hi);
+        const uint32_t hi = min(hi_end, win_hi);
         for (uint32_t j = cur + lane; j < hi; j += 64) {
           const uint32_t e = j - win_lo;
           const uint32_t pos = wp[e];
@@ -369,22 +380,158 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdP
       }
     };
 
+    // Per-tile bookkeeping, done before the MFMA loop that stages the tile.  Tiles with at most 64
+    // entries (the normal case) take the in-slot path: sc_cnt entries starting at window offset
+    // sc_e0, one per lane.  Larger tiles are left to scatter_range after the loop.
+    uint32_t sc_cnt = 0, sc_e0 = 0, big_lo = 0, big_hi = 0;
+    auto prepare_scatter = [&](int kt) {
+      sc_cnt = 0; big_lo = 0; big_hi = 0;
+      if (!band_ok || kt >= nk) return;
+      if ((kt & 63) == 0) {
+        const uint32_t t = tp_base + (uint32_t)kt + 1u + lane;
+        tp_reg = (t <= tp_base + (uint32_t)nk) ? p.tile_ptr[t] : band_end;
+        asm volatile("" : "+v"(tp_reg));       // consume the load here, so that no wait on it is needed later
+      }
+      const uint32_t hi = __builtin_amdgcn_readlane(tp_reg, kt & 63), lo = tile_lo;
+      tile_lo = hi;
+      if (hi <= lo) return;
+      if (SCATTER_IN_SLOTS && hi - lo <= 64u) {
+        if (lo < win_lo || hi > win_hi) refill(lo & ~3u);
+        sc_cnt = hi - lo;
+        sc_e0 = lo - win_lo;
+      } else {
+        big_lo = lo; big_hi = hi;
+      }
+    };
+
+    // ---- slices ---------------------------------------------------------------------------------
+    // Dense part: unit u = code word u%4 of row half u/4, DSPU slots per unit.  Words per slot:
+    // 4 | 2,2 | 2,1,1 | 1,1,1,1.  Scatter part (32-slot schedule only): window read, tile read,
+    // add + write, two slots apart; lanes without an entry go through a per-lane sink in LDS so
+    // that the code stays branch-free.
+    // Dense part: unit u = code word u%4 of row half u/4; DSPU slots per unit; the unit's four
+    // output words are spread 4 | 2,2 | 2,1,1 | 1,1,1,1 over them.  In the 32-slot schedule the
+    // three instructions of an output word (and_or, subtract offset, multiply by scale) run in
+    // three consecutive slots, so no slot holds two dependent VALU instructions.
+    // Scatter part (32-slot schedule only): window read, tile read, add + write, three slots
+    // apart; lanes without an entry go through a per-lane sink in LDS, which keeps it branch-free.
+    constexpr int PIPE = SCATTER_IN_SLOTS ? 1 : 0;      // slot distance between the stages of a word
+    u32x4 outw;
+    uint32_t st_a[3][2], st_b[3][2];
+    uint32_t sc_pos = 0xFFFFu;
+    float sc_val = 0.0f, sc_old = 0.0f;
+    uint16_t* sc_addr = nullptr;
+    auto make_slice = [&](int dst, int load_kt) {
+      return [&, dst, load_kt](int s) {
+        // the k-th (0 or 1) output word staged from slot `slot`: unit u, word w; false if none
+        auto item = [](int slot, int k, int& u, int& w) -> bool {
+          if (slot < 0 || slot >= 8 * DSPU) return false;
+          u = slot / DSPU;
+          const int ph = slot % DSPU;
+          const int w0 = (DSPU == 3) ? (ph == 0 ? 0 : ph + 1) : ph * (4 / DSPU);
+          const int nw = (DSPU == 3) ? (ph == 0 ? 2 : 1) : (4 / DSPU);
+          w = w0 + k;
+          return k < nw;
+        };
+        constexpr int KMAX = (DSPU == 1) ? 4 : 2;
+        static_assert(KMAX <= 2 || PIPE == 0, "stage registers hold two words per slot");
+#pragma unroll
+        for (int k = 0; k < KMAX; ++k) {
+          int u = 0, w = 0;
+          if (PIPE == 0) {                              // all three stages at once
+            if (item(s, k, u, w)) {
+              const int i = u >> 2, c = u & 3;
+              const _Float16 sh = __builtin_bit_cast(_Float16, sreg[i]);
+              outw[w] = dequant_out<DT>(qreg[i][c], w, (float)sh, half2_t{sh, sh}, dqk);
+              if (w == 3) {
+                *reinterpret_cast<u32x4*>(ldsB + dst * BN * BK + chunk_off(wr + 32 * i, 4 * wh + c)) = outw;
+                if (c == 3) load_w(load_kt, i);
+              }
+            }
+            continue;
+          }
+          if (item(s, k, u, w)) {                       // stage A: isolate the nibble pair under its exponent
+            const int i = u >> 2, c = u & 3;
+            const uint32_t q = qreg[i][c];
+            if (DT == SZO_TILE_F16)
+              st_a[s % 3][k] = and_or(w < 2 ? q : (q >> 8), (w & 1) ? 0x00F000F0u : 0x000F000Fu,
+                                      (w & 1) ? dqk.magic_hi : dqk.magic_lo);
+            if (w == 3 && c == 3 && DT == SZO_TILE_F16) load_q(load_kt, i);   // codes consumed: reload in place
+          }
+          if (item(s - 1, k, u, w) && DT == SZO_TILE_F16) {   // stage B: remove the exponent's offset (exact)
+            const _Float16 o = (w & 1) ? (_Float16)72.0f : (_Float16)1032.0f;
+            const half2_t h = __builtin_bit_cast(half2_t, st_a[(s - 1) % 3][k]) - half2_t{o, o};
+            st_b[(s - 1) % 3][k] = __builtin_bit_cast(uint32_t, h);
+          }
+          if (item(s - 2, k, u, w)) {                   // stage C: scale, rounded once
+            const int i = u >> 2, c = u & 3;
+            const _Float16 sh = __builtin_bit_cast(_Float16, sreg[i]);
+            if (DT == SZO_TILE_F16) {
+              const half2_t h = __builtin_bit_cast(half2_t, st_b[(s - 2) % 3][k]) * half2_t{sh, sh};
+              outw[w] = __builtin_bit_cast(uint32_t, h);
+            } else {
+              outw[w] = dequant_out<DT>(qreg[i][c], w, (float)sh, half2_t{sh, sh}, dqk);
+            }
+            if (w == 3) {
+#if defined(SZO_EXP) && (SZO_EXP & 32)
+              if (outw[0] == 0x12345678u)
+#endif
+              *reinterpret_cast<u32x4*>(ldsB + dst * BN * BK + chunk_off(wr + 32 * i, 4 * wh + c)) = outw;
+              if (c == 3) {
+                if (DT != SZO_TILE_F16) load_q(load_kt, i);
+                load_s(load_kt, i);
+              }
+            }
+          }
+        }
+        if (SCATTER_IN_SLOTS) {
+          const bool active = (uint32_t)lane < sc_cnt;
+          if (s == 24) {
+            const uint32_t e = active ? sc_e0 + lane : 0u;
+            sc_pos = wp[e];
+            sc_val = wv[e];
+          } else if (s == 27) {                         // every dense word of the tile is written by slot 25
+            const bool ok = active && sc_pos != 0xFFFFu;
+            sc_addr = ok ? ldsB + dst * BN * BK + sc_pos : sink16 + wave * 64 + lane;
+            sc_val = ok ? sc_val : 0.0f;
+            sc_old = Frag<DT>::load(sc_addr);
+          } else if (s == 30) {
+            Frag<DT>::store(sc_addr, sc_old + sc_val);
+          }
+        }
+      };
+    };
+
+    // Weight waves carry more staging instructions per MFMA slot than activation waves; a higher
+    // issue priority lets the two waves of a SIMD finish their K step together.
+    __builtin_amdgcn_s_setprio(SZO_W_PRIO);
     load_w(0, 0);
     load_w(0, 1);
+    prepare_scatter(0);
     {
       auto slice = make_slice(0, 1);
 #pragma unroll
       for (int s = 0; s < SLOTS; ++s) slice(s);
     }
-    scatter(0, 0);
+    if (big_hi > big_lo) scatter_range(big_lo, big_hi, 0);
     for (int kt = 0; kt < nk; kt += 2) {
+      SZO_STAMP(kt, 0);
       __syncthreads();                       // tile kt complete in buffer 0; buffer 1 no longer read
+      SZO_STAMP(kt, 1);
+      prepare_scatter(kt + 1);
       run_tile(0, make_slice(1, kt + 2));
-      scatter(kt + 1, 1);
+      SZO_STAMP(kt, 2);
+      if (big_hi > big_lo) scatter_range(big_lo, big_hi, 1);
+      SZO_STAMP(kt, 3);
       if (kt + 1 < nk) {
+        SZO_STAMP(kt + 1, 0);
         __syncthreads();
+        SZO_STAMP(kt + 1, 1);
+        prepare_scatter(kt + 2);
         run_tile(1, make_slice(0, kt + 3));
-        scatter(kt + 2, 0);
+        SZO_STAMP(kt + 1, 2);
+        if (big_hi > big_lo) scatter_range(big_lo, big_hi, 0);
+        SZO_STAMP(kt + 1, 3);
       }
     }
   } else {
@@ -394,10 +541,18 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdP
     const uint16_t* xrow[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u)
+#if defined(SZO_EXP) && (SZO_EXP & 16)
+      xrow[u] = p.x + (size_t)min(xr + X_ROWS_PER_PASS * u, p.M - 1) * p.K + xc * 8;
+#else
       xrow[u] = p.x + (size_t)min(m0 + xr + X_ROWS_PER_PASS * u, p.M - 1) * p.K + xc * 8;
+#endif
     u32x4 xreg[8];
     auto load_x = [&](int kt, int u) {
+#ifdef SZO_X_NT
+      xreg[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(xrow[u] + min(kt, nk - 1) * BK));
+#else
       xreg[u] = *reinterpret_cast<const u32x4*>(xrow[u] + min(kt, nk - 1) * BK);
+#endif
     };
     u32x4 outw;
     auto make_slice = [&](int dst, int load_kt) {
@@ -409,8 +564,11 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdP
           outw[w] = stage_x_word<DT>(xreg[u], w);
         }
         if (s % SPU == SPU - 1) {
+#if defined(SZO_EXP) && (SZO_EXP & 32)
+          if (outw[0] == 0x12345678u)
+#endif
           *reinterpret_cast<u32x4*>(ldsA + dst * BM * BK + chunk_off(xr + X_ROWS_PER_PASS * u, xc)) = outw;
-#if !(defined(SZO_EXP) && (SZO_EXP & 1))
+#if !(defined(SZO_EXP) && (SZO_EXP & (1 | 128)))
           load_x(load_kt, u);
 #endif
         }
@@ -425,11 +583,17 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdP
       for (int s = 0; s < SLOTS; ++s) slice(s);
     }
     for (int kt = 0; kt < nk; kt += 2) {
+      SZO_STAMP(kt, 0);
       __syncthreads();
+      SZO_STAMP(kt, 1);
       run_tile(0, make_slice(1, kt + 2));
+      SZO_STAMP(kt, 2);
       if (kt + 1 < nk) {
+        SZO_STAMP(kt + 1, 0);
         __syncthreads();
+        SZO_STAMP(kt + 1, 1);
         run_tile(1, make_slice(0, kt + 3));
+        SZO_STAMP(kt + 1, 2);
       }
     }
   }
@@ -483,7 +647,9 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdP
           if (FULL || (m0 + ml0 + dm < p.M && n0 + nl0 + dn < p.N)) {
             const float v = acc[i][j][r];
             const uint32_t off = ybase + (uint32_t)dm * (uint32_t)p.N + (uint32_t)dn;
+#ifndef SZO_TIMELINE
             if (STORE) p.y[off] = v;
+#endif
             if (FUSE_LOSS) {
               uint32_t tb;
               if (STAGED) tb = *reinterpret_cast<const uint16_t*>(trow + dm * TROW + dn * 2);
@@ -567,7 +733,7 @@ static int launch(FwdParams& p, hipStream_t stream) {
   p.grid_n = (p.N + BN - 1) / BN;
   const int64_t blocks = (int64_t)p.grid_m * p.grid_n;
   if (blocks > 0x7FFFFFFF) return SZO_EUNSUPPORTED;
-  constexpr size_t main_bytes = 2 * (size_t)(BM + BN) * BK * sizeof(uint16_t) + (size_t)(BN / 64) * kWindow * 6;
+  constexpr size_t main_bytes = 2 * (size_t)(BM + BN) * BK * sizeof(uint16_t) + (size_t)(BN / 64) * (kWindow * 6 + 128);
   constexpr size_t target_bytes = FUSE ? (size_t)BM * (BN * 2 + 32) : 0;      // staged target tile of the fused loss
   constexpr size_t lds_bytes = main_bytes > target_bytes ? main_bytes : target_bytes;
   auto kern = linear_fwd_kernel<WAVES_M, WAVES_N, WMB, WNB, DT, FUSE>;
