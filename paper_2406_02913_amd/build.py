@@ -9,7 +9,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libszo.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
-HIP_SOURCES = ["szo_kernels.hip", "szo_gemm.hip"]
+HIP_SOURCES = ["szo_kernels.hip", "szo_gemm.hip", "szo_smallm.hip"]
 HOST_SOURCES = ["szo_host.cpp"]
 
 COMMON = ["-O3", "-fPIC", "-std=c++17", "-I", os.path.join(ROOT, "include"), "-I", CSRC]

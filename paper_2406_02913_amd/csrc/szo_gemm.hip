@@ -821,6 +821,10 @@ int szo_set_tile_config(int config) {
 int szo_linear_fwd(const szo_linear_desc* desc, uint64_t seed, uint64_t step, int sign, float eps, void* stream) {
   const int rc = validate_desc(desc, sign, true, false);
   if (rc != SZO_OK) return rc;
+  if (desc->M == 0 || desc->N == 0) return SZO_OK;
+  if (g_tile_config == 0 && small_m_eligible(desc))
+    return small_m_launch_one(desc, seed, step, sign == 0 ? 0.0f : eps, sign == 0 ? 1 : sign, false, nullptr, nullptr,
+                              (hipStream_t)stream);
   return run_forward(desc, seed, step, sign, eps, nullptr, 0.0, (hipStream_t)stream);
 }
 
@@ -830,6 +834,15 @@ int szo_linear_fwd_mse(const szo_linear_desc* desc, uint64_t seed, uint64_t step
   if (rc != SZO_OK) return rc;
   if (!loss_acc || !workspace || ((uintptr_t)workspace & 7)) return SZO_EINVAL;
   if (desc->M == 0 || desc->N == 0) return SZO_OK;
+  if (g_tile_config == 0 && small_m_eligible(desc) && scale == 1.0 / ((double)desc->M * (double)desc->N)) {
+    // the few-token kernel computes both signs at once: make the requested one its "+" forward
+    const int nb = small_m_blocks(desc);
+    if (2 * nb > kMaxLossPartials) return SZO_EUNSUPPORTED;
+    rc = small_m_launch_one(desc, seed, step, (float)sign * eps, 1, true, partial_area(workspace),
+                            partial_area(workspace) + nb, (hipStream_t)stream);
+    if (rc != SZO_OK) return rc;
+    return reduce_partials(partial_area(workspace), nb, loss_acc, (hipStream_t)stream);
+  }
   int blocks;
   plan_tiles((int)desc->M, (int)desc->N, &blocks);
   if (blocks < 0 || blocks > kMaxLossPartials) return SZO_EUNSUPPORTED;
@@ -854,8 +867,16 @@ int szo_zo_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t ste
     if (blocks < 0) return SZO_EUNSUPPORTED;
     total += blocks;
   }
-  if (fuse && 2 * total > kMaxLossPartials) return SZO_EUNSUPPORTED;
   int rc;
+  // Few-token stacks: one pass over the weights serves both forwards of the step.
+  bool few = fuse && g_tile_config == 0 && n > 0 && n <= kMaxStepMatrices;
+  for (int i = 0; few && i < n; ++i) few = small_m_eligible(&descs[i]) && descs[i].M == descs[0].M;
+  if (few) {
+    if (small_m_table_bytes(n) > kTableBytesPerMatrix * (size_t)kMaxStepMatrices) return SZO_EUNSUPPORTED;
+    return small_m_step(descs, n, seed, step, eps, lr, (char*)workspace + kWorkspaceTableOffset,
+                        partial_area(workspace), scalars, true, s);
+  }
+  if (fuse && 2 * total > kMaxLossPartials) return SZO_EUNSUPPORTED;
   if (!fuse) {
     rc = zero_words(scalars, 6, s);      // a fill kernel, not a memset node: safe under graph capture
     if (rc != SZO_OK) return rc;

@@ -23,7 +23,10 @@ inline int hip_failed(hipError_t e) {
 // the sum independent of scheduling.
 constexpr int kMaxLossPartials = 1 << 20;
 constexpr size_t kWorkspaceHeader = 64;
-constexpr size_t kWorkspaceBytes = kWorkspaceHeader + sizeof(double) * (size_t)kMaxLossPartials;
+constexpr int kMaxStepMatrices = 4096;            // descriptor table of the few-token step
+constexpr size_t kTableBytesPerMatrix = 128;
+constexpr size_t kWorkspaceTableOffset = kWorkspaceHeader + sizeof(double) * (size_t)kMaxLossPartials;
+constexpr size_t kWorkspaceBytes = kWorkspaceTableOffset + kTableBytesPerMatrix * (size_t)kMaxStepMatrices;
 
 struct LossSink {
   unsigned int* ticket;   // device; zero between calls
@@ -40,6 +43,15 @@ inline LossSink make_sink(void* workspace, double* loss_acc, double scale) {
 int reduce_partials(const double* partials, int count, double* loss_acc, hipStream_t stream);
 // scalars[0] = sum partials[0..count), scalars[1] = sum partials[count..2*count), scalars[2] = SPSA g.
 int reduce_step(const double* partials, int count, float eps, double* scalars, hipStream_t stream);
+
+// Few-token path (szo_smallm.hip): M <= 16, K % 128 == 0, fp16 tile.
+bool small_m_eligible(const szo_linear_desc* d);
+int small_m_blocks(const szo_linear_desc* d);
+size_t small_m_table_bytes(int n);
+int small_m_launch_one(const szo_linear_desc* d, uint64_t seed, uint64_t step, float eps, int sign, bool loss_mode,
+                       double* partial_plus, double* partial_minus, hipStream_t stream);
+int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t step, float eps, float lr,
+                 void* table_dev, double* partial_plus, double* scalars, bool do_update, hipStream_t stream);
 
 // Sets n 32-bit words to zero with a small kernel (defined in szo_kernels.hip).
 int zero_words(void* p, int n, hipStream_t stream);

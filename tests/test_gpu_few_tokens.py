@@ -1,0 +1,98 @@
+"""GPU parity of the few-token path (M <= 16): dense product once, sparse
+product per sign (the SparseAddMM association of Appendix C.5)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import layer as olayer, philox as ophilox, zo as ozo
+from paper_2406_02913_amd import szo
+from helpers import make_pair, clone, rel_fro, sigma_g
+
+pytestmark = pytest.mark.gpu
+
+# (seed, M, N, K, group, density)
+SHAPES = [
+    (11, 16, 256, 128, 128, 1e-2),      # one strip, one 128-column block
+    (12, 16, 512, 1152, 128, 1e-3),     # crosses the 1024-column chunk boundary
+    (13, 1, 200, 256, 128, 5e-2),       # one token, ragged N, > 256 entries per band and chunk
+    (14, 7, 513, 2048, 128, 2e-3),      # ragged M and N, two chunks
+    (15, 16, 320, 256, 32, 1e-2),       # group 32: scale applied per element
+    (16, 9, 128, 384, 64, 2e-2),        # group 64
+    (17, 16, 256, 256, 128, 0.0),       # k = 0
+    (18, 16, 4096, 4096, 128, 1e-3),    # a full-size attention projection at 16 tokens
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_few_token_forward_matches_oracle(shape):
+    s, M, N, K, G, dens = shape
+    szo.szo_set_tile_config(0)
+    o, d = make_pair(s, M, N, K, G, dens, nnz_base=12)
+    seed, step, eps = 77, 5, 1e-3
+    z = ophilox.zbar(seed, step, 12, o.sp_idx.size)
+    tol = 2e-5 if G == 128 else 1e-3          # group 128 keeps (code-8) exact and scales in fp32
+    for sign in (+1, -1, 0):
+        d.y.fill_(float("nan"))
+        szo.szo_linear_fwd(d.desc(), seed, step, sign, eps)
+        torch.cuda.synchronize()
+        y = d.y.cpu().numpy()
+        assert np.isfinite(y).all()
+        yE = olayer.linear_fwd(o.x_bits, o.codes, o.scales, G, o.sp_idx, o.sp_val, z, sign, eps, "E")
+        assert rel_fro(y, yE) <= tol, (sign, rel_fro(y, yE))
+
+
+def test_few_token_path_agrees_with_the_tiled_kernel():
+    o, d = make_pair(21, 16, 384, 512, 128, 1e-2)
+    szo.szo_set_tile_config(0)
+    szo.szo_linear_fwd(d.desc(), 3, 1, -1, 1e-3)
+    a = d.y.cpu().numpy().copy()
+    szo.szo_set_tile_config(1)
+    szo.szo_linear_fwd(d.desc(), 3, 1, -1, 1e-3)
+    b = d.y.cpu().numpy().copy()
+    szo.szo_set_tile_config(0)
+    assert rel_fro(a, b) < 1e-3 and not np.array_equal(a, b)      # two different kernels, same answer
+
+
+def test_few_token_fused_loss_and_step():
+    szo.szo_set_tile_config(0)
+    o1, d1 = make_pair(31, 16, 512, 1152, 128, 2e-3, nnz_base=0)
+    base2 = (o1.sp_idx.size + 3) // 4 * 4
+    o2, d2 = make_pair(32, 16, 200, 256, 128, 1e-2, nnz_base=base2)
+    ws = szo.new_workspace()
+    # single-matrix fused loss, each sign
+    for sign in (+1, -1):
+        acc = torch.zeros(1, dtype=torch.float64, device="cuda")
+        szo.szo_linear_fwd_mse(d1.desc(with_y=False), 9, 2, sign, 1e-3, 1.0 / (d1.M * d1.N), acc, ws)
+        z = ophilox.zbar(9, 2, 0, o1.sp_idx.size)
+        yE = olayer.linear_fwd(o1.x_bits, o1.codes, o1.scales, 128, o1.sp_idx, o1.sp_val, z, sign, 1e-3, "E")
+        want = olayer.mse_loss(yE, o1.target_bits)
+        assert abs(acc.item() - want) <= 1e-5 * want
+    # whole steps over two matrices
+    scal = torch.zeros(3, dtype=torch.float64, device="cuda")
+    a, b = clone(o1), clone(o2)
+    sg = sigma_g([o1, o2])
+    descs = szo.desc_array([d1.desc(with_y=False), d2.desc(with_y=False)])
+    for s in range(4):
+        szo.szo_zo_step(descs, 5, s, 1e-3, 1e-3, scal, ws, szo.STEP_FUSED_LOSS)
+        lp, lm, g = scal.cpu().numpy()
+        r = ozo.zo_step([a, b], 5, s, 1e-3, 1e-3)
+        assert abs(lp - r["loss_plus"]) <= 1e-5 * r["loss_plus"]
+        assert abs(lm - r["loss_minus"]) <= 1e-5 * r["loss_minus"]
+        assert abs(g - r["g"]) <= 1e-2 * max(abs(r["g"]), sg), (s, g, r["g"], sg)
+    for om, dd, o in ((a, d1, o1), (b, d2, o2)):
+        dv_gpu = dd.sp_val.cpu().numpy().astype(np.float64) - o.sp_val
+        dv_ref = om.sp_val.astype(np.float64) - o.sp_val
+        assert np.linalg.norm(dv_gpu - dv_ref) <= 3e-2 * np.linalg.norm(dv_ref)
+
+
+def test_few_token_step_is_bit_reproducible():
+    szo.szo_set_tile_config(0)
+    outs = []
+    for _ in range(2):
+        _, d = make_pair(41, 16, 512, 1024, 128, 5e-3)
+        ws = szo.new_workspace()
+        scal = torch.zeros(3, dtype=torch.float64, device="cuda")
+        for s in range(3):
+            szo.szo_zo_step([d.desc(with_y=False)], 8, s, 1e-3, 1e-3, scal, ws, szo.STEP_FUSED_LOSS)
+        outs.append((scal.cpu().numpy().copy(), d.sp_val.cpu().numpy().copy()))
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
