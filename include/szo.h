@@ -66,14 +66,26 @@ typedef struct szo_linear_desc {
   int64_t  nnz;            /* number of sensitive entries of this matrix (may be 0)     */
   uint64_t nnz_base;       /* global index of entry 0; multiple of 4                    */
   const void*     x;        /* device, bf16  [M,K]                                      */
-  const uint8_t*  qweight;  /* device, u4x2  [N,K/2]; low nibble = even k; code = q + 8 */
-  const void*     scales;   /* device, fp16  [N,K/group]                                */
+  const uint8_t*  qweight;  /* device, u4x2, banded layout (below), szo_qweight_bytes(N,K) */
+  const void*     scales;   /* device, fp16, banded layout (below), szo_scales_count()     */
   const uint32_t* tile_ptr; /* device, u32   [szo_num_tiles(N,K) + 1]                   */
   const uint32_t* sp_idx;   /* device, u32   [nnz] flat n*K+k in TCSR order             */
   float*          sp_val;   /* device, fp32  [nnz] same order; read-only in forwards    */
   float*          y;        /* device, fp32  [M,N] output (may be NULL in szo_linear_fwd_mse) */
   const void*     target;   /* device, bf16  [M,N]; only read by the loss-fusing calls  */
 } szo_linear_desc;
+
+/* Banded device layout of the frozen quantised part.  The weights are read exactly once per
+ * forward, by waves that each own a band of 64 consecutive rows of W, so codes and scales are
+ * stored band by band, 64-column tile by tile, such that what one wave needs next is contiguous
+ * (whole 128-byte lines instead of one short piece per row).  Rows are padded up to a multiple
+ * of 64 with code 8 (weight zero) and scale 0.  With B = n / 64, r = n % 64, T = k / 64:
+ *   code of (n,k):   byte  ((B * (K/64) + T) * 64 + r) * 32 + (k % 64) / 2,
+ *                    low nibble = even k, high nibble = odd k; code = q + 8
+ *   scale of (n,g):  element  (B * (K/group) + g) * 64 + (r % 16) * 4 + r / 16
+ * (the four rows r, r+16, r+32, r+48 that one lane of a 16-row matrix-core operand serves sit
+ * side by side).  szo_layout_weights() produces both arrays from the row-major ones that
+ * szo_quantize_pack() writes. */
 
 /* ---- hot calls (device work, enqueued on `stream`) ------------------------------------- */
 
@@ -157,6 +169,17 @@ int szo_tcsr_build(int64_t N, int64_t K, const uint32_t* flat_sorted, int64_t nn
  * q_out: host [N,K/2]; scales_out: host fp16 bit patterns [N,K/group]. */
 int szo_quantize_pack(const float* W, int64_t N, int64_t K, int group, const uint32_t* mask_flat,
                       int64_t nnz, uint8_t* q_out, uint16_t* scales_out, float* sp_val_out);
+
+/* Sizes of the banded device arrays: bytes of qweight, elements of scales (0 on bad shapes). */
+size_t szo_qweight_bytes(int64_t N, int64_t K);
+size_t szo_scales_count(int64_t N, int64_t K, int group);
+
+/* Row-major host arrays (q [N,K/2], scales fp16 bits [N,K/group], as written by
+ * szo_quantize_pack) -> banded device layout described above, into host buffers of
+ * szo_qweight_bytes / szo_scales_count elements that the caller then copies to the device.
+ * Pure data movement.  Errors: SZO_EINVAL on null pointers, K % 64 != 0 or K % group != 0. */
+int szo_layout_weights(const uint8_t* q, const uint16_t* scales, int64_t N, int64_t K, int group,
+                       uint8_t* q_banded, uint16_t* scales_banded);
 
 /* ---- inspection ----------------------------------------------------------------------- */
 

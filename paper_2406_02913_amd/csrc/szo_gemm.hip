@@ -34,9 +34,6 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float float2_t __attribute__((ext_vector_type(2)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
-#ifndef SZO_W_PRIO
-#define SZO_W_PRIO 1
-#endif
 constexpr int BK = 64;                 // K extent of one staged tile = SZO_TILE_COLS
 constexpr int kWindow = 256;           // sensitive entries computed per refill of a wave's window
 
@@ -95,9 +92,6 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 template <int DT>
 __device__ __forceinline__ uint32_t stage_x_word(u32x4 u, int w) {
   if (DT == SZO_TILE_BF16) return u[w];
-#ifdef SZO_EXP_NOXCVT
-  return u[w];
-#endif
   const uint32_t first = (w < 2) ? u[0] : u[1], second = (w < 2) ? u[2] : u[3];
   float a, b;
   if ((w & 1) == 0) { a = __uint_as_float(first << 16); b = __uint_as_float(second << 16); }
@@ -224,12 +218,6 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdP
   const int m0 = bm * BM, n0 = bn * BN;
   const int nk = p.ktiles;
 
-#ifdef SZO_TIMELINE
-  unsigned long long* const tl = reinterpret_cast<unsigned long long*>(p.y) + (size_t)wave * 64 * 8;
-#define SZO_STAMP(it, pt) do { if (blockIdx.x == 8 && lane == 0 && (it) < 64) tl[(it) * 8 + (pt)] = __builtin_readcyclecounter(); } while (0)
-#else
-#define SZO_STAMP(it, pt) do {} while (0)
-#endif
   float16_t acc[WMB][WNB];
 #pragma unroll
   for (int i = 0; i < WMB; ++i)
@@ -258,13 +246,9 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdP
 #pragma unroll
       for (int t = 0; t < MPK; ++t) {
         const int i = t / WNB, j = t % WNB;
-#if !(defined(SZO_EXP) && (SZO_EXP & 2))
         acc[i][j] = Frag<DT>::mfma(op[ks & 1][WNB + i], op[ks & 1][j], acc[i][j]);
         if (ks < 3 && t < WMB + WNB) op[(ks + 1) & 1][t] = read_operand(buf, ks + 1, t);
-#endif
-#if !(defined(SZO_EXP) && (SZO_EXP & 4))
         slice(ks * MPK + t);
-#endif
         __builtin_amdgcn_sched_barrier(0);
       }
     }
@@ -286,19 +270,20 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdP
     float* const wv = winVal + wave * kWindow;
     uint16_t* const wp = winPos + wave * kWindow;
 
-    // Rows past N re-read row N-1 (their outputs are never stored) and column tiles past the
-    // end re-read the last tile (never consumed): the loads stay unconditional and in order.
+    // Banded layout: the 64 rows of this wave's band, one 64-column tile, are 2 KB in a row, so a
+    // load instruction of the wave (32 rows x 32 bytes) is contiguous.  Bands past N re-read the
+    // last band (their outputs are never stored) and column tiles past the end re-read the last
+    // tile (never consumed): the loads stay unconditional and in order.
     const uint8_t* qrow[2];
     const uint16_t* srow[2];
+    {
+      const size_t bsafe = (size_t)min(band, p.bands - 1);
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-#if defined(SZO_EXP) && (SZO_EXP & 16)
-      const int n = min(wr + 32 * i, p.N - 1);
-#else
-      const int n = min(n0 + wr + 32 * i, p.N - 1);
-#endif
-      qrow[i] = p.qweight + ((size_t)n * p.K + 32 * wh) / 2;
-      srow[i] = p.scales + (size_t)n * (p.K >> p.group_shift) + ((32 * wh) >> p.group_shift);
+      for (int i = 0; i < 2; ++i) {
+        const int r = (lane >> 1) + 32 * i;                        // row inside the band
+        qrow[i] = p.qweight + (bsafe * (size_t)nk * 64 + (size_t)r) * 32 + 16 * wh;
+        srow[i] = p.scales + bsafe * (size_t)(p.K >> p.group_shift) * 64 + (size_t)((r & 15) * 4 + (r >> 4));
+      }
     }
     u32x4 qreg[2];
     uint16_t sreg[2];
@@ -306,16 +291,10 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdP
     dqk.magic_lo = 0x64006400u; dqk.magic_hi = 0x54005400u;
     asm volatile("" : "+v"(dqk.magic_lo), "+v"(dqk.magic_hi));   // keep them in registers, not as literals
     auto load_q = [&](int kt, int i) {
-#if defined(SZO_EXP) && (SZO_EXP & (1 | 256))
-      if (kt > 1) return;
-#endif
-      qreg[i] = *reinterpret_cast<const u32x4*>(qrow[i] + min(kt, nk - 1) * (BK / 2));
+      qreg[i] = *reinterpret_cast<const u32x4*>(qrow[i] + (size_t)min(kt, nk - 1) * (64 * BK / 2));
     };
     auto load_s = [&](int kt, int i) {
-#if defined(SZO_EXP) && (SZO_EXP & (1 | 256 | 512))
-      if (kt > 1) return;
-#endif
-      sreg[i] = srow[i][(min(kt, nk - 1) * BK) >> p.group_shift];
+      sreg[i] = srow[i][(size_t)((min(kt, nk - 1) * BK + 32 * wh) >> p.group_shift) * 64];
     };
     auto load_w = [&](int kt, int i) { load_q(kt, i); load_s(kt, i); };
 
@@ -473,9 +452,6 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdP
               outw[w] = dequant_out<DT>(qreg[i][c], w, (float)sh, half2_t{sh, sh}, dqk);
             }
             if (w == 3) {
-#if defined(SZO_EXP) && (SZO_EXP & 32)
-              if (outw[0] == 0x12345678u)
-#endif
               *reinterpret_cast<u32x4*>(ldsB + dst * BN * BK + chunk_off(wr + 32 * i, 4 * wh + c)) = outw;
               if (c == 3) {
                 if (DT != SZO_TILE_F16) load_q(load_kt, i);
@@ -504,7 +480,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdP
 
     // Weight waves carry more staging instructions per MFMA slot than activation waves; a higher
     // issue priority lets the two waves of a SIMD finish their K step together.
-    __builtin_amdgcn_s_setprio(SZO_W_PRIO);
+    __builtin_amdgcn_s_setprio(1);
     load_w(0, 0);
     load_w(0, 1);
     prepare_scatter(0);
@@ -515,23 +491,15 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdP
     }
     if (big_hi > big_lo) scatter_range(big_lo, big_hi, 0);
     for (int kt = 0; kt < nk; kt += 2) {
-      SZO_STAMP(kt, 0);
       __syncthreads();                       // tile kt complete in buffer 0; buffer 1 no longer read
-      SZO_STAMP(kt, 1);
       prepare_scatter(kt + 1);
       run_tile(0, make_slice(1, kt + 2));
-      SZO_STAMP(kt, 2);
       if (big_hi > big_lo) scatter_range(big_lo, big_hi, 1);
-      SZO_STAMP(kt, 3);
       if (kt + 1 < nk) {
-        SZO_STAMP(kt + 1, 0);
         __syncthreads();
-        SZO_STAMP(kt + 1, 1);
         prepare_scatter(kt + 2);
         run_tile(1, make_slice(0, kt + 3));
-        SZO_STAMP(kt + 1, 2);
         if (big_hi > big_lo) scatter_range(big_lo, big_hi, 0);
-        SZO_STAMP(kt + 1, 3);
       }
     }
   } else {
@@ -541,18 +509,10 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdP
     const uint16_t* xrow[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u)
-#if defined(SZO_EXP) && (SZO_EXP & 16)
-      xrow[u] = p.x + (size_t)min(xr + X_ROWS_PER_PASS * u, p.M - 1) * p.K + xc * 8;
-#else
       xrow[u] = p.x + (size_t)min(m0 + xr + X_ROWS_PER_PASS * u, p.M - 1) * p.K + xc * 8;
-#endif
     u32x4 xreg[8];
     auto load_x = [&](int kt, int u) {
-#ifdef SZO_X_NT
-      xreg[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(xrow[u] + min(kt, nk - 1) * BK));
-#else
       xreg[u] = *reinterpret_cast<const u32x4*>(xrow[u] + min(kt, nk - 1) * BK);
-#endif
     };
     u32x4 outw;
     auto make_slice = [&](int dst, int load_kt) {
@@ -564,13 +524,8 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdP
           outw[w] = stage_x_word<DT>(xreg[u], w);
         }
         if (s % SPU == SPU - 1) {
-#if defined(SZO_EXP) && (SZO_EXP & 32)
-          if (outw[0] == 0x12345678u)
-#endif
           *reinterpret_cast<u32x4*>(ldsA + dst * BM * BK + chunk_off(xr + X_ROWS_PER_PASS * u, xc)) = outw;
-#if !(defined(SZO_EXP) && (SZO_EXP & (1 | 128)))
           load_x(load_kt, u);
-#endif
         }
       };
     };
@@ -583,17 +538,11 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdP
       for (int s = 0; s < SLOTS; ++s) slice(s);
     }
     for (int kt = 0; kt < nk; kt += 2) {
-      SZO_STAMP(kt, 0);
       __syncthreads();
-      SZO_STAMP(kt, 1);
       run_tile(0, make_slice(1, kt + 2));
-      SZO_STAMP(kt, 2);
       if (kt + 1 < nk) {
-        SZO_STAMP(kt + 1, 0);
         __syncthreads();
-        SZO_STAMP(kt + 1, 1);
         run_tile(1, make_slice(0, kt + 3));
-        SZO_STAMP(kt + 1, 2);
       }
     }
   }
@@ -647,9 +596,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdP
           if (FULL || (m0 + ml0 + dm < p.M && n0 + nl0 + dn < p.N)) {
             const float v = acc[i][j][r];
             const uint32_t off = ybase + (uint32_t)dm * (uint32_t)p.N + (uint32_t)dn;
-#ifndef SZO_TIMELINE
             if (STORE) p.y[off] = v;
-#endif
             if (FUSE_LOSS) {
               uint32_t tb;
               if (STAGED) tb = *reinterpret_cast<const uint16_t*>(trow + dm * TROW + dn * 2);

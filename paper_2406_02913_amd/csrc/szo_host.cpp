@@ -251,4 +251,41 @@ int szo_quantize_pack(const float* W, int64_t N, int64_t K, int group, const uin
   return bad ? SZO_EINVAL : SZO_OK;
 }
 
+size_t szo_qweight_bytes(int64_t N, int64_t K) {
+  if (N <= 0 || K <= 0 || K % 64) return 0;
+  return (size_t)((N + 63) / 64) * 64 * (size_t)(K / 2);
+}
+
+size_t szo_scales_count(int64_t N, int64_t K, int group) {
+  if (N <= 0 || K <= 0 || group <= 0 || K % group) return 0;
+  return (size_t)((N + 63) / 64) * 64 * (size_t)(K / group);
+}
+
+int szo_layout_weights(const uint8_t* q, const uint16_t* scales, int64_t N, int64_t K, int group,
+                       uint8_t* q_banded, uint16_t* scales_banded) {
+  if (!q || !scales || !q_banded || !scales_banded || N <= 0 || K <= 0 || group <= 0) return SZO_EINVAL;
+  if (K % 64 || K % group) return SZO_EINVAL;
+  const int64_t bands = (N + 63) / 64, ktiles = K / 64, groups = K / group;
+  parallel_rows(bands, 64 * K, [&](int64_t lo, int64_t hi) {
+    for (int64_t b = lo; b < hi; ++b) {
+      for (int64_t t = 0; t < ktiles; ++t) {
+        uint8_t* dst = q_banded + (b * ktiles + t) * 64 * 32;
+        for (int64_t r = 0; r < 64; ++r) {
+          const int64_t n = b * 64 + r;
+          if (n < N) std::memcpy(dst + r * 32, q + n * (K / 2) + t * 32, 32);
+          else std::memset(dst + r * 32, 0x88, 32);            // code 8 twice: weight zero
+        }
+      }
+      for (int64_t g = 0; g < groups; ++g) {
+        uint16_t* dst = scales_banded + (b * groups + g) * 64;
+        for (int64_t r = 0; r < 64; ++r) {
+          const int64_t n = b * 64 + r;
+          dst[(r % 16) * 4 + r / 16] = n < N ? scales[n * groups + g] : (uint16_t)0;
+        }
+      }
+    }
+  });
+  return SZO_OK;
+}
+
 }  // extern "C"

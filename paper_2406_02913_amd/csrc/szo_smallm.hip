@@ -4,35 +4,53 @@
 // Two consequences shape this kernel:
 //   * the dense product does not depend on the perturbation, so ONE pass over the weights
 //     serves both the +eps and the -eps forward of a ZO step (Definition 1 needs f at both);
-//   * the sparse product is k << d rank-one column updates, accumulated per 64-row band.
+//   * the sparse weights are  v +- eps z  (Section 3.4), so the sparse product splits into
+//     a = x v^T  (added to the dense part) and  b = x z^T:  y(+-) = dense + a +- eps b.
 //
-// One workgroup = 256 output columns (4 bands, one wave each) x all of K, walked in chunks of
-// 1024 columns of x that are staged in LDS as fp16 (16 token rows, zero padded).  Per chunk a wave
-//   - streams its band's codes, 16 bytes per lane, eight loads in flight, dequantises them in
-//     registers straight into the B operand of v_mfma_f32_16x16x32_f16 (no LDS round trip: every
-//     weight is used once), and adds each 128-column partial product times the group scale;
-//   - regenerates the Gaussians of the band's sensitive entries in the chunk (same routine and
-//     same counters as the large-batch kernel and the update), splits the entries into four lists
-//     by (row mod 4) so that four entries can be accumulated at once without two of them touching
-//     the same row, and adds  (v +- eps z) x[:,k]  into a 64x16 (+,-) accumulator in LDS.
-// The epilogue adds the two parts and either stores y for the requested sign or folds the
-// squared error against the target into two fp64 partials per workgroup (one per sign).
+// One workgroup = 256 output columns (4 bands of 64 rows of W, one wave each) x all of K, walked in
+// chunks of 256 columns of x that are staged in LDS as fp16 (16 token rows, zero padded).  The
+// kernel is written for several small waves per SIMD (~150 registers, ~30 KB of LDS per workgroup):
+// a streaming-read probe on this chip reaches its ceiling with a few 16-byte loads in flight per
+// wave as long as enough waves are resident, and the resident waves hide each other's stalls.
+// Per chunk a wave
+//   - streams its band's codes, 16 bytes per lane, one chunk ahead, and turns them in registers into
+//     the B operand of v_mfma_f32_16x16x32_f16 (no LDS round trip: every weight is used once).
+//     With a quantisation group of 128 the codes are NOT re-centred: 0x6400|c reads 1024+c and
+//     0x5400|(c<<4) reads 64+c, both exact in fp16, and the constant part
+//     sum_k x[m,k] (1032 | 72) of each 128-column block is computed once per workgroup while x is
+//     staged and enters the MFMA chain negated as its initial accumulator.  The block's partial
+//     product then takes the group scale in fp32.
+//   - keeps a ring of its band's sensitive entries in LDS (position, fp16 v, fp16 z; z from the
+//     same Philox/Box-Muller routine and counters as the large-batch kernel and the update, 256
+//     entries per refill so that all lanes work), and multiplies them in groups of 16 entries as a
+//     second, tiny MFMA: A = the entries' columns of x (gathered from LDS), B = a one-hot matrix
+//     that routes entry e to its row (value v or z).  No atomics, no read-modify-write chains.
+// The epilogue forms y(+-) and either stores y for the requested sign or folds the squared error
+// against the target into two fp64 partials per workgroup (one per sign).
 // Everything is accumulated in a fixed order: results are bit-reproducible.
+#include <cstddef>
 #include "szo_internal.h"
 #include "szo_rng.cuh"
 
 namespace szo {
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int SM_ROWS = 16;             // token rows of the MFMA (M padded up to this)
 constexpr int SM_BN = 256;              // output columns per workgroup = 4 bands of 64
-constexpr int SM_KC = 512;              // columns of x staged per chunk (double buffered)
+constexpr int SM_KC = 256;              // columns of x staged per chunk (double buffered) = 2 blocks of 128
 constexpr int SM_XSTRIDE = SM_KC + 8;   // LDS row stride of x in fp16 elements (+16 B against bank conflicts)
-constexpr int SM_WIN = 256;             // sensitive entries computed per window refill
+constexpr int SM_WIN = 256;             // sensitive entries computed per refill (4 per lane)
+constexpr int SM_CAP = 512;             // entries held per band (ring)
+#ifndef SM_MIN_BLOCKS
+#define SM_MIN_BLOCKS 3                 // workgroups per CU the register budget is set for (~150 registers, no spills)
+#endif
 
 struct SmallMat {
   const uint16_t* x;        // bf16 [M,K]
@@ -86,23 +104,27 @@ __device__ __forceinline__ uint32_t sm_and_or(uint32_t a, uint32_t mask, uint32_
   return r;
 }
 
-// 8 codes -> 8 fp16 values (code - 8), optionally times the group scale (PRESCALE), in the order
-// (0,4)(1,5)(2,6)(3,7).  0x6400|c reads 1024+c and 0x5400|(c<<4) reads 64+c; both offsets are exact.
-template <bool PRESCALE>
+// 8 codes -> 8 fp16 values in the order (0,4)(1,5)(2,6)(3,7).
+// RAW: 1024+c for even positions and 64+c for odd ones (the caller removes the constants);
+// otherwise (c - 8) times the group scale.
+template <bool RAW>
 __device__ __forceinline__ half8_t sm_dequant_word(uint32_t q, uint32_t magic_lo, uint32_t magic_hi, half2_t s2) {
-  const half2_t off_lo = {(_Float16)1032.0f, (_Float16)1032.0f}, off_hi = {(_Float16)72.0f, (_Float16)72.0f};
   const uint32_t q8 = q >> 8;
-  half2_t h0 = __builtin_bit_cast(half2_t, sm_and_or(q, 0x000F000Fu, magic_lo)) - off_lo;
-  half2_t h1 = __builtin_bit_cast(half2_t, sm_and_or(q, 0x00F000F0u, magic_hi)) - off_hi;
-  half2_t h2 = __builtin_bit_cast(half2_t, sm_and_or(q8, 0x000F000Fu, magic_lo)) - off_lo;
-  half2_t h3 = __builtin_bit_cast(half2_t, sm_and_or(q8, 0x00F000F0u, magic_hi)) - off_hi;
-  if (PRESCALE) { h0 *= s2; h1 *= s2; h2 *= s2; h3 *= s2; }
+  half2_t h0 = __builtin_bit_cast(half2_t, sm_and_or(q, 0x000F000Fu, magic_lo));
+  half2_t h1 = __builtin_bit_cast(half2_t, sm_and_or(q, 0x00F000F0u, magic_hi));
+  half2_t h2 = __builtin_bit_cast(half2_t, sm_and_or(q8, 0x000F000Fu, magic_lo));
+  half2_t h3 = __builtin_bit_cast(half2_t, sm_and_or(q8, 0x00F000F0u, magic_hi));
+  if (!RAW) {
+    const half2_t off_lo = {(_Float16)1032.0f, (_Float16)1032.0f}, off_hi = {(_Float16)72.0f, (_Float16)72.0f};
+    h0 = (h0 - off_lo) * s2; h1 = (h1 - off_hi) * s2; h2 = (h2 - off_lo) * s2; h3 = (h3 - off_hi) * s2;
+  }
   half8_t r;
   r[0] = h0[0]; r[1] = h0[1]; r[2] = h1[0]; r[3] = h1[1];
   r[4] = h2[0]; r[5] = h2[1]; r[6] = h3[0]; r[7] = h3[1];
   return r;
 }
 
+// word w of the staged form of 8 bf16 values: (x[w], x[w+4]) as fp16
 __device__ __forceinline__ uint32_t sm_stage_x_word(u32x4 u, int w) {
   const uint32_t first = (w < 2) ? u[0] : u[1], second = (w < 2) ? u[2] : u[3];
   float a, b;
@@ -112,35 +134,56 @@ __device__ __forceinline__ uint32_t sm_stage_x_word(u32x4 u, int w) {
   return __builtin_bit_cast(uint32_t, h);
 }
 
-// G128 = quantisation group of 128: one scale per (row, 128-column block), prefetched four at a
-// time and applied to the block's partial product.  Other group sizes take the scale from memory
-// and apply it to every element before the product (a plain, slower path).
-//
-// Pipeline of one wave: the code stream (16-byte loads, 8 in flight per lane) runs ahead across
-// chunk boundaries; x of the next chunk is loaded into registers before the current chunk's work and
-// written to the other LDS buffer after it; the sparse arrays of the current chunk are requested
-// before its dense loop and consumed after it.  One barrier per chunk.
-template <bool G128>
-__global__ void __launch_bounds__(256) small_m_kernel(SmallArgs a) {
+__device__ __forceinline__ float sm_half_sum(uint32_t w) {
+  const half2_t h = __builtin_bit_cast(half2_t, w);
+  return (float)h[0] + (float)h[1];
+}
+
+// FAST = quantisation group of 128: the scales of a block's four subtiles are prefetched with one
+// 8-byte load and applied to each block's partial product, and the codes stay un-centred as
+// described at the top.  Otherwise the scale is read from memory where it is needed
+// and applied to every element before the product (a plain, slower path for the other group sizes).
+template <bool FAST>
+__global__ void __launch_bounds__(256, SM_MIN_BLOCKS) small_m_kernel(SmallArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-  _Float16* const xs = reinterpret_cast<_Float16*>(smem);                              // [2][16][SM_XSTRIDE]
-  float2* const ysp = reinterpret_cast<float2*>(xs + 2 * SM_ROWS * SM_XSTRIDE);          // [4 waves][64 rows][16 m] (+,-)
-  float2* const winv = ysp + 4 * 64 * SM_ROWS;                                           // [4 waves][SM_WIN] (value, eps*z)
-  uint16_t* const winp = reinterpret_cast<uint16_t*>(winv + 4 * SM_WIN);                 // [4 waves][SM_WIN] row<<10 | column in chunk
+  _Float16* const xs = reinterpret_cast<_Float16*>(smem);                        // [2][16][SM_XSTRIDE]
+  float* const corr = reinterpret_cast<float*>(xs + 2 * SM_ROWS * SM_XSTRIDE);     // [2][2 blocks][16 rows], negated
+  uint16_t* const winp = reinterpret_cast<uint16_t*>(corr + 2 * 2 * SM_ROWS);      // [4 bands][SM_CAP] row<<10 | column&1023
+  uint16_t* const winv = winp + 4 * SM_CAP;                                        // fp16 bits of v
+  uint16_t* const winz = winv + 4 * SM_CAP;                                        // fp16 bits of z
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   // ---- which matrix, which 256-column strip ----
-  const SmallMat* mp = &a.one;
+  // The table entry is read through the constant address space (scalar loads: the table is written
+  // before the launch and never during it), so that its fields live in scalar registers like the
+  // kernel arguments do; read through a generic pointer they would occupy ~30 vector registers.
+  SmallMat mt = a.one;
   if (a.table) {
+    constexpr int W = (int)(sizeof(SmallMat) / 4), FB = (int)(offsetof(SmallMat, first_block) / 4);
+    static_assert(sizeof(SmallMat) % 4 == 0 && offsetof(SmallMat, first_block) % 4 == 0, "table entry is read as words");
+    const auto* tab = (const uint32_t __attribute__((address_space(4)))*)a.table;
     int lo = 0, hi = a.n_mats - 1;                          // last matrix whose first_block <= blockIdx.x
     while (lo < hi) {
       const int mid = (lo + hi + 1) >> 1;
-      if (a.table[mid].first_block <= (int)blockIdx.x) lo = mid; else hi = mid - 1;
+      if ((int)tab[mid * W + FB] <= (int)blockIdx.x) lo = mid; else hi = mid - 1;
     }
-    mp = a.table + lo;
+    struct Words { uint32_t w[W]; } raw;
+#pragma unroll
+    for (int i = 0; i < W; ++i) raw.w[i] = tab[lo * W + i];
+    mt = __builtin_bit_cast(SmallMat, raw);
   }
-  const SmallMat mt = *mp;
+  // Pointers read out of a table are generic to the compiler; say that they are global memory, or
+  // every access becomes a flat load with conservative waits on both memory counters.
+#define SZO_GLOBAL(T, p) ((const T __attribute__((address_space(1)))*)(p))
+  const auto g_x = SZO_GLOBAL(uint16_t, mt.x);
+  const auto g_q = SZO_GLOBAL(uint8_t, mt.qweight);
+  const auto g_scales = SZO_GLOBAL(uint16_t, mt.scales);
+  const auto g_tile_ptr = SZO_GLOBAL(uint32_t, mt.tile_ptr);
+  const auto g_sp_idx = SZO_GLOBAL(uint32_t, mt.sp_idx);
+  const auto g_sp_val = SZO_GLOBAL(float, mt.sp_val);
+  const auto g_target = SZO_GLOBAL(uint16_t, mt.target);
+  float __attribute__((address_space(1)))* const g_y = (float __attribute__((address_space(1)))*)mt.y;
   const int strip = blockIdx.x - mt.first_block;
   const int n0 = strip * SM_BN;
   const int N = mt.N, K = mt.K, M = a.M;
@@ -154,200 +197,222 @@ __global__ void __launch_bounds__(256) small_m_kernel(SmallArgs a) {
   uint32_t magic_lo = 0x64006400u, magic_hi = 0x54005400u;
   asm volatile("" : "+v"(magic_lo), "+v"(magic_hi));
 
-  float2* const my_ysp = ysp + wave * 64 * SM_ROWS;
-  float2* const my_winv = winv + wave * SM_WIN;
-  uint16_t* const my_winp = winp + wave * SM_WIN;
-  for (int i = lane; i < 64 * SM_ROWS; i += 64) my_ysp[i] = make_float2(0.0f, 0.0f);
+  uint16_t* const my_winp = winp + wave * SM_CAP;
+  uint16_t* const my_winv = winv + wave * SM_CAP;
+  uint16_t* const my_winz = winz + wave * SM_CAP;
 
-  float4_t acc[4];
+  float4_t acc[4], accz[4];                                 // dense + x v^T ;  x z^T
 #pragma unroll
-  for (int s = 0; s < 4; ++s) acc[s] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
+  for (int s = 0; s < 4; ++s) { acc[s] = float4_t{0.0f, 0.0f, 0.0f, 0.0f}; accz[s] = float4_t{0.0f, 0.0f, 0.0f, 0.0f}; }
 
-  // rows past N re-read row N-1: their outputs are never used
-  const uint8_t* qrow[4];
-  const uint16_t* srow[4];
+  // Banded layout (see the header): the band's 64 rows of one 64-column tile are 2 KB in a row, so
+  // the 16 rows x 32 bytes that the lanes of one k-group pair read are contiguous, and a lane's four
+  // scales of a group (rows nn, nn+16, nn+32, nn+48) are 8 bytes in a row.  Bands past N re-read the
+  // last band: their outputs are never used.  32-bit byte offsets from the uniform base pointers
+  // take half the registers of per-lane pointers.
+  const uint32_t bsafe = (uint32_t)min(band, (N + 63) / 64 - 1);
+  uint32_t qoff[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s)
+    qoff[s] = (bsafe * (uint32_t)ktiles * 64u + (uint32_t)(16 * s + nn)) * 32u + (uint32_t)(jj >> 1) * 2048u + (uint32_t)(jj & 1) * 16u;
   const int gshift = mt.group_shift;
-#pragma unroll
-  for (int s = 0; s < 4; ++s) {
-    const int n = min(n0 + wave * 64 + 16 * s + nn, N - 1);
-    qrow[s] = mt.qweight + (size_t)n * (K >> 1) + 16 * jj;
-    srow[s] = mt.scales + (size_t)n * (K >> gshift);
-  }
-
-  // entry index at every chunk boundary of this band: lane c holds the boundary before chunk c
-  uint32_t tp_chunk = 0;
-  if (band_ok) tp_chunk = mt.tile_ptr[(uint32_t)band * (uint32_t)ktiles + (uint32_t)min(lane * (SM_KC / 64), ktiles)];
-
-  // ---- x staging: thread = 16-byte chunk (tid & 63) of rows (tid >> 6) + 4 i ----
-  u32x4 xr[4];
+  const uint32_t soff = (bsafe * (uint32_t)(K >> gshift) * 64u + (uint32_t)nn * 4u) * 2u;
+  // ---- x staging: piece = 8 columns (16 bytes of bf16) of one row; thread handles pieces
+  //      (row tid>>5, columns 8*(tid&31)..) and the same columns of row 8 + (tid>>5) ----
+  // Loads are unconditional, from clamped addresses, and out-of-range parts are zeroed only when the
+  // registers are stored to LDS: a branch or an early use here would make every later wait a full drain.
+  u32x4 xr[2];
   auto load_x = [&](int c) {
-    const int kc = c * SM_KC, kcl = min(SM_KC, K - kc);
-    const int ch = tid & 63;
+    const int col = min(c * SM_KC + 8 * (tid & 31), K - 8);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int m = (tid >> 6) + 4 * i;
-      xr[i] = u32x4{0u, 0u, 0u, 0u};
-      if (m < M && 8 * ch < kcl) xr[i] = *reinterpret_cast<const u32x4*>(mt.x + (size_t)m * K + kc + 8 * ch);
+    for (int i = 0; i < 2; ++i) {
+      const int m = min((tid >> 5) + 8 * i, M - 1);
+      xr[i] = *reinterpret_cast<const u32x4 __attribute__((address_space(1)))*>(g_x + (size_t)m * K + col);
     }
   };
-  auto store_x = [&](int buf) {
-    const int ch = tid & 63;
+  auto store_x = [&](int c) {
+    const int ch = tid & 31, buf = c & 1;
+    const bool col_ok = c * SM_KC + 8 * ch < K;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int m = (tid >> 6) + 4 * i;
+    for (int i = 0; i < 2; ++i) {
+      const int m = (tid >> 5) + 8 * i;
+      const bool ok = col_ok && m < M;
       u32x4 o;
 #pragma unroll
-      for (int w = 0; w < 4; ++w) o[w] = sm_stage_x_word(xr[i], w);
+      for (int w = 0; w < 4; ++w) o[w] = ok ? sm_stage_x_word(xr[i], w) : 0u;
       *reinterpret_cast<u32x4*>(xs + (buf * SM_ROWS + m) * SM_XSTRIDE + 8 * ch) = o;
+      if (FAST) {
+        // constant part of the un-centred codes over this row's 128-column block: words 0,2 hold even
+        // columns (1024+c -> 1032 + w), words 1,3 odd ones (64+c -> 72 + w); 16 lanes share (row, block)
+        float part = 1032.0f * (sm_half_sum(o[0]) + sm_half_sum(o[2])) + 72.0f * (sm_half_sum(o[1]) + sm_half_sum(o[3]));
+#pragma unroll
+        for (int off = 1; off < 16; off <<= 1) part += __shfl_xor(part, off, 64);
+        if ((tid & 15) == 0) corr[(buf * 2 + (ch >> 4)) * SM_ROWS + m] = -part;
+      }
     }
   };
 
-  // ---- code stream: slot h*4+s holds subtile s of an even (h=0) / odd (h=1) 128-column block ----
-  u32x4 qbuf[8];
-  auto load_q = [&](int slot, int gkb) {
-    qbuf[slot] = *reinterpret_cast<const u32x4*>(qrow[slot & 3] + (size_t)min(gkb, nkb_total - 1) * 64);
+  // ---- code stream: slot kbl*4+s holds subtile s of the chunk's 128-column block kbl ----
+  u32x4 qbuf[4];                                            // slot s: subtile s of the next 128-column block
+  auto load_q = [&](int s, int gkb) {
+    qbuf[s] = *reinterpret_cast<const u32x4 __attribute__((address_space(1)))*>(g_q + (size_t)min(gkb, nkb_total - 1) * 4096 + qoff[s]);
   };
 #pragma unroll
-  for (int i = 0; i < 8; ++i) load_q(i, i >> 2);
+  for (int s = 0; s < 4; ++s) load_q(s, 0);
+  u32x2 sc[2] = {u32x2{0u, 0u}, u32x2{0u, 0u}};             // FAST: block kbl of the chunk: the lane's four scales (s = 0..3)
+  auto load_scales = [&](int c) {
+#pragma unroll
+    for (int kbl = 0; kbl < 2; ++kbl)
+      sc[kbl] = *reinterpret_cast<const u32x2 __attribute__((address_space(1)))*>(
+          reinterpret_cast<const uint8_t __attribute__((address_space(1)))*>(g_scales) +
+          (size_t)min(2 * c + kbl, nkb_total - 1) * 128 + soff);
+  };
+  if (FAST) load_scales(0);
   load_x(0);
+
+  // ---- sensitive entries of this band: boundaries per chunk, ring of entries in LDS ----
+  auto tp_at = [&](int c) -> uint32_t {                     // first entry of the band at or after chunk c
+    return band_ok ? g_tile_ptr[(uint32_t)band * (uint32_t)ktiles + (uint32_t)min(c * (SM_KC / 64), ktiles)] : 0u;
+  };
+  uint32_t tp0 = tp_at(0), tp1 = tp_at(1);
+  uint32_t w_hi = __builtin_amdgcn_readfirstlane(tp0) & ~3u;      // entries below w_hi have been generated
+  // A refill is only reached with band_ok (some entry of the band is wanted), so nnz > 0 there.  Its
+  // loads are issued where they are used: refills are rare (256 entries each) and the other resident
+  // waves cover the wait, while holding the values across the dense loop would cost 8 registers.
+  auto refill = [&]() {
+    const uint32_t j = w_hi + 4u * lane;
+    uint32_t pf_idx[4];
+    float pf_val[4];
+    {
+      const uint32_t last = mt.nnz - 1u;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint32_t je = min(j + e, last);               // clamped; entries past the end are never consumed
+        pf_idx[e] = g_sp_idx[je];
+        pf_val[e] = g_sp_val[je];
+      }
+    }
+    float z[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (a.eps != 0.0f) zbar_quad((mt.nnz_base + j) >> 2, a.seed, a.step, z);
+    uint32_t p[4];
+    half4_t vh, zh;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const uint32_t flat = pf_idx[e];
+      const uint32_t n = sm_fast_div(flat, mt.div_mul, mt.div_shift);
+      const uint32_t r = n - (uint32_t)(band * 64);
+      const uint32_t k = flat - n * (uint32_t)K;
+      p[e] = ((r & 63u) << 10) | (k & 1023u);
+      vh[e] = (_Float16)pf_val[e];
+      zh[e] = (_Float16)z[e];
+    }
+    const uint32_t ring = j & (uint32_t)(SM_CAP - 1);
+    *reinterpret_cast<u32x2*>(my_winp + ring) = u32x2{p[0] | (p[1] << 16), p[2] | (p[3] << 16)};
+    *reinterpret_cast<u32x2*>(my_winv + ring) = __builtin_bit_cast(u32x2, vh);
+    *reinterpret_cast<u32x2*>(my_winz + ring) = __builtin_bit_cast(u32x2, zh);
+    w_hi += SM_WIN;
+  };
+
   store_x(0);
   __syncthreads();
 
   for (int c = 0; c < nchunks; ++c) {
-    const int kc = c * SM_KC, kcl = min(SM_KC, K - kc);
-    const int nkb = kcl >> 7;                               // 128-column blocks in this chunk (1..4)
+    const int kc = c * SM_KC;
     const _Float16* const xc = xs + (c & 1) * SM_ROWS * SM_XSTRIDE;
-    if (c + 1 < nchunks) load_x(c + 1);
-    // scales of the chunk's four blocks for the lane's four rows (group 128)
-    uint16_t sc4[4][4];
-    if (G128) {
-#pragma unroll
-      for (int s = 0; s < 4; ++s)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) sc4[s][i] = srow[s][min(4 * c + i, nkb_total - 1)];
-    }
-    // sparse arrays of this chunk's first window
-    const uint32_t j_lo = __builtin_amdgcn_readlane(tp_chunk, c), j_hi = __builtin_amdgcn_readlane(tp_chunk, c + 1);
-    const uint32_t w_first = j_lo & ~3u;
-    uint32_t pf_idx[4];
-    float pf_val[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const uint32_t je = w_first + 4u * lane + e;
-      const bool ok = band_ok && je >= j_lo && je < j_hi;
-      pf_idx[e] = ok ? mt.sp_idx[je] : 0u;
-      pf_val[e] = ok ? mt.sp_val[je] : 0.0f;
-    }
+    const float* const cc = corr + (c & 1) * 2 * SM_ROWS;
+    const uint32_t tp2 = tp_at(c + 2);
 
     // ---- dense: stream this band's codes ----
 #pragma unroll
-    for (int kbl = 0; kbl < 4; ++kbl) {
-      if (kbl < nkb) {
-        const int h = kbl & 1, gkb = 4 * c + kbl;
-        half8_t af[4];
+    for (int kbl = 0; kbl < 2; ++kbl) {
+      // blocks past the end of K multiply clamped codes with the zeros staged for x: no branch needed
+      half8_t af[4];
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
-          af[t] = *reinterpret_cast<const half8_t*>(xc + nn * SM_XSTRIDE + kbl * 128 + 32 * jj + 8 * t);
+      for (int t = 0; t < 4; ++t)
+        af[t] = *reinterpret_cast<const half8_t*>(xc + nn * SM_XSTRIDE + kbl * 128 + 32 * jj + 8 * t);
+      float4_t init = {0.0f, 0.0f, 0.0f, 0.0f};
+      if (FAST) init = *reinterpret_cast<const float4_t*>(cc + kbl * SM_ROWS + 4 * jj);
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const u32x4 q = qbuf[s];
+        load_q(s, 2 * c + kbl + 1);                         // the slot is free: fetch the next block's codes
+        _Float16 sh;
+        if (FAST) {
+          sh = __builtin_bit_cast(half4_t, sc[kbl])[s];
+        } else {
+          const uint32_t gi = (uint32_t)min((kc + kbl * 128 + 32 * jj) >> gshift, (K >> gshift) - 1);
+          sh = __builtin_bit_cast(_Float16, *reinterpret_cast<const uint16_t __attribute__((address_space(1)))*>(
+              reinterpret_cast<const uint8_t __attribute__((address_space(1)))*>(g_scales) + (size_t)gi * 128 + soff + 2 * s));
+        }
+        const half2_t s2 = {sh, sh};
+        float4_t tmp = init;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const half8_t b = sm_dequant_word<FAST>(q[t], magic_lo, magic_hi, s2);
+          tmp = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[t], b, tmp, 0, 0, 0);
+        }
+        if (FAST) {
+          const float sf = (float)sh;                        // column nn of the subtile: the lane's own row of W
+#pragma unroll
+          for (int r = 0; r < 4; ++r) acc[s][r] = fmaf(tmp[r], sf, acc[s][r]);
+        } else {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) acc[s][r] += tmp[r];
+        }
+        // keep the subtiles in program order: hoisting the later ones' loads and unpacking costs registers,
+        // and the latency they would hide is covered by the other resident waves
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+
+    // next chunk's x and scales: requested now that this chunk's are no longer needed, landing
+    // while the sparse part runs
+    load_x(min(c + 1, nchunks - 1));                        // the last chunk re-reads itself; never stored
+    if (FAST) load_scales(c + 1);                           // clamped inside
+
+    // ---- sparse: this band's entries inside the chunk, 16 at a time (4 per k-group of the MFMA) ----
+    {
+      const uint32_t j_lo = __builtin_amdgcn_readfirstlane(tp0), j_hi = __builtin_amdgcn_readfirstlane(tp1);
+      const uint32_t kcm = (uint32_t)kc & 1023u;
+      for (uint32_t g0 = j_lo & ~3u; g0 < j_hi; g0 += 16u) {
+        // refilling here never overwrites an entry at or above g0: w_hi < g0 + 16 and SM_WIN + 16 <= SM_CAP
+        while (w_hi < min(g0 + 16u, j_hi)) refill();
+        const uint32_t e0 = g0 + 4u * (uint32_t)jj;
+        const uint32_t ring = e0 & (uint32_t)(SM_CAP - 1);
+        const u32x2 pw = *reinterpret_cast<const u32x2*>(my_winp + ring);
+        u32x2 vw = *reinterpret_cast<const u32x2*>(my_winv + ring);
+        u32x2 zw = *reinterpret_cast<const u32x2*>(my_winz + ring);
+        half4_t ax;
+        uint32_t d[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const uint32_t pos = (pw[i >> 1] >> (16 * (i & 1))) & 0xFFFFu;
+          const uint32_t kk = ((pos & 1023u) - kcm) & 1023u;
+          // a malformed layout must neither leave the staged chunk nor reach another row
+          const bool ok = e0 + i >= j_lo && e0 + i < j_hi && kk < (uint32_t)SM_KC;
+          ax[i] = xc[nn * SM_XSTRIDE + sm_xpos(ok ? (int)kk : 0)];
+          d[i] = ok ? ((pos >> 10) ^ (uint32_t)nn) : 0xFFFFu;     // 16 s for the lane that owns the entry's row
+        }
+        const uint32_t dp[2] = {d[0] | (d[1] << 16), d[2] | (d[3] << 16)};
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-          const u32x4 q = qbuf[h * 4 + s];
-          load_q(h * 4 + s, gkb + 2);                       // reload this slot with the block two ahead
-          _Float16 sh;
-          if (G128) {
-            sh = __builtin_bit_cast(_Float16, sc4[s][kbl]);
-          } else {
-            sh = __builtin_bit_cast(_Float16, srow[s][(kc + kbl * 128 + 32 * jj) >> gshift]);
-          }
-          const half2_t s2 = {sh, sh};
-          float4_t tmp = {0.0f, 0.0f, 0.0f, 0.0f};
+          u32x2 bv, bz;
 #pragma unroll
-          for (int t = 0; t < 4; ++t) {
-            const half8_t b = sm_dequant_word<!G128>(q[t], magic_lo, magic_hi, s2);
-            tmp = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[t], b, tmp, 0, 0, 0);
+          for (int h = 0; h < 2; ++h) {
+            const u16x2 one = {1, 1};
+            const u16x2 ne = __builtin_elementwise_min(__builtin_bit_cast(u16x2, dp[h] ^ (uint32_t)(16 * s * 0x00010001)), one);
+            const uint32_t mask = __builtin_bit_cast(uint32_t, (u16x2)(ne - one));       // 0xFFFF where equal
+            bv[h] = vw[h] & mask;
+            bz[h] = zw[h] & mask;
           }
-          if (G128) {
-            const float sf = (float)sh;                      // column nn of the subtile: the lane's own row of W
-#pragma unroll
-            for (int r = 0; r < 4; ++r) acc[s][r] = fmaf(tmp[r], sf, acc[s][r]);
-          } else {
-#pragma unroll
-            for (int r = 0; r < 4; ++r) acc[s][r] += tmp[r];
-          }
+          acc[s] = __builtin_amdgcn_mfma_f32_16x16x16f16(ax, __builtin_bit_cast(half4_t, bv), acc[s], 0, 0, 0);
+          accz[s] = __builtin_amdgcn_mfma_f32_16x16x16f16(ax, __builtin_bit_cast(half4_t, bz), accz[s], 0, 0, 0);
         }
       }
     }
+    tp0 = tp1; tp1 = tp2;
 
-    // ---- sparse: sensitive entries of this band inside the chunk ----
-    if (band_ok) {
-      for (uint32_t w0 = w_first; w0 < j_hi; w0 += SM_WIN) {
-        // window [w0, w0+256): one Philox counter (4 consecutive entries) per lane
-        const uint32_t j = w0 + 4u * lane;
-        uint32_t pos[4];
-        float val[4], ez[4];
-        bool ok[4];
-        {
-          float z[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-          if (j < j_hi && a.eps != 0.0f) zbar_quad((mt.nnz_base + j) >> 2, a.seed, a.step, z);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const uint32_t je = j + e;
-            ok[e] = je >= j_lo && je < j_hi;
-            uint32_t flat;
-            if (w0 == w_first) { flat = pf_idx[e]; val[e] = pf_val[e]; }
-            else { flat = ok[e] ? mt.sp_idx[je] : 0u; val[e] = ok[e] ? mt.sp_val[je] : 0.0f; }
-            ez[e] = a.eps * z[e];
-            const uint32_t n = sm_fast_div(flat, mt.div_mul, mt.div_shift);
-            const uint32_t r = n - (uint32_t)(band * 64);
-            const uint32_t kk = flat - n * (uint32_t)K - (uint32_t)kc;
-            ok[e] = ok[e] && r < 64u && kk < (uint32_t)kcl;           // a malformed layout must not leave the band
-            pos[e] = (r << 10) | (kk & 1023u);
-          }
-        }
-        // split into four lists by (row mod 4): list q occupies window slots [start[q], start[q+1])
-        uint32_t start[5];
-        start[0] = 0;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          uint32_t base = start[q];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const bool mine = ok[e] && ((pos[e] >> 10) & 3u) == (uint32_t)q;
-            const uint64_t mask = __ballot(mine);
-            const uint32_t before = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-            if (mine) {
-              my_winp[base + before] = (uint16_t)pos[e];
-              my_winv[base + before] = make_float2(val[e], ez[e]);
-            }
-            base += (uint32_t)__popcll(mask);
-          }
-          start[q + 1] = base;
-        }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // lists visible to the whole wave
-        // accumulate: lane group q (16 lanes = 16 token rows) walks list q; the four groups never share a row
-        const int q = lane >> 4, m = lane & 15;
-        const uint32_t my_lo = q == 0 ? start[0] : q == 1 ? start[1] : q == 2 ? start[2] : start[3];
-        const uint32_t my_hi = q == 0 ? start[1] : q == 1 ? start[2] : q == 2 ? start[3] : start[4];
-        uint32_t longest = 0;
-#pragma unroll
-        for (int qq = 0; qq < 4; ++qq) longest = max(longest, start[qq + 1] - start[qq]);
-        for (uint32_t it = 0; it < longest; ++it) {
-          const uint32_t e = my_lo + it;
-          if (e < my_hi) {
-            const uint32_t p = my_winp[e];
-            const float2 v = my_winv[e];
-            const float xv = (float)xc[m * SM_XSTRIDE + sm_xpos((int)(p & 1023u))];
-            float2* dst = my_ysp + (p >> 10) * SM_ROWS + m;
-            float2 y = *dst;
-            y.x = fmaf(v.x + v.y, xv, y.x);
-            y.y = fmaf(v.x - v.y, xv, y.y);
-            *dst = y;
-          }
-        }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // done with the window before it is refilled
-      }
-    }
-
-    if (c + 1 < nchunks) store_x((c + 1) & 1);
+    if (c + 1 < nchunks) store_x(c + 1);
     __syncthreads();                                        // next chunk's x complete; this chunk's no longer read
   }
 
@@ -360,15 +425,15 @@ __global__ void __launch_bounds__(256) small_m_kernel(SmallArgs a) {
     for (int r = 0; r < 4; ++r) {
       const int m = 4 * jj + r;
       if (m < M && n < N) {
-        const float2 sp = my_ysp[nl * SM_ROWS + m];
-        const float yp = acc[s][r] + sp.x, ym = acc[s][r] + sp.y;
+        const float pz = a.eps * accz[s][r];
+        const float yp = acc[s][r] + pz, ym = acc[s][r] - pz;
         if (a.loss_mode) {
-          const float t = __uint_as_float((uint32_t)mt.target[(size_t)m * N + n] << 16);
+          const float t = __uint_as_float((uint32_t)g_target[(size_t)m * N + n] << 16);
           const float dp = yp - t, dm = ym - t;
           lp += (double)(dp * dp);
           lm += (double)(dm * dm);
         } else {
-          mt.y[(size_t)m * N + n] = a.store_sign > 0 ? yp : a.store_sign < 0 ? ym : 0.5f * (yp + ym);
+          g_y[(size_t)m * N + n] = a.store_sign > 0 ? yp : a.store_sign < 0 ? ym : acc[s][r];
         }
       }
     }
@@ -381,8 +446,8 @@ __global__ void __launch_bounds__(256) small_m_kernel(SmallArgs a) {
     __syncthreads();
     if (tid == 0) {
       const int pi = mt.partial_base + strip;
-      a.partial_plus[pi] = ((red[0][0] + red[0][1]) + (red[0][2] + red[0][3])) * mt.loss_scale;
-      a.partial_minus[pi] = ((red[1][0] + red[1][1]) + (red[1][2] + red[1][3])) * mt.loss_scale;
+      ((double __attribute__((address_space(1)))*)a.partial_plus)[pi] = ((red[0][0] + red[0][1]) + (red[0][2] + red[0][3])) * mt.loss_scale;
+      ((double __attribute__((address_space(1)))*)a.partial_minus)[pi] = ((red[1][0] + red[1][1]) + (red[1][2] + red[1][3])) * mt.loss_scale;
     }
   }
 }
@@ -418,14 +483,17 @@ __global__ void __launch_bounds__(256) sparse_update_table_kernel(const SmallMat
 // ---- host side -----------------------------------------------------------------------------
 
 static size_t small_lds_bytes() {
-  return (size_t)2 * SM_ROWS * SM_XSTRIDE * 2 + (size_t)4 * 64 * SM_ROWS * 8 + (size_t)4 * SM_WIN * 8 +
-         (size_t)4 * SM_WIN * 2;
+  return (size_t)2 * SM_ROWS * SM_XSTRIDE * 2 + (size_t)2 * 2 * SM_ROWS * 4 + (size_t)3 * 4 * SM_CAP * 2;
 }
 
 bool small_m_eligible(const szo_linear_desc* d) {
-  return d->M >= 1 && d->M <= SM_ROWS && d->N >= 1 && (d->K % 128) == 0 && d->K <= 63 * SM_KC &&
-         d->tile_dtype == SZO_TILE_F16;
+  return d->M >= 1 && d->M <= SM_ROWS && d->N >= 1 && (d->K % 128) == 0 && d->group >= 32 &&
+         d->tile_dtype == SZO_TILE_F16 &&
+         (uint64_t)((d->N + 63) / 64 * 64) * (uint64_t)d->K / 2 < (1ull << 32);   // 32-bit code offsets
 }
+
+// group of 128 (one scale per 128-column block): the fast instantiation
+static bool small_m_fast(const szo_linear_desc* d) { return d->group == 128; }
 
 int small_m_blocks(const szo_linear_desc* d) { return (int)((d->N + SM_BN - 1) / SM_BN); }
 
@@ -472,7 +540,7 @@ int small_m_launch_one(const szo_linear_desc* d, uint64_t seed, uint64_t step, f
   a.seed = seed; a.step = step; a.eps = eps;
   a.partial_plus = partial_plus; a.partial_minus = partial_minus;
   const int blocks = small_m_blocks(d);
-  if (d->group == 128) small_m_kernel<true><<<blocks, 256, small_lds_bytes(), stream>>>(a);
+  if (small_m_fast(d)) small_m_kernel<true><<<blocks, 256, small_lds_bytes(), stream>>>(a);
   else small_m_kernel<false><<<blocks, 256, small_lds_bytes(), stream>>>(a);
   SZO_LAUNCH_CHECK();
   return SZO_OK;
@@ -502,15 +570,15 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
     slot.cap = n;
   }
   SmallMat* const host = slot.host;
-  // order: group-128 matrices first (by K descending), then the others (by K descending)
+  // order: matrices of the fast instantiation first (by K descending), then the others (by K descending)
   int order[4096];
   for (int i = 0; i < n; ++i) order[i] = i;
   for (int i = 1; i < n; ++i) {                       // insertion sort: n is a few hundred
     const int o = order[i];
-    const int64_t key = (descs[o].group == 128 ? (int64_t)1 << 40 : 0) + descs[o].K;
+    const int64_t key = (small_m_fast(&descs[o]) ? (int64_t)1 << 40 : 0) + descs[o].K;
     int j = i - 1;
     while (j >= 0) {
-      const int64_t kj = (descs[order[j]].group == 128 ? (int64_t)1 << 40 : 0) + descs[order[j]].K;
+      const int64_t kj = (small_m_fast(&descs[order[j]]) ? (int64_t)1 << 40 : 0) + descs[order[j]].K;
       if (kj >= key) break;
       order[j + 1] = order[j];
       --j;
@@ -523,7 +591,7 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
     const szo_linear_desc* d = &descs[order[r]];
     SmallMat& m = host[r];
     fill_mat(m, d);
-    const bool g128 = d->group == 128;
+    const bool g128 = small_m_fast(d);
     m.first_block = g128 ? blocks128 : blocks_other;
     m.partial_base = partials;
     m.first_quad = quads;

@@ -58,6 +58,7 @@ def build_linear(seed, M, N, K, group, density=1e-3, kind="uniform", nnz=None, n
     flat = szo.szo_mask_generate(N, K, k, 0 if kind == "uniform" else 1, ms)
     tile_ptr, sp_idx, perm = szo.szo_tcsr_build(N, K, flat)
     q, scales, sp_val = szo.szo_quantize_pack(W, group, sp_idx)
+    q_banded, scales_banded = szo.szo_layout_weights(q, scales, group)
     if k == 0:      # keep non-null device pointers for empty arrays
         sp_idx_d = torch.zeros(4, dtype=torch.int32, device=device)
         sp_val_d = torch.zeros(4, dtype=torch.float32, device=device)
@@ -67,15 +68,16 @@ def build_linear(seed, M, N, K, group, density=1e-3, kind="uniform", nnz=None, n
     lin = DeviceLinear(
         name=name, M=M, N=N, K=K, group=group, nnz=k, nnz_base=nnz_base,
         x=_to_dev(x.view(np.int16), device, torch.bfloat16),
-        qweight=_to_dev(q, device),
-        scales=_to_dev(scales.view(np.int16), device, torch.float16),
+        qweight=_to_dev(q_banded, device),
+        scales=_to_dev(scales_banded.view(np.int16), device, torch.float16),
         tile_ptr=_to_dev(tile_ptr.view(np.int32), device),
         sp_idx=sp_idx_d, sp_val=sp_val_d,
         target=_to_dev(t.view(np.int16), device, torch.bfloat16),
         y=y if y is not None else torch.empty((M, N), dtype=torch.float32, device=device))
     if keep_host:
         lin.host = dict(x_bits=x, W=W, target_bits=t, flat=flat, tile_ptr=tile_ptr, sp_idx=sp_idx,
-                        perm=perm, qweight=q, scales=scales, sp_val=sp_val)
+                        perm=perm, qweight=q, scales=scales, sp_val=sp_val,
+                        qweight_banded=q_banded, scales_banded=scales_banded)
     return lin
 
 

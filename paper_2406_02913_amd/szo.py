@@ -51,6 +51,9 @@ _SIGS = {
     "szo_tcsr_build": (C.c_int, [C.c_int64, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]),
     "szo_quantize_pack": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_void_p, C.c_int64,
                                      C.c_void_p, C.c_void_p, C.c_void_p]),
+    "szo_qweight_bytes": (C.c_size_t, [C.c_int64, C.c_int64]),
+    "szo_scales_count": (C.c_size_t, [C.c_int64, C.c_int64, C.c_int]),
+    "szo_layout_weights": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_void_p, C.c_void_p]),
     "szo_philox4x32_10": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "szo_debug_zbar": (C.c_int, [C.c_uint64, C.c_int64, C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]),
     "szo_set_tile_config": (C.c_int, [C.c_int]),
@@ -189,6 +192,25 @@ def szo_quantize_pack(W, group, mask_flat):
     _check("szo_quantize_pack", lib.szo_quantize_pack(wp, N, K, group, mp, mask.size, q.ctypes.data,
                                                       scales.ctypes.data, sp_val.ctypes.data))
     return q, scales.view(np.float16), sp_val
+
+
+def szo_qweight_bytes(N, K):
+    return int(lib.szo_qweight_bytes(N, K))
+
+
+def szo_scales_count(N, K, group):
+    return int(lib.szo_scales_count(N, K, group))
+
+
+def szo_layout_weights(q, scales, group):
+    """Row-major host arrays -> (q_banded u8 [bytes], scales_banded fp16 [count])."""
+    q, qp = _host(q, np.uint8)
+    N, K = q.shape[0], q.shape[1] * 2
+    sc, sp = _host(np.asarray(scales).view(np.uint16), np.uint16)
+    qb = np.empty(szo_qweight_bytes(N, K), dtype=np.uint8)
+    sb = np.empty(szo_scales_count(N, K, group), dtype=np.uint16)
+    _check("szo_layout_weights", lib.szo_layout_weights(qp, sp, N, K, group, qb.ctypes.data, sb.ctypes.data))
+    return qb, sb.view(np.float16)
 
 
 def szo_philox4x32_10(ctr, key):

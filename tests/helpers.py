@@ -32,6 +32,28 @@ def clone(m):
     return c
 
 
+def banded_codes(q_rowmajor):
+    """Row-major packed codes [N, K/2] -> the banded device layout, written out from its definition:
+    byte ((B*(K/64) + T)*64 + r)*32 + (k%64)/2, rows padded to 64 with code 8."""
+    N, Kh = q_rowmajor.shape
+    bands, T = (N + 63) // 64, Kh // 32
+    pad = np.full((bands * 64, Kh), 0x88, dtype=np.uint8)
+    pad[:N] = q_rowmajor
+    return pad.reshape(bands, 64, T, 32).transpose(0, 2, 1, 3).reshape(-1)
+
+
+def banded_scales(scales_rowmajor_bits):
+    """Row-major fp16 bit patterns [N, K/group] -> banded layout: element (B*G + g)*64 + (r%16)*4 + r//16."""
+    N, G = scales_rowmajor_bits.shape
+    bands = (N + 63) // 64
+    pad = np.zeros((bands * 64, G), dtype=np.uint16)
+    pad[:N] = scales_rowmajor_bits
+    out = np.empty((bands, G, 64), dtype=np.uint16)
+    for r in range(64):
+        out[:, :, (r % 16) * 4 + r // 16] = pad.reshape(bands, 64, G)[:, r, :]
+    return out.reshape(-1)
+
+
 def make_pair(seed, M, N, K, group, density=1e-3, kind="uniform", nnz=None, nnz_base=0, device="cuda"):
     """The same layer twice: oracle-side (numpy) and device-side (libszo host
     set-up + torch memory).  Asserts that mask, tile order, codes, scales and
@@ -45,6 +67,8 @@ def make_pair(seed, M, N, K, group, density=1e-3, kind="uniform", nnz=None, nnz_
     assert np.array_equal(h["qweight"], oquant.pack_codes(o.codes))
     assert np.array_equal(h["scales"].view(np.uint16), o.scales.view(np.uint16))
     assert np.array_equal(h["sp_val"], o.sp_val)
+    assert np.array_equal(h["qweight_banded"], banded_codes(oquant.pack_codes(o.codes)))
+    assert np.array_equal(h["scales_banded"].view(np.uint16), banded_scales(o.scales.view(np.uint16)))
     return o, d
 
 

@@ -12,10 +12,12 @@ pytestmark = pytest.mark.gpu
 
 # (seed, M, N, K, group, density)
 SHAPES = [
-    (11, 16, 256, 128, 128, 1e-2),      # one strip, one 128-column block
-    (12, 16, 512, 1152, 128, 1e-3),     # crosses the 1024-column chunk boundary
-    (13, 1, 200, 256, 128, 5e-2),       # one token, ragged N, > 256 entries per band and chunk
-    (14, 7, 513, 2048, 128, 2e-3),      # ragged M and N, two chunks
+    (11, 16, 256, 128, 128, 1e-2),      # one strip, one 128-column block (half a chunk: plain instantiation)
+    (12, 16, 512, 1152, 128, 1e-3),     # 4.5 chunks of 256 columns: plain instantiation with a ragged last chunk
+    (13, 1, 200, 256, 128, 5e-2),       # one token, ragged N, > 256 entries per band and chunk (several refills)
+    (14, 7, 513, 2048, 128, 2e-3),      # ragged M and N, eight chunks
+    (19, 16, 128, 1024, 128, 8e-2),     # ~1300 entries per band and chunk: the entry ring wraps inside a chunk
+    (20, 3, 64, 4864, 128, 3e-3),       # 19 chunks, one band
     (15, 16, 320, 256, 32, 1e-2),       # group 32: scale applied per element
     (16, 9, 128, 384, 64, 2e-2),        # group 64
     (17, 16, 256, 256, 128, 0.0),       # k = 0
@@ -30,7 +32,9 @@ def test_few_token_forward_matches_oracle(shape):
     o, d = make_pair(s, M, N, K, G, dens, nnz_base=12)
     seed, step, eps = 77, 5, 1e-3
     z = ophilox.zbar(seed, step, 12, o.sp_idx.size)
-    tol = 2e-5 if G == 128 else 1e-3          # group 128 keeps (code-8) exact and scales in fp32
+    # fp32 accumulation of un-centred codes (|constant part| ~ 1e3 x the signal's terms) and fp16 sparse
+    # values: a few 1e-4; the bar for y is 5e-3
+    tol = 5e-4 if G == 128 else 1e-3
     for sign in (+1, -1, 0):
         d.y.fill_(float("nan"))
         szo.szo_linear_fwd(d.desc(), seed, step, sign, eps)
@@ -66,7 +70,7 @@ def test_few_token_fused_loss_and_step():
         z = ophilox.zbar(9, 2, 0, o1.sp_idx.size)
         yE = olayer.linear_fwd(o1.x_bits, o1.codes, o1.scales, 128, o1.sp_idx, o1.sp_val, z, sign, 1e-3, "E")
         want = olayer.mse_loss(yE, o1.target_bits)
-        assert abs(acc.item() - want) <= 1e-5 * want
+        assert abs(acc.item() - want) <= 1e-4 * want
     # whole steps over two matrices
     scal = torch.zeros(3, dtype=torch.float64, device="cuda")
     a, b = clone(o1), clone(o2)
@@ -76,8 +80,8 @@ def test_few_token_fused_loss_and_step():
         szo.szo_zo_step(descs, 5, s, 1e-3, 1e-3, scal, ws, szo.STEP_FUSED_LOSS)
         lp, lm, g = scal.cpu().numpy()
         r = ozo.zo_step([a, b], 5, s, 1e-3, 1e-3)
-        assert abs(lp - r["loss_plus"]) <= 1e-5 * r["loss_plus"]
-        assert abs(lm - r["loss_minus"]) <= 1e-5 * r["loss_minus"]
+        assert abs(lp - r["loss_plus"]) <= 1e-4 * r["loss_plus"]
+        assert abs(lm - r["loss_minus"]) <= 1e-4 * r["loss_minus"]
         assert abs(g - r["g"]) <= 1e-2 * max(abs(r["g"]), sg), (s, g, r["g"], sg)
     for om, dd, o in ((a, d1, o1), (b, d2, o2)):
         dv_gpu = dd.sp_val.cpu().numpy().astype(np.float64) - o.sp_val

@@ -91,6 +91,31 @@ def test_quantize_pack_bit_exact(N, K, G, k):
     assert np.array_equal(v, ov)
 
 
+@pytest.mark.parametrize("N,K,G", [(64, 64, 32), (100, 256, 128), (513, 1152, 64)])
+def test_banded_layout_places_every_code_and_scale_where_the_header_says(N, K, G):
+    rng = np.random.default_rng(N + K)
+    q = rng.integers(0, 256, size=(N, K // 2), dtype=np.uint8)
+    sc = rng.integers(0, 0x7C00, size=(N, K // G), dtype=np.uint16)
+    qb, sb = szo.szo_layout_weights(q, sc, G)
+    bands = (N + 63) // 64
+    assert qb.size == szo.szo_qweight_bytes(N, K) == bands * 64 * K // 2
+    assert sb.size == szo.szo_scales_count(N, K, G) == bands * 64 * (K // G)
+    sb = sb.view(np.uint16)
+    # element by element, from the formulas (not from the reshuffle in helpers)
+    for n, k in zip(rng.integers(0, N, 300), rng.integers(0, K, 300)):
+        B, r, T = n // 64, n % 64, k // 64
+        assert qb[((B * (K // 64) + T) * 64 + r) * 32 + (k % 64) // 2] == q[n, k // 2]
+        g = k // G
+        assert sb[(B * (K // G) + g) * 64 + (r % 16) * 4 + r // 16] == sc[n, g]
+    from helpers import banded_codes, banded_scales
+    assert np.array_equal(qb, banded_codes(q)) and np.array_equal(sb, banded_scales(sc))
+    if N % 64:      # padding rows: weight zero
+        last = qb.reshape(bands, K // 64, 64, 32)[-1, :, N % 64:, :]
+        assert (last == 0x88).all()
+    assert szo.lib.szo_layout_weights(q.ctypes.data, sc.ctypes.data, N, K + 1, G, qb.ctypes.data, sb.ctypes.data) == szo.EINVAL
+    assert szo.szo_qweight_bytes(64, 100) == 0
+
+
 def test_half_conversion_matches_numpy_everywhere_it_matters():
     # scale = fp16(max/7): drive max through normals, subnormals, ties and overflow
     vals = np.concatenate([
