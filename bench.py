@@ -27,9 +27,11 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def algorithmic_bytes_fwd(m):
-    """Bytes one forward must move: codes + scales + sparse (idx, val) + x + y."""
-    return (m.N * m.K // 2 + 2 * m.N * (m.K // m.group) + 8 * m.nnz + 2 * m.M * m.K + 4 * m.M * m.N)
+def algorithmic_bytes_fwd(m, fused=True):
+    """Bytes one pass over a matrix must move: codes + scales + sparse (idx, val) + x, and either
+    the bf16 target (loss fused into the kernel) or the fp32 y it writes."""
+    return (m.N * m.K // 2 + 2 * m.N * (m.K // m.group) + 8 * m.nnz + 2 * m.M * m.K
+            + (2 if fused else 4) * m.M * m.N)
 
 
 def cpu_baseline(cfg, args, total_flops_per_step):
@@ -78,7 +80,7 @@ def main():
     ap.add_argument("--seed", type=int, default=2024)
     ap.add_argument("--data-seed", type=int, default=0)
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle baseline leg (0 = skip)")
-    ap.add_argument("--kernel-reps", type=int, default=3, help="passes over the stack when timing the forward kernel alone")
+    ap.add_argument("--kernel-reps", type=int, default=3, help="extra steps run with per-launch kernel timing switched on")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
@@ -133,41 +135,40 @@ def main():
     log(f"[bench] {ms_per_step:.3f} ms/step (events), {1e3 * wall / args.steps:.3f} ms/step (wall); "
         f"last step L+={lp:.6f} L-={lm:.6f} g={g:.4e}")
 
-    # ---- the dominant kernel alone: every forward launch of the stack, bracketed by events ----
+    # ---- the dominant kernel alone: the library brackets every forward-kernel launch of a few more
+    #      steps with events on the launch stream (szo_kernel_timing) ----
     fwd_flops = sum(2.0 * m.M * m.N * m.K for m in mats)
-    fwd_bytes = sum(algorithmic_bytes_fwd(m) for m in mats)
-    acc = torch.zeros(1, dtype=torch.float64, device="cuda")
-
-    def fwd_pass(sign):
-        for i, m in enumerate(mats):
-            if args.unfused_loss:
-                szo.szo_linear_fwd(descs[i], args.seed, 0, sign, eps, stream.cuda_stream)
-            else:
-                szo.szo_linear_fwd_mse(descs[i], args.seed, 0, sign, eps, 1.0 / (m.M * m.N), acc, ws, stream.cuda_stream)
-
-    fwd_pass(+1)
-    torch.cuda.synchronize()
-    k0, k1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    k0.record(stream)
-    for r in range(args.kernel_reps):
-        fwd_pass(+1 if r % 2 == 0 else -1)
-    k1.record(stream)
-    torch.cuda.synchronize()
-    launches = args.kernel_reps * len(mats)
-    k_ms = k0.elapsed_time(k1) / launches
-    tflops = fwd_flops / len(mats) / (k_ms * 1e-3) / 1e12
-    gbs = fwd_bytes / len(mats) / (k_ms * 1e-3) / 1e9
-    mfma_bound = (fwd_flops / fwd_bytes) > (PEAK_MFMA_16BIT_TFLOPS * 1e12) / (PEAK_HBM_GBS * 1e9)
+    few = all(m.M <= 16 for m in mats) and dt == szo.TILE_F16       # the library's few-token path
+    reps = max(1, args.kernel_reps)
+    szo.szo_kernel_timing(True)
+    for s in range(reps):
+        one_step(args.warmup + args.steps + s)
+    k_total_ms, launches = szo.szo_kernel_timing_read()
+    szo.szo_kernel_timing(False)
+    k_ms = k_total_ms / launches
+    if few:
+        # one launch streams every matrix once and serves both signs
+        kernel = "small_m_kernel"
+        launch_bytes = float(sum(algorithmic_bytes_fwd(m, fused=bool(flags)) for m in mats)) * reps / launches
+        launch_flops = 2 * fwd_flops * reps / launches
+    else:
+        kernel = "linear_fwd_kernel"
+        launch_bytes = float(sum(algorithmic_bytes_fwd(m, fused=bool(flags)) for m in mats)) * 2 * reps / launches
+        launch_flops = 2 * fwd_flops * reps / launches
+    tflops = launch_flops / (k_ms * 1e-3) / 1e12
+    gbs = launch_bytes / (k_ms * 1e-3) / 1e9
+    mfma_bound = (launch_flops / launch_bytes) > (PEAK_MFMA_16BIT_TFLOPS * 1e12) / (PEAK_HBM_GBS * 1e9)
     if mfma_bound:
         roof = {"bound": "mfma", "achieved": round(tflops, 2), "peak": PEAK_MFMA_16BIT_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(tflops / PEAK_MFMA_16BIT_TFLOPS, 4), "traffic": None}
     else:
         roof = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None}
-    roof.update({"kernel": "linear_fwd_kernel", "avg_launch_us": round(1e3 * k_ms, 2), "launches_timed": launches,
-                 "flops_per_launch": fwd_flops / len(mats), "bytes_per_launch": fwd_bytes / len(mats)})
+    roof.update({"kernel": kernel, "avg_launch_us": round(1e3 * k_ms, 2), "launches_timed": launches,
+                 "flops_per_launch": launch_flops, "bytes_per_launch": launch_bytes})
     step_flops = 2 * fwd_flops
-    log(f"[bench] forward kernel: {1e3 * k_ms:.1f} us/launch avg, {tflops:.1f} TFLOP/s, {gbs:.1f} GB/s algorithmic")
+    log(f"[bench] {kernel}: {1e3 * k_ms:.1f} us/launch avg over {launches} launches, {tflops:.1f} TFLOP/s, "
+        f"{gbs:.1f} GB/s algorithmic")
 
     base = None
     if args.cpu_seconds > 0:

@@ -183,6 +183,15 @@ int szo_layout_weights(const uint8_t* q, const uint16_t* scales, int64_t N, int6
 
 /* ---- inspection ----------------------------------------------------------------------- */
 
+/* Timing of the forward kernels (the tiled kernel and the few-token kernel) for benchmarks.
+ * szo_kernel_timing(1) makes every later forward-kernel launch record a pair of events around
+ * itself on the stream it is launched on; szo_kernel_timing(0) stops that.  Either call drops
+ * what was recorded.  szo_kernel_timing_read() waits for the recorded launches, returns the sum
+ * of their durations in milliseconds and their number, and starts a new collection.  Process-
+ * wide state, for one measuring thread; events are created on demand and kept. */
+int szo_kernel_timing(int enable);
+int szo_kernel_timing_read(double* total_ms /* host */, int64_t* launches /* host */);
+
 /* Host evaluation of Philox-4x32-10 (ten rounds; multipliers 0xD2511F53, 0xCD9E8D57; key
  * increments 0x9E3779B9, 0xBB67AE85). */
 int szo_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);

@@ -689,9 +689,11 @@ static int launch(FwdParams& p, hipStream_t stream) {
     SZO_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
     attr_set = true;
   }
+  int rc = timing_begin(stream);
+  if (rc != SZO_OK) return rc;
   kern<<<(unsigned)blocks, 64 * WAVES_M * WAVES_N, lds_bytes, stream>>>(p);
   SZO_LAUNCH_CHECK();
-  return SZO_OK;
+  return timing_end(stream);
 }
 
 // Which workgroup tile a shape runs with, and how many workgroups (= loss partials) that makes.

@@ -53,6 +53,12 @@ int small_m_launch_one(const szo_linear_desc* d, uint64_t seed, uint64_t step, f
 int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t step, float eps, float lr,
                  void* table_dev, double* partial_plus, double* scalars, bool do_update, hipStream_t stream);
 
+// Optional timing of the forward kernels (szo_kernel_timing): when switched on, every launch of a
+// forward kernel is bracketed by a pair of events on its own stream.  Both calls are no-ops when
+// timing is off.  Defined in szo_kernels.hip.
+int timing_begin(hipStream_t stream);
+int timing_end(hipStream_t stream);
+
 // Sets n 32-bit words to zero with a small kernel (defined in szo_kernels.hip).
 int zero_words(void* p, int n, hipStream_t stream);
 

@@ -1,5 +1,6 @@
 // Small kernels of the step: the Gaussian inspection kernel, the stand-in MSE loss, the SPSA
 // scalar (Definition 1) and the sparse ZO-SGD update (Section 3.4, fixed-parameter update rule).
+#include <vector>
 #include "szo_internal.h"
 #include "szo_rng.cuh"
 
@@ -150,7 +151,68 @@ int zero_words(void* p, int n, hipStream_t stream) {
 
 using namespace szo;
 
+// ---- optional timing of the forward kernels ---------------------------------------------------
+// Process-wide, meant for one measuring thread: a growing pool of event pairs, one pair per
+// forward-kernel launch since the last read.
+namespace szo {
+namespace {
+struct TimingState {
+  bool on = false;
+  std::vector<hipEvent_t> start, stop;
+  size_t used = 0;          // pairs recorded since the last read
+  bool open = false;        // a begin without its end
+};
+TimingState g_timing;
+}  // namespace
+
+int timing_begin(hipStream_t stream) {
+  if (!g_timing.on) return SZO_OK;
+  if (g_timing.used == g_timing.start.size()) {
+    hipEvent_t a, b;
+    SZO_HIP(hipEventCreate(&a));
+    SZO_HIP(hipEventCreate(&b));
+    g_timing.start.push_back(a);
+    g_timing.stop.push_back(b);
+  }
+  SZO_HIP(hipEventRecord(g_timing.start[g_timing.used], stream));
+  g_timing.open = true;
+  return SZO_OK;
+}
+
+int timing_end(hipStream_t stream) {
+  if (!g_timing.on || !g_timing.open) return SZO_OK;
+  SZO_HIP(hipEventRecord(g_timing.stop[g_timing.used], stream));
+  g_timing.used += 1;
+  g_timing.open = false;
+  return SZO_OK;
+}
+
+}  // namespace szo
+
 extern "C" {
+
+int szo_kernel_timing(int enable) {
+  szo::g_timing.on = enable != 0;
+  szo::g_timing.used = 0;
+  szo::g_timing.open = false;
+  return SZO_OK;
+}
+
+int szo_kernel_timing_read(double* total_ms, int64_t* launches) {
+  using szo::g_timing;
+  if (!total_ms || !launches) return SZO_EINVAL;
+  double sum = 0.0;
+  for (size_t i = 0; i < g_timing.used; ++i) {
+    SZO_HIP(hipEventSynchronize(g_timing.stop[i]));
+    float ms = 0.0f;
+    SZO_HIP(hipEventElapsedTime(&ms, g_timing.start[i], g_timing.stop[i]));
+    sum += (double)ms;
+  }
+  *total_ms = sum;
+  *launches = (int64_t)g_timing.used;
+  g_timing.used = 0;
+  return SZO_OK;
+}
 
 int szo_last_hip_error(void) { return g_last_hip_error; }
 int szo_version(void) { return 1; }

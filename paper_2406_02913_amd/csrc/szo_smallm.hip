@@ -540,10 +540,12 @@ int small_m_launch_one(const szo_linear_desc* d, uint64_t seed, uint64_t step, f
   a.seed = seed; a.step = step; a.eps = eps;
   a.partial_plus = partial_plus; a.partial_minus = partial_minus;
   const int blocks = small_m_blocks(d);
+  int trc = timing_begin(stream);
+  if (trc != SZO_OK) return trc;
   if (small_m_fast(d)) small_m_kernel<true><<<blocks, 256, small_lds_bytes(), stream>>>(a);
   else small_m_kernel<false><<<blocks, 256, small_lds_bytes(), stream>>>(a);
   SZO_LAUNCH_CHECK();
-  return SZO_OK;
+  return timing_end(stream);
 }
 
 // A whole stack in one launch per group size.  The table is assembled on the host, longest K
@@ -612,13 +614,17 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
   const SmallMat* tdev = (const SmallMat*)table_dev;
   if (blocks128 > 0) {
     a.table = tdev; a.n_mats = n128;
+    if ((rc = timing_begin(stream)) != SZO_OK) return rc;
     small_m_kernel<true><<<blocks128, 256, small_lds_bytes(), stream>>>(a);
     SZO_LAUNCH_CHECK();
+    if ((rc = timing_end(stream)) != SZO_OK) return rc;
   }
   if (blocks_other > 0) {
     a.table = tdev + n128; a.n_mats = n - n128;
+    if ((rc = timing_begin(stream)) != SZO_OK) return rc;
     small_m_kernel<false><<<blocks_other, 256, small_lds_bytes(), stream>>>(a);
     SZO_LAUNCH_CHECK();
+    if ((rc = timing_end(stream)) != SZO_OK) return rc;
   }
   rc = reduce_step(partial_plus, partials, eps, scalars, stream);
   if (rc != SZO_OK) return rc;

@@ -57,6 +57,8 @@ _SIGS = {
     "szo_philox4x32_10": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "szo_debug_zbar": (C.c_int, [C.c_uint64, C.c_int64, C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]),
     "szo_set_tile_config": (C.c_int, [C.c_int]),
+    "szo_kernel_timing": (C.c_int, [C.c_int]),
+    "szo_kernel_timing_read": (C.c_int, [C.c_void_p, C.c_void_p]),
     "szo_last_hip_error": (C.c_int, []),
     "szo_version": (C.c_int, []),
 }
@@ -228,6 +230,17 @@ def szo_debug_zbar(nnz_base, nnz, seed, step, words_out=None, z_out=None, stream
 
 def szo_set_tile_config(config):
     _check("szo_set_tile_config", lib.szo_set_tile_config(config))
+
+
+def szo_kernel_timing(enable):
+    _check("szo_kernel_timing", lib.szo_kernel_timing(1 if enable else 0))
+
+
+def szo_kernel_timing_read():
+    """(sum of the recorded forward-kernel durations in ms, number of launches)."""
+    ms, n = C.c_double(0.0), C.c_int64(0)
+    _check("szo_kernel_timing_read", lib.szo_kernel_timing_read(C.byref(ms), C.byref(n)))
+    return ms.value, n.value
 
 
 def szo_last_hip_error():
