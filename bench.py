@@ -69,8 +69,9 @@ def cpu_baseline(cfg, args, total_flops_per_step):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=None, help="timed steps (default 20; 200 for the few-token workloads)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed steps first (default 3; 30 for the few-token workloads, "
+                    "whose sub-millisecond steps otherwise end before the clocks have settled)")
     ap.add_argument("--workload", default="c3", help="c1|c2|c3|c4|c5|c3m16 (see synth.WORKLOADS)")
     ap.add_argument("--layers", type=int, default=None, help="override the number of decoder blocks")
     ap.add_argument("--m", type=int, default=None, help="override the token count")
@@ -80,8 +81,22 @@ def main():
     ap.add_argument("--seed", type=int, default=2024)
     ap.add_argument("--data-seed", type=int, default=0)
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle baseline leg (0 = skip)")
-    ap.add_argument("--kernel-reps", type=int, default=3, help="extra steps run with per-launch kernel timing switched on")
+    ap.add_argument("--kernel-reps", type=int, default=None,
+                    help="extra steps run with per-launch kernel timing switched on (default: as many as --steps)")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="instead of the benchmark: copy a buffer of this many MiB five times with a plain copy kernel "
+                         "and exit (known traffic, to scale the FETCH_SIZE / WRITE_SIZE counters of a profiler run)")
     args = ap.parse_args()
+    if args.copy_calibration:
+        import torch
+        n = args.copy_calibration << 20
+        src = torch.ones(n, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_per_launch": n, "launches": 5}), flush=True)
+        return
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
         sys.exit(2)
@@ -89,6 +104,11 @@ def main():
     import torch
     from paper_2406_02913_amd import stack, synth, szo
 
+    few_default = (args.m or synth.WORKLOADS[args.workload]["M"]) <= 16
+    if args.steps is None:
+        args.steps = 200 if few_default else 20
+    if args.warmup is None:
+        args.warmup = 30 if few_default else 3
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dt = szo.TILE_F16 if args.tile == "f16" else szo.TILE_BF16
@@ -139,7 +159,7 @@ def main():
     #      steps with events on the launch stream (szo_kernel_timing) ----
     fwd_flops = sum(2.0 * m.M * m.N * m.K for m in mats)
     few = all(m.M <= 16 for m in mats) and dt == szo.TILE_F16       # the library's few-token path
-    reps = max(1, args.kernel_reps)
+    reps = args.steps if args.kernel_reps is None else max(1, args.kernel_reps)
     szo.szo_kernel_timing(True)
     for s in range(reps):
         one_step(args.warmup + args.steps + s)

@@ -154,6 +154,14 @@ __global__ void __launch_bounds__(256, SM_MIN_BLOCKS) small_m_kernel(SmallArgs a
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  // Workgroup ids go round-robin over the 8 XCDs, each with its own L2.  Remap them so that eight
+  // consecutive strips (normally of one matrix, which all read the same x) run on one XCD and
+  // consecutive groups of eight rotate over the XCDs; the ragged tail (< 64 ids) keeps its order.
+  int bid = (int)blockIdx.x;
+  if (bid < (int)(gridDim.x & ~63u)) {
+    const int xcd = bid & 7, i = bid >> 3;
+    bid = (((i >> 3) << 3) + xcd) * 8 + (i & 7);
+  }
   // ---- which matrix, which 256-column strip ----
   // The table entry is read through the constant address space (scalar loads: the table is written
   // before the launch and never during it), so that its fields live in scalar registers like the
@@ -163,10 +171,10 @@ __global__ void __launch_bounds__(256, SM_MIN_BLOCKS) small_m_kernel(SmallArgs a
     constexpr int W = (int)(sizeof(SmallMat) / 4), FB = (int)(offsetof(SmallMat, first_block) / 4);
     static_assert(sizeof(SmallMat) % 4 == 0 && offsetof(SmallMat, first_block) % 4 == 0, "table entry is read as words");
     const auto* tab = (const uint32_t __attribute__((address_space(4)))*)a.table;
-    int lo = 0, hi = a.n_mats - 1;                          // last matrix whose first_block <= blockIdx.x
+    int lo = 0, hi = a.n_mats - 1;                          // last matrix whose first_block <= bid
     while (lo < hi) {
       const int mid = (lo + hi + 1) >> 1;
-      if ((int)tab[mid * W + FB] <= (int)blockIdx.x) lo = mid; else hi = mid - 1;
+      if ((int)tab[mid * W + FB] <= bid) lo = mid; else hi = mid - 1;
     }
     struct Words { uint32_t w[W]; } raw;
 #pragma unroll
@@ -184,7 +192,7 @@ __global__ void __launch_bounds__(256, SM_MIN_BLOCKS) small_m_kernel(SmallArgs a
   const auto g_sp_val = SZO_GLOBAL(float, mt.sp_val);
   const auto g_target = SZO_GLOBAL(uint16_t, mt.target);
   float __attribute__((address_space(1)))* const g_y = (float __attribute__((address_space(1)))*)mt.y;
-  const int strip = blockIdx.x - mt.first_block;
+  const int strip = bid - mt.first_block;
   const int n0 = strip * SM_BN;
   const int N = mt.N, K = mt.K, M = a.M;
   const int ktiles = K >> 6;
@@ -480,6 +488,14 @@ __global__ void __launch_bounds__(256) sparse_update_table_kernel(const SmallMat
   }
 }
 
+// Copies the step's table from pinned host memory (mapped into the device's address space) into
+// the workspace.  A kernel rather than a DMA copy: the hand-over from the copy engine to the
+// compute queue costs more than reading a few tens of KB over the host link from a kernel.
+__global__ void __launch_bounds__(256) upload_table_kernel(const uint32_t* __restrict__ src, uint32_t* __restrict__ dst, int words) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < words) dst[i] = src[i];
+}
+
 // ---- host side -----------------------------------------------------------------------------
 
 static size_t small_lds_bytes() {
@@ -559,7 +575,7 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
   if (rc != SZO_OK) return rc;
   // Pinned staging for the table: a ring of four, so that the host may run a few steps ahead of
   // the GPU; a slot is reused only after the copy that read it has executed.
-  struct Slot { SmallMat* host; int cap; hipEvent_t copied; bool used; };
+  struct Slot { SmallMat* host; const uint32_t* host_dev; int cap; hipEvent_t copied; bool used; };   // host_dev: device address of host
   static thread_local Slot ring[4] = {};
   static thread_local unsigned turn = 0;
   Slot& slot = ring[turn++ & 3];
@@ -568,7 +584,8 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
   if (n > slot.cap) {
     if (slot.host) (void)hipHostFree(slot.host);
     slot.host = nullptr; slot.cap = 0;
-    SZO_HIP(hipHostMalloc((void**)&slot.host, sizeof(SmallMat) * (size_t)n, hipHostMallocDefault));
+    SZO_HIP(hipHostMalloc((void**)&slot.host, sizeof(SmallMat) * (size_t)n, hipHostMallocMapped));
+    SZO_HIP(hipHostGetDevicePointer((void**)&slot.host_dev, slot.host, 0));
     slot.cap = n;
   }
   SmallMat* const host = slot.host;
@@ -603,7 +620,11 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
     quads += ((int64_t)d->nnz + 3) / 4;
   }
   if (2 * (int64_t)partials > kMaxLossPartials) return SZO_EUNSUPPORTED;
-  SZO_HIP(hipMemcpyAsync(table_dev, host, sizeof(SmallMat) * (size_t)n, hipMemcpyHostToDevice, stream));
+  {
+    const int words = (int)(sizeof(SmallMat) * (size_t)n / 4);
+    upload_table_kernel<<<(words + 255) / 256, 256, 0, stream>>>(slot.host_dev, (uint32_t*)table_dev, words);
+    SZO_LAUNCH_CHECK();
+  }
   SZO_HIP(hipEventRecord(slot.copied, stream));
   slot.used = true;
   SmallArgs a{};
