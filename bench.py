@@ -21,6 +21,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_MFMA_16BIT_TFLOPS = 2500.0      # MI355X dense fp16/bf16 matrix peak
 PEAK_HBM_GBS = 8000.0                # MI355X HBM3E
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# script scaled by a plain copy of known size (profiles/*.md give the commands and the raw readings).
+# Only valid for the unmodified workloads; anything else reports null.
+MEASURED_TRAFFIC_BYTES = {"c3": 2.346e8, "c3m16": 3.912e9}
 
 
 def log(*a):
@@ -184,6 +188,8 @@ def main():
     else:
         roof = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None}
+    if (args.layers is None and args.m is None and args.density is None and flags and dt == szo.TILE_F16):
+        roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(args.workload)
     roof.update({"kernel": kernel, "avg_launch_us": round(1e3 * k_ms, 2), "launches_timed": launches,
                  "flops_per_launch": launch_flops, "bytes_per_launch": launch_bytes})
     step_flops = 2 * fwd_flops
