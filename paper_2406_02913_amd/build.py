@@ -11,6 +11,7 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 HIP_SOURCES = ["szo_kernels.hip", "szo_gemm.hip", "szo_smallm.hip"]
 HOST_SOURCES = ["szo_host.cpp"]
+PROBES = ["mfma_ceiling", "hbm_read_ceiling"]
 
 COMMON = ["-O3", "-fPIC", "-std=c++17", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 # packed fp32 VALU forms are switched off (see the hardware notes this project follows)
@@ -37,6 +38,13 @@ def build(verbose=False, extra=()):
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
+    # stand-alone measurement probes (ceilings quoted in the profile summaries); not linked into the library
+    for probe in PROBES:
+        cmd = [HIPCC, "-O3", "-std=c++17"] + DEVICE + [os.path.join(CSRC, "probes", probe + ".hip"),
+                                                        "-o", os.path.join(HERE, "probe_" + probe)]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.check_call(cmd)
     return LIB
 
 
