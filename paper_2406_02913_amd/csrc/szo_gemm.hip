@@ -823,7 +823,7 @@ int szo_zo_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t ste
   if (few) {
     if (small_m_table_bytes(n) > kTableBytesPerMatrix * (size_t)kMaxStepMatrices) return SZO_EUNSUPPORTED;
     return small_m_step(descs, n, seed, step, eps, lr, (char*)workspace + kWorkspaceTableOffset,
-                        partial_area(workspace), scalars, true, s);
+                        partial_area(workspace), scalars, true, true, s);
   }
   if (fuse && 2 * total > kMaxLossPartials) return SZO_EUNSUPPORTED;
   if (!fuse) {
@@ -852,6 +852,10 @@ int szo_zo_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t ste
   rc = fuse ? reduce_step(partial_area(workspace), (int)total, eps, scalars, s)
             : szo_spsa_g(scalars, scalars + 1, eps, scalars + 2, s);
   if (rc != SZO_OK) return rc;
+  // one grouped update launch for the whole stack (per-matrix launches when the table does not fit)
+  if (small_m_table_bytes(n) <= kTableBytesPerMatrix * (size_t)kMaxStepMatrices)
+    return small_m_step(descs, n, seed, step, eps, lr, (char*)workspace + kWorkspaceTableOffset, nullptr, scalars,
+                        false, true, s);
   for (int i = 0; i < n; ++i) {
     rc = szo_sparse_update(descs[i].sp_val, descs[i].sp_idx, descs[i].nnz, descs[i].nnz_base, seed, step,
                            scalars + 2, lr, s);

@@ -51,7 +51,8 @@ size_t small_m_table_bytes(int n);
 int small_m_launch_one(const szo_linear_desc* d, uint64_t seed, uint64_t step, float eps, int sign, bool loss_mode,
                        double* partial_plus, double* partial_minus, hipStream_t stream);
 int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t step, float eps, float lr,
-                 void* table_dev, double* partial_plus, double* scalars, bool do_update, hipStream_t stream);
+                 void* table_dev, double* partial_plus, double* scalars, bool do_forward, bool do_update,
+                 hipStream_t stream);
 
 // Optional timing of the forward kernels (szo_kernel_timing): when switched on, every launch of a
 // forward kernel is bracketed by a pair of events on its own stream.  Both calls are no-ops when

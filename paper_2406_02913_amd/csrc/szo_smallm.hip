@@ -567,12 +567,14 @@ int small_m_launch_one(const szo_linear_desc* d, uint64_t seed, uint64_t step, f
 // A whole stack in one launch per group size.  The table is assembled on the host, longest K
 // first (their workgroups run longest, so they should start first), copied into `table_dev`
 // (device, small_m_table_bytes(n)) with an asynchronous copy on the stream, and also drives one
-// grouped sparse update when `do_update` is set.  *total_partials receives the number of partials
-// per sign.
+// grouped sparse update when `do_update` is set.  With `do_forward` false only the table is staged
+// and the update runs (used by the many-token step, whose forwards are launched per matrix).
 int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t step, float eps, float lr,
-                 void* table_dev, double* partial_plus, double* scalars, bool do_update, hipStream_t stream) {
+                 void* table_dev, double* partial_plus, double* scalars, bool do_forward, bool do_update,
+                 hipStream_t stream) {
   int rc = set_small_attrs();
   if (rc != SZO_OK) return rc;
+  if (n > 4096) return SZO_EUNSUPPORTED;
   // Pinned staging for the table: a ring of four, so that the host may run a few steps ahead of
   // the GPU; a slot is reused only after the copy that read it has executed.
   struct Slot { SmallMat* host; const uint32_t* host_dev; int cap; hipEvent_t copied; bool used; };   // host_dev: device address of host
@@ -619,7 +621,7 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
     partials += b;
     quads += ((int64_t)d->nnz + 3) / 4;
   }
-  if (2 * (int64_t)partials > kMaxLossPartials) return SZO_EUNSUPPORTED;
+  if (do_forward && 2 * (int64_t)partials > kMaxLossPartials) return SZO_EUNSUPPORTED;
   {
     const int words = (int)(sizeof(SmallMat) * (size_t)n / 4);
     upload_table_kernel<<<(words + 255) / 256, 256, 0, stream>>>(slot.host_dev, (uint32_t*)table_dev, words);
@@ -633,22 +635,24 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
   a.seed = seed; a.step = step; a.eps = eps;
   a.partial_plus = partial_plus; a.partial_minus = partial_plus + partials;
   const SmallMat* tdev = (const SmallMat*)table_dev;
-  if (blocks128 > 0) {
+  if (do_forward && blocks128 > 0) {
     a.table = tdev; a.n_mats = n128;
     if ((rc = timing_begin(stream)) != SZO_OK) return rc;
     small_m_kernel<true><<<blocks128, 256, small_lds_bytes(), stream>>>(a);
     SZO_LAUNCH_CHECK();
     if ((rc = timing_end(stream)) != SZO_OK) return rc;
   }
-  if (blocks_other > 0) {
+  if (do_forward && blocks_other > 0) {
     a.table = tdev + n128; a.n_mats = n - n128;
     if ((rc = timing_begin(stream)) != SZO_OK) return rc;
     small_m_kernel<false><<<blocks_other, 256, small_lds_bytes(), stream>>>(a);
     SZO_LAUNCH_CHECK();
     if ((rc = timing_end(stream)) != SZO_OK) return rc;
   }
-  rc = reduce_step(partial_plus, partials, eps, scalars, stream);
-  if (rc != SZO_OK) return rc;
+  if (do_forward) {
+    rc = reduce_step(partial_plus, partials, eps, scalars, stream);
+    if (rc != SZO_OK) return rc;
+  }
   if (do_update && quads > 0) {
     const int64_t ub = (quads + 255) / 256;
     if (ub > 0x7FFFFFFF) return SZO_EUNSUPPORTED;

@@ -1,0 +1,83 @@
+"""GPU parity at the benchmark's full sizes and in the launch configuration
+bench.py times (tile configuration chosen by the library, fused loss, heavy
+tail mask at 0.1 %).  The oracle cannot form a 4096 x 11008 output in seconds,
+so outputs are sampled: whole rows of W (all of K) for a set of output columns
+that is guaranteed to contain sensitive entries, times a set of token rows."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import layer as olayer, philox as ophilox
+from oracle.quant import bf16_bits_to_f64
+from paper_2406_02913_amd import szo
+from helpers import make_pair, rel_fro
+
+pytestmark = pytest.mark.gpu
+
+
+def _sampled_oracle(o, z, sign, eps, rows_n, rows_m, mode, K):
+    """y[rows_m][:, rows_n] from the oracle's own functions on the sub-matrix of
+    W made of rows rows_n (entries of other rows dropped, indices renumbered)."""
+    rows_n = np.asarray(rows_n)
+    n_of = o.sp_idx.astype(np.int64) // K
+    k_of = o.sp_idx.astype(np.int64) % K
+    pos = {int(n): i for i, n in enumerate(rows_n)}
+    keep = np.isin(n_of, rows_n)
+    sub_idx = np.array([pos[int(n)] for n in n_of[keep]], dtype=np.int64) * K + k_of[keep]
+    return olayer.linear_fwd(o.x_bits[rows_m], o.codes[rows_n], o.scales[rows_n], o.group, sub_idx,
+                             o.sp_val[keep], None if z is None else z[keep], sign, eps, mode, "f16")
+
+
+@pytest.mark.parametrize("name,M,N,K", [("gate", 4096, 11008, 4096), ("down", 4096, 4096, 11008)])
+def test_full_size_forward_sampled(name, M, N, K):
+    szo.szo_set_tile_config(0)                                   # what bench.py runs
+    o, d = make_pair(5 if name == "gate" else 6, M, N, K, 128, 1e-3, kind="heavy_tail", nnz_base=1 << 33)
+    seed, step, eps = 2024, 3, 1e-3
+    z = ophilox.zbar(seed, step, 1 << 33, o.sp_idx.size)        # counters beyond 32 bits
+    rng = np.random.default_rng(N + K)
+    n_of = o.sp_idx.astype(np.int64) // K
+    hot = np.unique(n_of[rng.integers(0, n_of.size, 24)])        # columns that own sensitive entries
+    rows_n = np.unique(np.concatenate([hot, rng.integers(0, N, 24), [0, N - 1, 255, 256]]))
+    rows_m = np.unique(np.concatenate([rng.integers(0, M, 40), [0, M - 1, 255, 256]]))
+    for sign in (+1, -1):
+        d.y.fill_(float("nan"))
+        szo.szo_linear_fwd(d.desc(), seed, step, sign, eps)
+        torch.cuda.synchronize()
+        y = d.y[torch.as_tensor(rows_m, device="cuda")][:, torch.as_tensor(rows_n, device="cuda")].cpu().numpy()
+        assert np.isfinite(y).all()
+        yE = _sampled_oracle(o, z, sign, eps, rows_n, rows_m, "E", K)
+        yD = _sampled_oracle(o, z, sign, eps, rows_n, rows_m, "D", K)
+        assert rel_fro(y, yE) <= 5e-3, (sign, rel_fro(y, yE))
+        assert rel_fro(y, yD) <= 2e-5, (sign, rel_fro(y, yD))   # nothing dropped or misplaced
+    # the sampled columns with entries really see the perturbation
+    szo.szo_linear_fwd(d.desc(), seed, step, 0, eps)
+    torch.cuda.synchronize()
+    y0 = d.y[torch.as_tensor(rows_m, device="cuda")][:, torch.as_tensor(hot, device="cuda")].cpu().numpy()
+    y0E = _sampled_oracle(o, None, 0, eps, hot, rows_m, "E", K)
+    assert rel_fro(y0, y0E) <= 5e-3
+    ypE = _sampled_oracle(o, z, +1, eps, hot, rows_m, "E", K)
+    assert np.abs(ypE - y0E).max() > 0
+
+
+def test_full_size_fused_loss_matches_separate_loss_and_sampled_oracle_loss():
+    M = N = K = 4096
+    szo.szo_set_tile_config(0)
+    o, d = make_pair(7, M, N, K, 128, 1e-3, kind="heavy_tail")
+    ws = szo.new_workspace()
+    seed, step, eps = 11, 0, 1e-3
+    fused = torch.zeros(1, dtype=torch.float64, device="cuda")
+    szo.szo_linear_fwd_mse(d.desc(with_y=False), seed, step, +1, eps, 1.0 / (M * N), fused, ws)
+    sep = torch.zeros(1, dtype=torch.float64, device="cuda")
+    szo.szo_linear_fwd(d.desc(), seed, step, +1, eps)
+    szo.szo_mse_loss(d.y, d.target, M * N, 1.0 / (M * N), sep, ws)
+    torch.cuda.synchronize()
+    assert abs(fused.item() - sep.item()) <= 1e-8 * sep.item()
+    # the loss restricted to a sample of outputs, against the oracle on the same sample
+    z = ophilox.zbar(seed, step, 0, o.sp_idx.size)
+    rng = np.random.default_rng(3)
+    rows_n, rows_m = np.unique(rng.integers(0, N, 48)), np.unique(rng.integers(0, M, 48))
+    y = d.y[torch.as_tensor(rows_m, device="cuda")][:, torch.as_tensor(rows_n, device="cuda")].cpu().numpy().astype(np.float64)
+    t = bf16_bits_to_f64(o.target_bits[rows_m][:, rows_n])
+    yE = _sampled_oracle(o, z, +1, eps, rows_n, rows_m, "E", K)
+    got, want = np.mean((y - t) ** 2), np.mean((yE - t) ** 2)
+    assert abs(got - want) <= 1e-4 * want
