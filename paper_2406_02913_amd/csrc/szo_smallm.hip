@@ -17,9 +17,9 @@
 //     the B operand of v_mfma_f32_16x16x32_f16 (no LDS round trip: every weight is used once).
 //     With a quantisation group of 128 the codes are NOT re-centred: 0x6400|c reads 1024+c and
 //     0x5400|(c<<4) reads 64+c, both exact in fp16, and the constant part
-//     sum_k x[m,k] (1032 | 72) of each 128-column block is computed once per workgroup while x is
-//     staged and enters the MFMA chain negated as its initial accumulator.  The block's partial
-//     product then takes the group scale in fp32.
+//     sum_k x[m,k] (1032 | 72) of each 128-column block comes out of one more MFMA chain per block
+//     against a constant operand and seeds the chains of the block's four subtiles, negated.  The
+//     block's partial product then takes the group scale in fp32.
 //   - keeps a ring of its band's sensitive entries in LDS (position, fp16 v, fp16 z; z from the
 //     same Philox/Box-Muller routine and counters as the large-batch kernel and the update, 256
 //     entries per refill so that all lanes work), and multiplies them in groups of 16 entries as a
@@ -134,11 +134,6 @@ __device__ __forceinline__ uint32_t sm_stage_x_word(u32x4 u, int w) {
   return __builtin_bit_cast(uint32_t, h);
 }
 
-__device__ __forceinline__ float sm_half_sum(uint32_t w) {
-  const half2_t h = __builtin_bit_cast(half2_t, w);
-  return (float)h[0] + (float)h[1];
-}
-
 // FAST = quantisation group of 128: the scales of a block's four subtiles are prefetched with one
 // 8-byte load and applied to each block's partial product, and the codes stay un-centred as
 // described at the top.  Otherwise the scale is read from memory where it is needed
@@ -147,8 +142,7 @@ template <bool FAST>
 __global__ void __launch_bounds__(256, SM_MIN_BLOCKS) small_m_kernel(SmallArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
   _Float16* const xs = reinterpret_cast<_Float16*>(smem);                        // [2][16][SM_XSTRIDE]
-  float* const corr = reinterpret_cast<float*>(xs + 2 * SM_ROWS * SM_XSTRIDE);     // [2][2 blocks][16 rows], negated
-  uint16_t* const winp = reinterpret_cast<uint16_t*>(corr + 2 * 2 * SM_ROWS);      // [4 bands][SM_CAP] row<<10 | column&1023
+  uint16_t* const winp = reinterpret_cast<uint16_t*>(xs + 2 * SM_ROWS * SM_XSTRIDE);   // [4 bands][SM_CAP] packed position (see refill)
   uint16_t* const winv = winp + 4 * SM_CAP;                                        // fp16 bits of v
   uint16_t* const winz = winv + 4 * SM_CAP;                                        // fp16 bits of z
 
@@ -204,6 +198,10 @@ __global__ void __launch_bounds__(256, SM_MIN_BLOCKS) small_m_kernel(SmallArgs a
 
   uint32_t magic_lo = 0x64006400u, magic_hi = 0x54005400u;
   asm volatile("" : "+v"(magic_lo), "+v"(magic_hi));
+  // B operand of the constant-part chain: every column holds -(1032, 1032, 72, 72, 1032, 1032, 72, 72), the
+  // offsets of the un-centred codes in the element order (0,4)(1,5)(2,6)(3,7)
+  const half8_t minus_offsets = {(_Float16)-1032.0f, (_Float16)-1032.0f, (_Float16)-72.0f, (_Float16)-72.0f,
+                                 (_Float16)-1032.0f, (_Float16)-1032.0f, (_Float16)-72.0f, (_Float16)-72.0f};
 
   uint16_t* const my_winp = winp + wave * SM_CAP;
   uint16_t* const my_winv = winv + wave * SM_CAP;
@@ -249,24 +247,21 @@ __global__ void __launch_bounds__(256, SM_MIN_BLOCKS) small_m_kernel(SmallArgs a
 #pragma unroll
       for (int w = 0; w < 4; ++w) o[w] = ok ? sm_stage_x_word(xr[i], w) : 0u;
       *reinterpret_cast<u32x4*>(xs + (buf * SM_ROWS + m) * SM_XSTRIDE + 8 * ch) = o;
-      if (FAST) {
-        // constant part of the un-centred codes over this row's 128-column block: words 0,2 hold even
-        // columns (1024+c -> 1032 + w), words 1,3 odd ones (64+c -> 72 + w); 16 lanes share (row, block)
-        float part = 1032.0f * (sm_half_sum(o[0]) + sm_half_sum(o[2])) + 72.0f * (sm_half_sum(o[1]) + sm_half_sum(o[3]));
-#pragma unroll
-        for (int off = 1; off < 16; off <<= 1) part += __shfl_xor(part, off, 64);
-        if ((tid & 15) == 0) corr[(buf * 2 + (ch >> 4)) * SM_ROWS + m] = -part;
-      }
     }
   };
 
   // ---- code stream: slot kbl*4+s holds subtile s of the chunk's 128-column block kbl ----
-  u32x4 qbuf[4];                                            // slot s: subtile s of the next 128-column block
-  auto load_q = [&](int s, int gkb) {
-    qbuf[s] = *reinterpret_cast<const u32x4 __attribute__((address_space(1)))*>(g_q + (size_t)min(gkb, nkb_total - 1) * 4096 + qoff[s]);
+#ifndef SM_RING
+#define SM_RING 1                       // 128-column blocks of codes in flight per wave (1 or 2)
+#endif
+  // slot (b % SM_RING)*4 + s: subtile s of 128-column block b.  With two blocks in flight the stream
+  // keeps running while the wave is busy with the sparse part and the barrier of a chunk.
+  u32x4 qbuf[4 * SM_RING];
+  auto load_q = [&](int slot, int gkb) {
+    qbuf[slot] = *reinterpret_cast<const u32x4 __attribute__((address_space(1)))*>(g_q + (size_t)min(gkb, nkb_total - 1) * 4096 + qoff[slot & 3]);
   };
 #pragma unroll
-  for (int s = 0; s < 4; ++s) load_q(s, 0);
+  for (int i = 0; i < 4 * SM_RING; ++i) load_q(i, i >> 2);
   u32x2 sc[2] = {u32x2{0u, 0u}, u32x2{0u, 0u}};             // FAST: block kbl of the chunk: the lane's four scales (s = 0..3)
   auto load_scales = [&](int c) {
 #pragma unroll
@@ -310,7 +305,8 @@ __global__ void __launch_bounds__(256, SM_MIN_BLOCKS) small_m_kernel(SmallArgs a
       const uint32_t n = sm_fast_div(flat, mt.div_mul, mt.div_shift);
       const uint32_t r = n - (uint32_t)(band * 64);
       const uint32_t k = flat - n * (uint32_t)K;
-      p[e] = ((r & 63u) << 10) | (k & 1023u);
+      // window word: bits 0-7 position of the column inside the staged chunk row, 8-11 row mod 16, 12-13 subtile
+      p[e] = (uint32_t)sm_xpos((int)(k & (uint32_t)(SM_KC - 1))) | ((r & 15u) << 8) | (((r >> 4) & 3u) << 12);
       vh[e] = (_Float16)pf_val[e];
       zh[e] = (_Float16)z[e];
     }
@@ -327,7 +323,6 @@ __global__ void __launch_bounds__(256, SM_MIN_BLOCKS) small_m_kernel(SmallArgs a
   for (int c = 0; c < nchunks; ++c) {
     const int kc = c * SM_KC;
     const _Float16* const xc = xs + (c & 1) * SM_ROWS * SM_XSTRIDE;
-    const float* const cc = corr + (c & 1) * 2 * SM_ROWS;
     const uint32_t tp2 = tp_at(c + 2);
 
     // ---- dense: stream this band's codes ----
@@ -338,12 +333,19 @@ __global__ void __launch_bounds__(256, SM_MIN_BLOCKS) small_m_kernel(SmallArgs a
 #pragma unroll
       for (int t = 0; t < 4; ++t)
         af[t] = *reinterpret_cast<const half8_t*>(xc + nn * SM_XSTRIDE + kbl * 128 + 32 * jj + 8 * t);
+      // FAST: minus the constant part of the un-centred codes, sum_k x[m,k] (1032 | 72) over the block, from
+      // one more MFMA chain against a constant operand; it seeds the four subtiles' chains.
       float4_t init = {0.0f, 0.0f, 0.0f, 0.0f};
-      if (FAST) init = *reinterpret_cast<const float4_t*>(cc + kbl * SM_ROWS + 4 * jj);
+      if (FAST) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) init = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[t], minus_offsets, init, 0, 0, 0);
+      }
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
-        const u32x4 q = qbuf[s];
-        load_q(s, 2 * c + kbl + 1);                         // the slot is free: fetch the next block's codes
+        constexpr int kRingMask = SM_RING - 1;
+        const int slot = (kbl & kRingMask) * 4 + s;
+        const u32x4 q = qbuf[slot];
+        load_q(slot, 2 * c + kbl + SM_RING);                // the slot is free: fetch the block SM_RING ahead
         _Float16 sh;
         if (FAST) {
           sh = __builtin_bit_cast(half4_t, sc[kbl])[s];
@@ -381,35 +383,40 @@ __global__ void __launch_bounds__(256, SM_MIN_BLOCKS) small_m_kernel(SmallArgs a
     // ---- sparse: this band's entries inside the chunk, 16 at a time (4 per k-group of the MFMA) ----
     {
       const uint32_t j_lo = __builtin_amdgcn_readfirstlane(tp0), j_hi = __builtin_amdgcn_readfirstlane(tp1);
-      const uint32_t kcm = (uint32_t)kc & 1023u;
+      const uint32_t span = j_hi - j_lo;
+      const _Float16* const xrow = xc + nn * SM_XSTRIDE;
       for (uint32_t g0 = j_lo & ~3u; g0 < j_hi; g0 += 16u) {
         // refilling here never overwrites an entry at or above g0: w_hi < g0 + 16 and SM_WIN + 16 <= SM_CAP
         while (w_hi < min(g0 + 16u, j_hi)) refill();
         const uint32_t e0 = g0 + 4u * (uint32_t)jj;
         const uint32_t ring = e0 & (uint32_t)(SM_CAP - 1);
         const u32x2 pw = *reinterpret_cast<const u32x2*>(my_winp + ring);
-        u32x2 vw = *reinterpret_cast<const u32x2*>(my_winv + ring);
-        u32x2 zw = *reinterpret_cast<const u32x2*>(my_winz + ring);
+        const u32x2 vw = *reinterpret_cast<const u32x2*>(my_winv + ring);
+        const u32x2 zw = *reinterpret_cast<const u32x2*>(my_winz + ring);
+        const uint32_t rel = e0 - j_lo;                      // wraps for entries before the chunk's first
         half4_t ax;
-        uint32_t d[4];
-#pragma unroll
+        uint32_t mlo[4], mhi[4];                            // entry i: 0xFFFF in halfword s of (mlo, mhi) iff this lane
+#pragma unroll                                              // owns the entry's row in subtile s
         for (int i = 0; i < 4; ++i) {
-          const uint32_t pos = (pw[i >> 1] >> (16 * (i & 1))) & 0xFFFFu;
-          const uint32_t kk = ((pos & 1023u) - kcm) & 1023u;
-          // a malformed layout must neither leave the staged chunk nor reach another row
-          const bool ok = e0 + i >= j_lo && e0 + i < j_hi && kk < (uint32_t)SM_KC;
-          ax[i] = xc[nn * SM_XSTRIDE + sm_xpos(ok ? (int)kk : 0)];
-          d[i] = ok ? ((pos >> 10) ^ (uint32_t)nn) : 0xFFFFu;     // 16 s for the lane that owns the entry's row
+          const uint32_t w = pw[i >> 1];
+          const int sh = 16 * (i & 1);
+          // Entries outside [j_lo, j_hi) are masked out below; their column field is < 256 whatever the
+          // window holds, so the gather stays inside the staged row.
+          ax[i] = xrow[__builtin_amdgcn_ubfe(w, sh, 8)];
+          const bool mine = rel + (uint32_t)i < span && __builtin_amdgcn_ubfe(w, sh + 8, 4) == (uint32_t)nn;
+          const uint32_t s16 = (w >> (sh + 8)) & 0x30u;     // 16 * subtile
+          const uint64_t m = (uint64_t)0xFFFFu << s16;
+          mlo[i] = mine ? (uint32_t)m : 0u;
+          mhi[i] = mine ? (uint32_t)(m >> 32) : 0u;
         }
-        const uint32_t dp[2] = {d[0] | (d[1] << 16), d[2] | (d[3] << 16)};
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
           u32x2 bv, bz;
 #pragma unroll
           for (int h = 0; h < 2; ++h) {
-            const u16x2 one = {1, 1};
-            const u16x2 ne = __builtin_elementwise_min(__builtin_bit_cast(u16x2, dp[h] ^ (uint32_t)(16 * s * 0x00010001)), one);
-            const uint32_t mask = __builtin_bit_cast(uint32_t, (u16x2)(ne - one));       // 0xFFFF where equal
+            const uint32_t ma = (s < 2) ? mlo[2 * h] : mhi[2 * h], mb = (s < 2) ? mlo[2 * h + 1] : mhi[2 * h + 1];
+            // halfword (s & 1) of ma -> low half, of mb -> high half
+            const uint32_t mask = __builtin_amdgcn_perm(mb, ma, (s & 1) ? 0x07060302u : 0x05040100u);
             bv[h] = vw[h] & mask;
             bz[h] = zw[h] & mask;
           }
@@ -499,7 +506,7 @@ __global__ void __launch_bounds__(256) upload_table_kernel(const uint32_t* __res
 // ---- host side -----------------------------------------------------------------------------
 
 static size_t small_lds_bytes() {
-  return (size_t)2 * SM_ROWS * SM_XSTRIDE * 2 + (size_t)2 * 2 * SM_ROWS * 4 + (size_t)3 * 4 * SM_CAP * 2;
+  return (size_t)2 * SM_ROWS * SM_XSTRIDE * 2 + (size_t)3 * 4 * SM_CAP * 2;
 }
 
 bool small_m_eligible(const szo_linear_desc* d) {

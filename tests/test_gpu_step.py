@@ -117,3 +117,18 @@ def test_bf16_tile_is_available_and_less_accurate_on_g():
     print("g error fp16 tile:", e16, "bf16 tile:", ebf)
     assert max(e16) <= 1e-2
     assert np.mean(ebf) > np.mean(e16)
+
+
+def test_kernel_timing_counts_forward_launches_only():
+    _, d = make_pair(3, 64, 256, 256, 32, 1e-3)
+    ws = szo.new_workspace()
+    scal = torch.zeros(3, dtype=torch.float64, device="cuda")
+    szo.szo_set_tile_config(0)
+    szo.szo_kernel_timing(True)
+    for s in range(3):
+        szo.szo_zo_step([d.desc(with_y=False)], 1, s, 1e-3, 1e-6, scal, ws, szo.STEP_FUSED_LOSS)
+    ms, n = szo.szo_kernel_timing_read()
+    szo.szo_kernel_timing(False)
+    assert n == 6 and 0.0 < ms < 100.0          # two forwards per step on the tiled path
+    szo.szo_zo_step([d.desc(with_y=False)], 1, 3, 1e-3, 1e-6, scal, ws, szo.STEP_FUSED_LOSS)
+    assert szo.szo_kernel_timing_read() == (0.0, 0)

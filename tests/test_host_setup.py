@@ -158,3 +158,10 @@ def test_hot_calls_validate_before_touching_the_gpu():
     assert szo.lib.szo_spsa_g(None, None, 0.1, None, None) == szo.EINVAL
     assert szo.lib.szo_zo_step(None, 1, 0, 0, 0.1, 0.1, None, None, 0, None) == szo.EINVAL
     assert szo.lib.szo_debug_zbar(0, -1, 0, 0, None, None, None) == szo.EINVAL
+
+
+def test_kernel_timing_calls_are_safe_without_any_launch():
+    szo.szo_kernel_timing(True)
+    assert szo.szo_kernel_timing_read() == (0.0, 0)
+    szo.szo_kernel_timing(False)
+    assert szo.lib.szo_kernel_timing_read(None, None) == szo.EINVAL
