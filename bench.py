@@ -82,6 +82,9 @@ def main():
     ap.add_argument("--density", type=float, default=None)
     ap.add_argument("--tile", default="f16", choices=["f16", "bf16"])
     ap.add_argument("--unfused-loss", action="store_true", help="write y and run the separate loss kernel")
+    ap.add_argument("--tile-config", type=int, default=0, choices=[0, 1, 2],
+                    help="0: the library chooses (few-token path for M <= 64); 1 / 2: force the tiled kernel with "
+                         "128x128 / 256x256 workgroup tiles (for comparisons)")
     ap.add_argument("--seed", type=int, default=2024)
     ap.add_argument("--data-seed", type=int, default=0)
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle baseline leg (0 = skip)")
@@ -108,7 +111,7 @@ def main():
     import torch
     from paper_2406_02913_amd import stack, synth, szo
 
-    few_default = (args.m or synth.WORKLOADS[args.workload]["M"]) <= 16
+    few_default = (args.m or synth.WORKLOADS[args.workload]["M"]) <= 64
     if args.steps is None:
         args.steps = 200 if few_default else 20
     if args.warmup is None:
@@ -134,6 +137,7 @@ def main():
     log(f"[bench] {len(mats)} matrices resident after {time.perf_counter() - t0:.1f} s, "
         f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB")
 
+    szo.szo_set_tile_config(args.tile_config)
     descs = szo.desc_array([m.desc(dt, with_y=bool(args.unfused_loss)) for m in mats])
     ws = szo.new_workspace()
     scal = torch.zeros(3, dtype=torch.float64, device="cuda")
@@ -162,7 +166,7 @@ def main():
     # ---- the dominant kernel alone: the library brackets every forward-kernel launch of a few more
     #      steps with events on the launch stream (szo_kernel_timing) ----
     fwd_flops = sum(2.0 * m.M * m.N * m.K for m in mats)
-    few = all(m.M <= 16 for m in mats) and dt == szo.TILE_F16       # the library's few-token path
+    few = all(m.M <= 64 for m in mats) and dt == szo.TILE_F16 and args.tile_config == 0   # the library's few-token path
     reps = args.steps if args.kernel_reps is None else max(1, args.kernel_reps)
     szo.szo_kernel_timing(True)
     for s in range(reps):
@@ -188,7 +192,7 @@ def main():
     else:
         roof = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None}
-    if (args.layers is None and args.m is None and args.density is None and flags and dt == szo.TILE_F16):
+    if (args.layers is None and args.m is None and args.density is None and flags and dt == szo.TILE_F16 and args.tile_config == 0):
         roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(args.workload)
     roof.update({"kernel": kernel, "avg_launch_us": round(1e3 * k_ms, 2), "launches_timed": launches,
                  "flops_per_launch": launch_flops, "bytes_per_launch": launch_bytes})

@@ -819,9 +819,8 @@ int szo_zo_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t ste
   int rc;
   // Few-token stacks: one pass over the weights serves both forwards of the step.
   bool few = fuse && g_tile_config == 0 && n > 0 && n <= kMaxStepMatrices;
-  for (int i = 0; few && i < n; ++i) few = small_m_eligible(&descs[i]) && descs[i].M == descs[0].M;
+  for (int i = 0; few && i < n; ++i) few = small_m_step_eligible(&descs[i]);
   if (few) {
-    if (small_m_table_bytes(n) > kTableBytesPerMatrix * (size_t)kMaxStepMatrices) return SZO_EUNSUPPORTED;
     return small_m_step(descs, n, seed, step, eps, lr, (char*)workspace + kWorkspaceTableOffset,
                         partial_area(workspace), scalars, true, true, s);
   }

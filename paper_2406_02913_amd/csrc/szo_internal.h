@@ -46,6 +46,7 @@ int reduce_step(const double* partials, int count, float eps, double* scalars, h
 
 // Few-token path (szo_smallm.hip): M <= 16, K % 128 == 0, fp16 tile.
 bool small_m_eligible(const szo_linear_desc* d);
+bool small_m_step_eligible(const szo_linear_desc* d);      // M <= 64: sliced into 16-token passes
 int small_m_blocks(const szo_linear_desc* d);
 size_t small_m_table_bytes(int n);
 int small_m_launch_one(const szo_linear_desc* d, uint64_t seed, uint64_t step, float eps, int sign, bool loss_mode,

@@ -28,6 +28,7 @@
 // The epilogue forms y(+-) and either stores y for the requested sign or folds the squared error
 // against the target into two fp64 partials per workgroup (one per sign).
 // Everything is accumulated in a fixed order: results are bit-reproducible.
+#include <algorithm>
 #include <cstddef>
 #include "szo_internal.h"
 #include "szo_rng.cuh"
@@ -64,6 +65,7 @@ struct SmallMat {
   uint64_t nnz_base;
   double loss_scale;
   int N, K;
+  int M;                    // token rows of this entry (<= 16): a matrix with more tokens is split into slices
   uint32_t nnz;
   int group_shift;
   uint32_t div_mul;
@@ -73,11 +75,12 @@ struct SmallMat {
   int64_t first_quad;       // Philox counters (groups of 4 entries) of earlier matrices: grouped update
 };
 
+static_assert(sizeof(SmallMat) <= kTableBytesPerMatrix, "table entries must fit the workspace's table area");
+
 struct SmallArgs {
   const SmallMat* table;    // device table of n_mats matrices, or null: use `one`
   SmallMat one;
   int n_mats;
-  int M;
   int store_sign;           // store mode: which forward to write (-1, 0, +1); loss mode: unused
   int loss_mode;            // 1: write loss partials for both signs, 0: store y
   uint64_t seed, step;
@@ -188,7 +191,7 @@ __global__ void __launch_bounds__(256, SM_MIN_BLOCKS) small_m_kernel(SmallArgs a
   float __attribute__((address_space(1)))* const g_y = (float __attribute__((address_space(1)))*)mt.y;
   const int strip = bid - mt.first_block;
   const int n0 = strip * SM_BN;
-  const int N = mt.N, K = mt.K, M = a.M;
+  const int N = mt.N, K = mt.K, M = mt.M;
   const int ktiles = K >> 6;
   const int band = (n0 >> 6) + wave;                        // band of the sparse layout owned by this wave
   const bool band_ok = band * 64 < N && mt.nnz > 0;
@@ -518,6 +521,15 @@ bool small_m_eligible(const szo_linear_desc* d) {
 // group of 128 (one scale per 128-column block): the fast instantiation
 static bool small_m_fast(const szo_linear_desc* d) { return d->group == 128; }
 
+// The step also takes matrices with up to 64 tokens: they run as up to four 16-token slices, each a
+// pass of its own over the weights (still cheaper than the tiled kernel at these sizes).
+bool small_m_step_eligible(const szo_linear_desc* d) {
+  if (d->M < 1 || d->M > 4 * SM_ROWS) return false;
+  szo_linear_desc one = *d;
+  one.M = 1;
+  return small_m_eligible(&one);
+}
+
 int small_m_blocks(const szo_linear_desc* d) { return (int)((d->N + SM_BN - 1) / SM_BN); }
 
 size_t small_m_table_bytes(int n) { return sizeof(SmallMat) * (size_t)n; }
@@ -528,7 +540,7 @@ static void fill_mat(SmallMat& m, const szo_linear_desc* d) {
   m.target = (const uint16_t*)d->target; m.y = d->y;
   m.nnz_base = d->nnz_base;
   m.loss_scale = 1.0 / ((double)d->M * (double)d->N);
-  m.N = (int)d->N; m.K = (int)d->K; m.nnz = (uint32_t)d->nnz;
+  m.N = (int)d->N; m.K = (int)d->K; m.M = (int)d->M; m.nnz = (uint32_t)d->nnz;
   int gs = 0;
   while ((1 << gs) < d->group) ++gs;
   m.group_shift = gs;
@@ -558,7 +570,7 @@ int small_m_launch_one(const szo_linear_desc* d, uint64_t seed, uint64_t step, f
   if (rc != SZO_OK) return rc;
   SmallArgs a{};
   fill_mat(a.one, d);
-  a.table = nullptr; a.n_mats = 1; a.M = (int)d->M;
+  a.table = nullptr; a.n_mats = 1;
   a.store_sign = sign; a.loss_mode = loss_mode ? 1 : 0;
   a.seed = seed; a.step = step; a.eps = eps;
   a.partial_plus = partial_plus; a.partial_minus = partial_minus;
@@ -590,12 +602,15 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
   Slot& slot = ring[turn++ & 3];
   if (slot.used) SZO_HIP(hipEventSynchronize(slot.copied));
   if (!slot.copied) SZO_HIP(hipEventCreateWithFlags(&slot.copied, hipEventDisableTiming));
-  if (n > slot.cap) {
+  int max_entries = 0;
+  for (int i = 0; i < n; ++i) max_entries += do_forward ? (int)((descs[i].M + SM_ROWS - 1) / SM_ROWS) : 1;
+  if (small_m_table_bytes(max_entries) > kTableBytesPerMatrix * (size_t)kMaxStepMatrices) return SZO_EUNSUPPORTED;
+  if (max_entries > slot.cap) {
     if (slot.host) (void)hipHostFree(slot.host);
     slot.host = nullptr; slot.cap = 0;
-    SZO_HIP(hipHostMalloc((void**)&slot.host, sizeof(SmallMat) * (size_t)n, hipHostMallocMapped));
+    SZO_HIP(hipHostMalloc((void**)&slot.host, sizeof(SmallMat) * (size_t)max_entries, hipHostMallocMapped));
     SZO_HIP(hipHostGetDevicePointer((void**)&slot.host_dev, slot.host, 0));
-    slot.cap = n;
+    slot.cap = max_entries;
   }
   SmallMat* const host = slot.host;
   // order: matrices of the fast instantiation first (by K descending), then the others (by K descending)
@@ -613,31 +628,39 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
     }
     order[j + 1] = o;
   }
-  int n128 = 0, blocks128 = 0, blocks_other = 0, partials = 0;
+  int n128 = 0, blocks128 = 0, blocks_other = 0, partials = 0, entries = 0;
   int64_t quads = 0;
   for (int r = 0; r < n; ++r) {
     const szo_linear_desc* d = &descs[order[r]];
-    SmallMat& m = host[r];
-    fill_mat(m, d);
     const bool g128 = small_m_fast(d);
-    m.first_block = g128 ? blocks128 : blocks_other;
-    m.partial_base = partials;
-    m.first_quad = quads;
-    const int b = small_m_blocks(d);
-    if (g128) { blocks128 += b; ++n128; } else blocks_other += b;
-    partials += b;
+    // forward: one table entry per slice of 16 token rows; update only: one entry per matrix
+    const int slices = do_forward ? (int)((d->M + SM_ROWS - 1) / SM_ROWS) : 1;
+    for (int sl = 0; sl < slices; ++sl) {
+      SmallMat& m = host[entries++];
+      fill_mat(m, d);
+      if (do_forward) {
+        m.x += (size_t)sl * SM_ROWS * (size_t)d->K;
+        m.target += (size_t)sl * SM_ROWS * (size_t)d->N;
+        m.M = (int)std::min<int64_t>(SM_ROWS, d->M - (int64_t)sl * SM_ROWS);
+      }
+      m.first_block = g128 ? blocks128 : blocks_other;
+      m.partial_base = partials;
+      m.first_quad = quads;          // every slice of a matrix: the update finds the last one, once
+      const int b = small_m_blocks(d);
+      if (g128) { blocks128 += b; ++n128; } else blocks_other += b;
+      partials += b;
+    }
     quads += ((int64_t)d->nnz + 3) / 4;
   }
   if (do_forward && 2 * (int64_t)partials > kMaxLossPartials) return SZO_EUNSUPPORTED;
   {
-    const int words = (int)(sizeof(SmallMat) * (size_t)n / 4);
+    const int words = (int)(sizeof(SmallMat) * (size_t)entries / 4);
     upload_table_kernel<<<(words + 255) / 256, 256, 0, stream>>>(slot.host_dev, (uint32_t*)table_dev, words);
     SZO_LAUNCH_CHECK();
   }
   SZO_HIP(hipEventRecord(slot.copied, stream));
   slot.used = true;
   SmallArgs a{};
-  a.M = (int)descs[0].M;
   a.store_sign = 1; a.loss_mode = 1;
   a.seed = seed; a.step = step; a.eps = eps;
   a.partial_plus = partial_plus; a.partial_minus = partial_plus + partials;
@@ -650,7 +673,7 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
     if ((rc = timing_end(stream)) != SZO_OK) return rc;
   }
   if (do_forward && blocks_other > 0) {
-    a.table = tdev + n128; a.n_mats = n - n128;
+    a.table = tdev + n128; a.n_mats = entries - n128;
     if ((rc = timing_begin(stream)) != SZO_OK) return rc;
     small_m_kernel<false><<<blocks_other, 256, small_lds_bytes(), stream>>>(a);
     SZO_LAUNCH_CHECK();
@@ -663,7 +686,7 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
   if (do_update && quads > 0) {
     const int64_t ub = (quads + 255) / 256;
     if (ub > 0x7FFFFFFF) return SZO_EUNSUPPORTED;
-    sparse_update_table_kernel<<<(unsigned)ub, 256, 0, stream>>>(tdev, n, quads, seed, step, scalars + 2, lr);
+    sparse_update_table_kernel<<<(unsigned)ub, 256, 0, stream>>>(tdev, entries, quads, seed, step, scalars + 2, lr);
     SZO_LAUNCH_CHECK();
   }
   return SZO_OK;

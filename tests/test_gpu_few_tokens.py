@@ -132,3 +132,35 @@ def test_one_full_size_block_at_16_tokens_two_steps():
         dv_gpu = dd.sp_val.cpu().numpy().astype(np.float64) - o.sp_val
         dv_ref = om.sp_val.astype(np.float64) - o.sp_val
         assert np.linalg.norm(dv_gpu - dv_ref) <= 3e-2 * np.linalg.norm(dv_ref) + 1e-12
+
+
+def test_step_with_up_to_64_tokens_runs_as_16_token_slices():
+    """17..64 tokens: the step streams the weights once per slice of 16 token rows; matrices of
+    different token counts may share a step, and the sparse values are updated exactly once."""
+    szo.szo_set_tile_config(0)
+    o1, d1 = make_pair(51, 64, 320, 512, 128, 2e-3, nnz_base=0)
+    b2 = (o1.sp_idx.size + 3) // 4 * 4
+    o2, d2 = make_pair(52, 40, 256, 384, 64, 5e-3, nnz_base=b2)          # ragged last slice, plain instantiation
+    b3 = b2 + (o2.sp_idx.size + 3) // 4 * 4
+    o3, d3 = make_pair(53, 16, 128, 256, 128, 1e-2, nnz_base=b3)
+    ws = szo.new_workspace()
+    scal = torch.zeros(3, dtype=torch.float64, device="cuda")
+    os_, ds_ = [o1, o2, o3], [d1, d2, d3]
+    ref = [clone(o) for o in os_]
+    sg = sigma_g(os_)
+    descs = szo.desc_array([d.desc(with_y=False) for d in ds_])
+    szo.szo_kernel_timing(True)
+    for s in range(3):
+        szo.szo_zo_step(descs, 23, s, 1e-3, 1e-3, scal, ws, szo.STEP_FUSED_LOSS)
+        lp, lm, g = scal.cpu().numpy()
+        r = ozo.zo_step(ref, 23, s, 1e-3, 1e-3)
+        assert abs(lp - r["loss_plus"]) <= 1e-4 * r["loss_plus"]
+        assert abs(lm - r["loss_minus"]) <= 1e-4 * r["loss_minus"]
+        assert abs(g - r["g"]) <= 1e-2 * max(abs(r["g"]), sg), (s, g, r["g"], sg)
+    _, launches = szo.szo_kernel_timing_read()
+    szo.szo_kernel_timing(False)
+    assert launches == 6                       # few-token path: one launch per instantiation and step
+    for om, dd, o in zip(ref, ds_, os_):
+        dv_gpu = dd.sp_val.cpu().numpy().astype(np.float64) - o.sp_val
+        dv_ref = om.sp_val.astype(np.float64) - o.sp_val
+        assert np.linalg.norm(dv_gpu - dv_ref) <= 3e-2 * np.linalg.norm(dv_ref)
