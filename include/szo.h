@@ -129,7 +129,9 @@ int szo_sparse_update(float* sp_val, const uint32_t* sp_idx, int64_t nnz, uint64
 /* One whole step over `n` layers: for every layer a +eps forward and a -eps forward, each
  * followed by its loss with scale 1/(M*N); then g; then the update of every layer.
  * scalars: device double[3], overwritten with (L+, L-, g).  flags: bit 0 set = use the
- * loss-fusing forward and never write y (desc->y may then be NULL).
+ * loss-fusing forward and never write y (desc->y may then be NULL); large steps then run all
+ * forwards (every layer, both signs) as one launch driven by a descriptor table that is staged in
+ * the workspace, and steps with at most 64 tokens per layer stream the weights once for both signs.
  * descs: host array.  Everything is enqueued on `stream`; no host synchronisation. */
 #define SZO_STEP_FUSED_LOSS 1
 int szo_zo_step(const szo_linear_desc* descs /* host */, int n, uint64_t seed, uint64_t step,
@@ -203,8 +205,10 @@ int szo_debug_zbar(uint64_t nnz_base, int64_t nnz, uint64_t seed, uint64_t step,
                    uint32_t* words_out, float* z_out, void* stream);
 
 /* Tuning/testing hook: which workgroup tile the forward uses.  0 = chosen from the shape
- * (default), 1 = 128x128 outputs with 4 waves, 2 = 256x256 outputs with 8 waves.  Process-wide,
- * not thread-safe; results do not depend on it beyond fp32 summation order. */
+ * (default; also enables the few-token path for M <= 64), 1 = 128x128 outputs with 4 waves,
+ * 2 = 256x256 outputs with 8 waves, 3 = as 2 and szo_zo_step always launches all forwards of a
+ * step as one grid (with 0 and 2 it does so only when the step has at least 192 tiles).
+ * Process-wide, not thread-safe; results do not depend on it beyond fp32 summation order. */
 int szo_set_tile_config(int config);
 
 /* HIP error code of the most recent SZO_ELAUNCH on this thread (0 if none). */

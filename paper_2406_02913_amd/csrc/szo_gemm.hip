@@ -21,6 +21,8 @@
 // them 256 at a time (one Philox counter = four consecutive entries per lane) into a small
 // LDS window holding (tile position, value), and each K step only copies the few entries of
 // its tile from the window into the weight tile.
+#include <cstddef>
+#include <vector>
 #include "szo_internal.h"
 #include "szo_rng.cuh"
 #include <type_traits>
@@ -58,6 +60,8 @@ struct FwdParams {
   float signed_eps;         // sign * eps; 0 = no perturbation
   double* partials;         // fused loss: one scaled partial per workgroup, [grid_m*grid_n]
   double loss_scale;
+  int first_block;          // grouped launch: id of this entry's first workgroup (a multiple of 8)
+  int pad_;
 };
 
 // floor(v / d) for 32-bit v with a precomputed multiplier (Granlund-Montgomery, round-up form).
@@ -169,8 +173,11 @@ template <> struct Frag<SZO_TILE_BF16> {
 // the compiler from regrouping the slots.  Global loads are in place: as soon as a unit's
 // registers have been consumed they are reloaded with the same unit of the tile after next,
 // which gives every load one full K step (about a microsecond) to arrive.
+// `bid` is the workgroup's id inside this forward (0 .. grid_m*grid_n - 1); its residue mod 8 is the
+// XCD the workgroup runs on, both in a launch of its own and in a grouped launch (entries start at
+// multiples of 8).
 template <int WAVES_M, int WAVES_N, int WMB, int WNB, int DT, bool FUSE_LOSS>
-__global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdParams p) {
+__device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bid) {
   constexpr int NWAVES = WAVES_M * WAVES_N;
   constexpr int BM = 32 * WMB * WAVES_M, BN = 32 * WNB * WAVES_N;
   constexpr int W_WAVES = BN / 64;                 // one per 64-row band of the weight tile
@@ -208,7 +215,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdP
   int bm, bn;
   {
     const int G = p.grid_m * p.grid_n, q = G >> 3, r = G & 7;
-    const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
+    const int xcd = bid & 7, idx = bid >> 3;
     const int L = xcd * q + min(xcd, r) + idx;
     const int width = 4 * p.grid_n, g = L / width, first_m = 4 * g;
     const int gsize = min(p.grid_m - first_m, 4), rem = L - g * width;
@@ -634,14 +641,43 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdP
       double b = 0.0;
 #pragma unroll
       for (int i = 0; i < NWAVES; ++i) b += scratch[i];
-      p.partials[blockIdx.x] = b * p.loss_scale;
+      p.partials[bid] = b * p.loss_scale;
     }
   }
 }
 
+template <int WAVES_M, int WAVES_N, int WMB, int WNB, int DT, bool FUSE_LOSS>
+__global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdParams p) {
+  linear_fwd_body<WAVES_M, WAVES_N, WMB, WNB, DT, FUSE_LOSS>(p, (int)blockIdx.x);
+}
+
+// Grouped launch: every forward of a step (all matrices, both signs) in one grid, so that the only
+// partly filled round of workgroups is the last one of the step, not the last one of every matrix.
+// `table` holds one FwdParams per forward, ordered by first_block; a workgroup finds its entry by
+// binary search and reads it through the constant address space (scalar loads into scalar registers).
+// Workgroups between an entry's last tile and the next multiple of 8 have nothing to do.
+template <int WAVES_M, int WAVES_N, int WMB, int WNB, int DT, bool FUSE_LOSS>
+__global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_table_kernel(const FwdParams* table, int n_entries) {
+  constexpr int W = (int)(sizeof(FwdParams) / 4), FB = (int)(offsetof(FwdParams, first_block) / 4);
+  static_assert(sizeof(FwdParams) % 4 == 0 && offsetof(FwdParams, first_block) % 4 == 0, "table entry is read as words");
+  const auto* tab = (const uint32_t __attribute__((address_space(4)))*)table;
+  int lo = 0, hi = n_entries - 1;                           // last entry whose first_block <= blockIdx.x
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if ((int)tab[mid * W + FB] <= (int)blockIdx.x) lo = mid; else hi = mid - 1;
+  }
+  struct Words { uint32_t w[W]; } raw;
+#pragma unroll
+  for (int i = 0; i < W; ++i) raw.w[i] = tab[lo * W + i];
+  const FwdParams p = __builtin_bit_cast(FwdParams, raw);
+  const int bid = (int)blockIdx.x - p.first_block;
+  if (bid >= p.grid_m * p.grid_n) return;
+  linear_fwd_body<WAVES_M, WAVES_N, WMB, WNB, DT, FUSE_LOSS>(p, bid);
+}
+
 // ---- host side -----------------------------------------------------------------------------
 
-static int g_tile_config = 0;      // 0 = choose by shape, 1 = 128x128 (4 waves), 2 = 256x256 (8 waves)
+static int g_tile_config = 0;      // 0 = choose by shape, 1 = 128x128 (4 waves), 2 = 256x256 (8 waves), 3 = 2 + always group the step
 
 static int ilog2_exact(int v) {
   int s = 0;
@@ -703,6 +739,7 @@ static int plan_tiles(int M, int N, int* blocks_out) {
     const int64_t big_blocks = (int64_t)((M + 255) / 256) * ((N + 255) / 256);
     cfg = big_blocks >= 192 ? 2 : 1;
   }
+  if (cfg == 3) cfg = 2;
   const int t = cfg == 2 ? 256 : 128;
   const int64_t blocks = (int64_t)((M + t - 1) / t) * ((N + t - 1) / t);
   *blocks_out = blocks > 0x7FFFFFFF ? -1 : (int)blocks;
@@ -718,11 +755,9 @@ static int dispatch_tile(FwdParams& p, hipStream_t stream) {
 
 // Enqueues one forward.  With `partials` set the loss is fused: workgroup b stores
 // scale * sum (y - target)^2 of its tile to partials[b].
-static int run_forward(const szo_linear_desc* d, uint64_t seed, uint64_t step, int sign, float eps,
-                       double* partials, double scale, hipStream_t stream) {
-  const bool fuse = partials != nullptr;
-  if (d->M == 0 || d->N == 0) return SZO_OK;
-  FwdParams p{};
+static int fill_params(FwdParams& p, const szo_linear_desc* d, uint64_t seed, uint64_t step, int sign, float eps,
+                       double* partials, double scale) {
+  p = FwdParams{};
   p.x = (const uint16_t*)d->x;
   p.qweight = d->qweight;
   p.scales = (const uint16_t*)d->scales;
@@ -748,12 +783,89 @@ static int run_forward(const szo_linear_desc* d, uint64_t seed, uint64_t step, i
   p.signed_eps = (float)sign * eps;
   p.partials = partials;
   p.loss_scale = scale;
+  return SZO_OK;
+}
+
+static int run_forward(const szo_linear_desc* d, uint64_t seed, uint64_t step, int sign, float eps,
+                       double* partials, double scale, hipStream_t stream) {
+  const bool fuse = partials != nullptr;
+  if (d->M == 0 || d->N == 0) return SZO_OK;
+  FwdParams p;
+  const int frc = fill_params(p, d, seed, step, sign, eps, partials, scale);
+  if (frc != SZO_OK) return frc;
   if (d->tile_dtype == SZO_TILE_F16)
     return fuse ? dispatch_tile<SZO_TILE_F16, true>(p, stream) : dispatch_tile<SZO_TILE_F16, false>(p, stream);
   return fuse ? dispatch_tile<SZO_TILE_BF16, true>(p, stream) : dispatch_tile<SZO_TILE_BF16, false>(p, stream);
 }
 
 static double* partial_area(void* workspace) { return (double*)((char*)workspace + kWorkspaceHeader); }
+
+template <int DT>
+static int launch_table(const FwdParams* table_dev, int entries, int64_t blocks, hipStream_t stream) {
+  constexpr int BM = 256, BN = 256;
+  constexpr size_t main_bytes = 2 * (size_t)(BM + BN) * BK * sizeof(uint16_t) + (size_t)(BN / 64) * (kWindow * 6 + 128);
+  constexpr size_t target_bytes = (size_t)BM * (BN * 2 + 32);
+  constexpr size_t lds_bytes = main_bytes > target_bytes ? main_bytes : target_bytes;
+  auto kern = linear_fwd_table_kernel<2, 4, 4, 2, DT, true>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    SZO_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
+    attr_set = true;
+  }
+  int rc = timing_begin(stream);
+  if (rc != SZO_OK) return rc;
+  kern<<<(unsigned)blocks, 512, lds_bytes, stream>>>(table_dev, entries);
+  SZO_LAUNCH_CHECK();
+  return timing_end(stream);
+}
+
+// Both forwards of every matrix of a step as ONE launch of 256x256 tiles with the loss fused.
+// Returns SZO_EUNSUPPORTED when the stack does not qualify (the caller then launches per matrix):
+// mixed tile types, a table that does not fit the workspace, or too few tiles to fill the chip.
+// On success *partials_per_sign is the number of loss partials of one sign: the "+" partials are
+// partials[0 .. T), the "-" partials partials[T .. 2T).
+static int grouped_forwards(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t step, float eps,
+                            void* table_dev, double* partials, int64_t* partials_per_sign, hipStream_t stream) {
+  if (g_tile_config == 1) return SZO_EUNSUPPORTED;
+  int64_t T = 0;
+  int live = 0;
+  for (int i = 0; i < n; ++i) {
+    const szo_linear_desc* d = &descs[i];
+    if (d->M == 0 || d->N == 0) continue;
+    if (d->tile_dtype != descs[0].tile_dtype) return SZO_EUNSUPPORTED;
+    T += (int64_t)((d->M + 255) / 256) * ((d->N + 255) / 256);
+    ++live;
+  }
+  if ((T < 192 && g_tile_config != 3) || T == 0 || 2 * T > kMaxLossPartials) return SZO_EUNSUPPORTED;
+  if (sizeof(FwdParams) * (size_t)(2 * live) > kTableBytesPerMatrix * (size_t)kMaxStepMatrices) return SZO_EUNSUPPORTED;
+  static thread_local std::vector<FwdParams> table;
+  table.clear();
+  int64_t first_block = 0, offset = 0;
+  for (int i = 0; i < n; ++i) {
+    const szo_linear_desc* d = &descs[i];
+    if (d->M == 0 || d->N == 0) continue;
+    const double scale = 1.0 / ((double)d->M * (double)d->N);
+    const int gm = (int)((d->M + 255) / 256), gn = (int)((d->N + 255) / 256);
+    for (int pass = 0; pass < 2; ++pass) {                  // "+" then "-": the pair shares x and the codes in L2
+      FwdParams p;
+      const int rc = fill_params(p, d, seed, step, pass == 0 ? +1 : -1, eps, partials + (pass == 0 ? 0 : T) + offset, scale);
+      if (rc != SZO_OK) return rc;
+      p.grid_m = gm; p.grid_n = gn;
+      p.y = nullptr;                                        // the step's fused path never writes y
+      p.first_block = (int)first_block;
+      table.push_back(p);
+      first_block += ((int64_t)gm * gn + 7) & ~(int64_t)7;
+      if (first_block > 0x7FFFFFFF) return SZO_EUNSUPPORTED;
+    }
+    offset += (int64_t)gm * gn;
+  }
+  int rc = stage_table(table.data(), sizeof(FwdParams) * table.size(), table_dev, stream);
+  if (rc != SZO_OK) return rc;
+  *partials_per_sign = T;
+  if (descs[0].tile_dtype == SZO_TILE_F16)
+    return launch_table<SZO_TILE_F16>((const FwdParams*)table_dev, (int)table.size(), first_block, stream);
+  return launch_table<SZO_TILE_BF16>((const FwdParams*)table_dev, (int)table.size(), first_block, stream);
+}
 
 }  // namespace szo
 
@@ -762,7 +874,7 @@ using namespace szo;
 extern "C" {
 
 int szo_set_tile_config(int config) {
-  if (config < 0 || config > 2) return SZO_EINVAL;
+  if (config < 0 || config > 3) return SZO_EINVAL;
   g_tile_config = config;
   return SZO_OK;
 }
@@ -824,33 +936,48 @@ int szo_zo_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t ste
     return small_m_step(descs, n, seed, step, eps, lr, (char*)workspace + kWorkspaceTableOffset,
                         partial_area(workspace), scalars, true, true, s);
   }
-  if (fuse && 2 * total > kMaxLossPartials) return SZO_EUNSUPPORTED;
-  if (!fuse) {
-    rc = zero_words(scalars, 6, s);      // a fill kernel, not a memset node: safe under graph capture
-    if (rc != SZO_OK) return rc;
-  }
-  for (int pass = 0; pass < 2; ++pass) {
-    const int sign = pass == 0 ? +1 : -1;
-    double* part = partial_area(workspace) + (size_t)pass * (size_t)total;
-    for (int i = 0; i < n; ++i) {
-      const szo_linear_desc* d = &descs[i];
-      if (d->M == 0 || d->N == 0) continue;
-      const double scale = 1.0 / ((double)d->M * (double)d->N);
-      if (fuse) {
-        int blocks;
-        plan_tiles((int)d->M, (int)d->N, &blocks);
-        rc = run_forward(d, seed, step, sign, eps, part, scale, s);
-        part += blocks;
-      } else {
-        rc = run_forward(d, seed, step, sign, eps, nullptr, 0.0, s);
-        if (rc == SZO_OK) rc = szo_mse_loss(d->y, d->target, d->M * d->N, scale, scalars + pass, workspace, s);
-      }
+  bool grouped = false;
+  if (fuse) {
+    int64_t T = 0;
+    rc = grouped_forwards(descs, n, seed, step, eps, (char*)workspace + kWorkspaceTableOffset, partial_area(workspace),
+                          &T, s);
+    if (rc == SZO_OK) {
+      grouped = true;
+      rc = reduce_step(partial_area(workspace), (int)T, eps, scalars, s);
       if (rc != SZO_OK) return rc;
+    } else if (rc != SZO_EUNSUPPORTED) {
+      return rc;
     }
   }
-  rc = fuse ? reduce_step(partial_area(workspace), (int)total, eps, scalars, s)
-            : szo_spsa_g(scalars, scalars + 1, eps, scalars + 2, s);
-  if (rc != SZO_OK) return rc;
+  if (!grouped) {
+    if (fuse && 2 * total > kMaxLossPartials) return SZO_EUNSUPPORTED;
+    if (!fuse) {
+      rc = zero_words(scalars, 6, s);      // a fill kernel, not a memset node: safe under graph capture
+      if (rc != SZO_OK) return rc;
+    }
+    for (int pass = 0; pass < 2; ++pass) {
+      const int sign = pass == 0 ? +1 : -1;
+      double* part = partial_area(workspace) + (size_t)pass * (size_t)total;
+      for (int i = 0; i < n; ++i) {
+        const szo_linear_desc* d = &descs[i];
+        if (d->M == 0 || d->N == 0) continue;
+        const double scale = 1.0 / ((double)d->M * (double)d->N);
+        if (fuse) {
+          int blocks;
+          plan_tiles((int)d->M, (int)d->N, &blocks);
+          rc = run_forward(d, seed, step, sign, eps, part, scale, s);
+          part += blocks;
+        } else {
+          rc = run_forward(d, seed, step, sign, eps, nullptr, 0.0, s);
+          if (rc == SZO_OK) rc = szo_mse_loss(d->y, d->target, d->M * d->N, scale, scalars + pass, workspace, s);
+        }
+        if (rc != SZO_OK) return rc;
+      }
+    }
+    rc = fuse ? reduce_step(partial_area(workspace), (int)total, eps, scalars, s)
+              : szo_spsa_g(scalars, scalars + 1, eps, scalars + 2, s);
+    if (rc != SZO_OK) return rc;
+  }
   // one grouped update launch for the whole stack (per-matrix launches when the table does not fit)
   if (small_m_table_bytes(n) <= kTableBytesPerMatrix * (size_t)kMaxStepMatrices)
     return small_m_step(descs, n, seed, step, eps, lr, (char*)workspace + kWorkspaceTableOffset, nullptr, scalars,

@@ -61,6 +61,13 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
 int timing_begin(hipStream_t stream);
 int timing_end(hipStream_t stream);
 
+// Copies `bytes` (a multiple of 4) of host data into device memory `dst`, in stream order, without
+// blocking the host: the data goes through a ring of four pinned, device-mapped host buffers (grown
+// on demand with hipHostMalloc) and a small copy kernel reads it from there.  A kernel rather than a
+// DMA copy because handing over from the copy engine to the compute queue costs more than reading a
+// few tens of KB over the host link.  Defined in szo_kernels.hip.
+int stage_table(const void* src, size_t bytes, void* dst, hipStream_t stream);
+
 // Sets n 32-bit words to zero with a small kernel (defined in szo_kernels.hip).
 int zero_words(void* p, int n, hipStream_t stream);
 

@@ -1,5 +1,6 @@
 // Small kernels of the step: the Gaussian inspection kernel, the stand-in MSE loss, the SPSA
 // scalar (Definition 1) and the sparse ZO-SGD update (Section 3.4, fixed-parameter update rule).
+#include <cstring>
 #include <vector>
 #include "szo_internal.h"
 #include "szo_rng.cuh"
@@ -137,6 +138,39 @@ int reduce_partials(const double* partials, int count, double* loss_acc, hipStre
 int reduce_step(const double* partials, int count, float eps, double* scalars, hipStream_t stream) {
   reduce_step_kernel<<<1, 1024, 0, stream>>>(partials, count, eps, scalars);
   SZO_LAUNCH_CHECK();
+  return SZO_OK;
+}
+
+__global__ void __launch_bounds__(256) stage_copy_kernel(const uint32_t* __restrict__ src, uint32_t* __restrict__ dst, int words) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < words) dst[i] = src[i];
+}
+
+int stage_table(const void* src, size_t bytes, void* dst, hipStream_t stream) {
+  if (bytes == 0) return SZO_OK;
+  if (bytes & 3) return SZO_EINVAL;
+  // A ring of four, so that the host may run a few steps ahead of the GPU; a slot is reused only
+  // after the copy kernel that read it has executed.
+  struct Slot { void* host; const uint32_t* host_dev; size_t cap; hipEvent_t copied; bool used; };
+  static thread_local Slot ring[4] = {};
+  static thread_local unsigned turn = 0;
+  Slot& slot = ring[turn++ & 3];
+  if (slot.used) SZO_HIP(hipEventSynchronize(slot.copied));
+  if (!slot.copied) SZO_HIP(hipEventCreateWithFlags(&slot.copied, hipEventDisableTiming));
+  if (bytes > slot.cap) {
+    if (slot.host) (void)hipHostFree(slot.host);
+    slot.host = nullptr; slot.cap = 0;
+    const size_t cap = (bytes + 4095) & ~(size_t)4095;
+    SZO_HIP(hipHostMalloc(&slot.host, cap, hipHostMallocMapped));
+    SZO_HIP(hipHostGetDevicePointer((void**)&slot.host_dev, slot.host, 0));
+    slot.cap = cap;
+  }
+  memcpy(slot.host, src, bytes);
+  const int words = (int)(bytes / 4);
+  stage_copy_kernel<<<(words + 255) / 256, 256, 0, stream>>>(slot.host_dev, (uint32_t*)dst, words);
+  SZO_LAUNCH_CHECK();
+  SZO_HIP(hipEventRecord(slot.copied, stream));
+  slot.used = true;
   return SZO_OK;
 }
 

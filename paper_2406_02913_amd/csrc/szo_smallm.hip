@@ -30,6 +30,7 @@
 // Everything is accumulated in a fixed order: results are bit-reproducible.
 #include <algorithm>
 #include <cstddef>
+#include <vector>
 #include "szo_internal.h"
 #include "szo_rng.cuh"
 
@@ -498,14 +499,6 @@ __global__ void __launch_bounds__(256) sparse_update_table_kernel(const SmallMat
   }
 }
 
-// Copies the step's table from pinned host memory (mapped into the device's address space) into
-// the workspace.  A kernel rather than a DMA copy: the hand-over from the copy engine to the
-// compute queue costs more than reading a few tens of KB over the host link from a kernel.
-__global__ void __launch_bounds__(256) upload_table_kernel(const uint32_t* __restrict__ src, uint32_t* __restrict__ dst, int words) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i < words) dst[i] = src[i];
-}
-
 // ---- host side -----------------------------------------------------------------------------
 
 static size_t small_lds_bytes() {
@@ -594,25 +587,12 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
   int rc = set_small_attrs();
   if (rc != SZO_OK) return rc;
   if (n > 4096) return SZO_EUNSUPPORTED;
-  // Pinned staging for the table: a ring of four, so that the host may run a few steps ahead of
-  // the GPU; a slot is reused only after the copy that read it has executed.
-  struct Slot { SmallMat* host; const uint32_t* host_dev; int cap; hipEvent_t copied; bool used; };   // host_dev: device address of host
-  static thread_local Slot ring[4] = {};
-  static thread_local unsigned turn = 0;
-  Slot& slot = ring[turn++ & 3];
-  if (slot.used) SZO_HIP(hipEventSynchronize(slot.copied));
-  if (!slot.copied) SZO_HIP(hipEventCreateWithFlags(&slot.copied, hipEventDisableTiming));
   int max_entries = 0;
   for (int i = 0; i < n; ++i) max_entries += do_forward ? (int)((descs[i].M + SM_ROWS - 1) / SM_ROWS) : 1;
   if (small_m_table_bytes(max_entries) > kTableBytesPerMatrix * (size_t)kMaxStepMatrices) return SZO_EUNSUPPORTED;
-  if (max_entries > slot.cap) {
-    if (slot.host) (void)hipHostFree(slot.host);
-    slot.host = nullptr; slot.cap = 0;
-    SZO_HIP(hipHostMalloc((void**)&slot.host, sizeof(SmallMat) * (size_t)max_entries, hipHostMallocMapped));
-    SZO_HIP(hipHostGetDevicePointer((void**)&slot.host_dev, slot.host, 0));
-    slot.cap = max_entries;
-  }
-  SmallMat* const host = slot.host;
+  static thread_local std::vector<SmallMat> host_table;
+  host_table.resize((size_t)max_entries);
+  SmallMat* const host = host_table.data();
   // order: matrices of the fast instantiation first (by K descending), then the others (by K descending)
   int order[4096];
   for (int i = 0; i < n; ++i) order[i] = i;
@@ -653,13 +633,8 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
     quads += ((int64_t)d->nnz + 3) / 4;
   }
   if (do_forward && 2 * (int64_t)partials > kMaxLossPartials) return SZO_EUNSUPPORTED;
-  {
-    const int words = (int)(sizeof(SmallMat) * (size_t)entries / 4);
-    upload_table_kernel<<<(words + 255) / 256, 256, 0, stream>>>(slot.host_dev, (uint32_t*)table_dev, words);
-    SZO_LAUNCH_CHECK();
-  }
-  SZO_HIP(hipEventRecord(slot.copied, stream));
-  slot.used = true;
+  rc = stage_table(host, sizeof(SmallMat) * (size_t)entries, table_dev, stream);
+  if (rc != SZO_OK) return rc;
   SmallArgs a{};
   a.store_sign = 1; a.loss_mode = 1;
   a.seed = seed; a.step = step; a.eps = eps;

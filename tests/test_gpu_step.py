@@ -132,3 +132,46 @@ def test_kernel_timing_counts_forward_launches_only():
     assert n == 6 and 0.0 < ms < 100.0          # two forwards per step on the tiled path
     szo.szo_zo_step([d.desc(with_y=False)], 1, 3, 1e-3, 1e-6, scal, ws, szo.STEP_FUSED_LOSS)
     assert szo.szo_kernel_timing_read() == (0.0, 0)
+
+
+def test_grouped_launch_of_a_step_equals_per_matrix_launches_bit_for_bit():
+    """Tile configuration 3 runs all forwards of a step (every matrix, both signs) as one grid driven
+    by a descriptor table; configuration 2 launches them one by one.  Same tiles, same arithmetic,
+    same order of the loss partials: identical scalars and identical updated values."""
+    shapes = [(61, 300, 384, 1024, 128, 2e-3), (62, 257, 130, 192, 32, 0.0), (63, 129, 513, 512, 128, 2e-2),
+              (64, 70, 192, 4160, 64, 1e-1)]
+    results = []
+    for cfg in (2, 3):
+        szo.szo_set_tile_config(cfg)
+        os_, ds_, base = [], [], 0
+        for (sd, M, N, K, G, dens) in shapes:
+            o, d = make_pair(sd, M, N, K, G, dens, nnz_base=base)
+            base += (o.sp_idx.size + 3) // 4 * 4
+            os_.append(o)
+            ds_.append(d)
+        ws = szo.new_workspace()
+        scal = torch.zeros(3, dtype=torch.float64, device="cuda")
+        descs = szo.desc_array([d.desc(with_y=False) for d in ds_])
+        hist = []
+        szo.szo_kernel_timing(True)
+        for s in range(3):
+            szo.szo_zo_step(descs, 31, s, 1e-3, 1e-3, scal, ws, szo.STEP_FUSED_LOSS)
+            hist.append(scal.cpu().numpy().copy())
+        _, launches = szo.szo_kernel_timing_read()
+        szo.szo_kernel_timing(False)
+        assert launches == (3 if cfg == 3 else 3 * 2 * len(shapes))
+        results.append((hist, [d.sp_val.cpu().numpy().copy() for d in ds_]))
+        if cfg == 3:        # and both agree with the oracle
+            ref = [clone(o) for o in os_]
+            sg = sigma_g(os_)
+            for s in range(3):
+                r = ozo.zo_step(ref, 31, s, 1e-3, 1e-3)
+                lp, lm, g = hist[s]
+                assert abs(lp - r["loss_plus"]) <= 1e-6 * r["loss_plus"]
+                assert abs(g - r["g"]) <= 1e-2 * max(abs(r["g"]), sg)
+    szo.szo_set_tile_config(0)
+    (h2, v2), (h3, v3) = results
+    for a, b in zip(h2, h3):
+        assert np.array_equal(a, b)
+    for a, b in zip(v2, v3):
+        assert np.array_equal(a, b)
