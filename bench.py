@@ -24,7 +24,7 @@ PEAK_HBM_GBS = 8000.0                # MI355X HBM3E
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # script scaled by a plain copy of known size (profiles/*.md give the commands and the raw readings).
 # Only valid for the unmodified workloads; anything else reports null.
-MEASURED_TRAFFIC_BYTES = {"c3": 2.346e8, "c3m16": 3.912e9}
+MEASURED_TRAFFIC_BYTES = {"c3": 1.4187e11, "c3m16": 3.632e9}
 
 
 def log(*a):
@@ -180,7 +180,8 @@ def main():
         launch_bytes = float(sum(algorithmic_bytes_fwd(m, fused=bool(flags)) for m in mats)) * reps / launches
         launch_flops = 2 * fwd_flops * reps / launches
     else:
-        kernel = "linear_fwd_kernel"
+        # large fused steps run every forward of the step in one table-driven launch
+        kernel = "linear_fwd_table_kernel" if launches == reps else "linear_fwd_kernel"
         launch_bytes = float(sum(algorithmic_bytes_fwd(m, fused=bool(flags)) for m in mats)) * 2 * reps / launches
         launch_flops = 2 * fwd_flops * reps / launches
     tflops = launch_flops / (k_ms * 1e-3) / 1e12
