@@ -70,6 +70,32 @@ def cpu_baseline(cfg, args, total_flops_per_step):
             "cpu": platform.processor() or platform.machine(), "os_cpu_count": os.cpu_count()}
 
 
+def host_rebuild(args):
+    """Dynamic-mask bookkeeping (the paper's variant that re-selects the mask every 100 steps) as a
+    host-side throughput figure: everything libszo's host calls must redo when the mask of a matrix
+    changes.  No GPU involved; the copy of the new arrays to the device is not included."""
+    from paper_2406_02913_amd import synth, szo
+    cfg = synth.WORKLOADS[args.workload]
+    rows, total = [], 0.0
+    for i, (name, N, K) in enumerate(cfg["block"]):
+        W = synth.dense_weight(synth.matrix_seed(args.data_seed, 0, i), N, K)
+        k = int(cfg["density"] * N * K + 0.5)
+        t0 = time.perf_counter()
+        flat = szo.szo_mask_generate(N, K, k, 0 if cfg["mask"] == "uniform" else 1, 4242 + i)
+        t1 = time.perf_counter()
+        tile_ptr, sp_idx, perm = szo.szo_tcsr_build(N, K, flat)
+        t2 = time.perf_counter()
+        q, scales, sp_val = szo.szo_quantize_pack(W, cfg["group"], sp_idx)
+        t3 = time.perf_counter()
+        szo.szo_layout_weights(q, scales, cfg["group"])
+        t4 = time.perf_counter()
+        rows.append({"matrix": name, "N": N, "K": K, "nnz": k, "mask_s": t1 - t0, "tile_order_s": t2 - t1,
+                     "split_quantise_s": t3 - t2, "layout_s": t4 - t3})
+        total += t4 - t0
+    print(json.dumps({"host_rebuild_s_per_block": total, "blocks_per_s": 1.0 / total, "threads": os.cpu_count(),
+                      "workload": args.workload, "per_matrix": rows}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -90,6 +116,9 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle baseline leg (0 = skip)")
     ap.add_argument("--kernel-reps", type=int, default=None,
                     help="extra steps run with per-launch kernel timing switched on (default: as many as --steps)")
+    ap.add_argument("--host-rebuild", action="store_true",
+                    help="instead of the benchmark: time the host-side bookkeeping of a mask change (new mask -> tile "
+                         "order -> re-split and re-quantise -> banded layout) for one block of the workload and exit")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark: copy a buffer of this many MiB five times with a plain copy kernel "
                          "and exit (known traffic, to scale the FETCH_SIZE / WRITE_SIZE counters of a profiler run)")
@@ -103,6 +132,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_bytes_per_launch": n, "launches": 5}), flush=True)
+        return
+    if args.host_rebuild:
+        host_rebuild(args)
         return
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
