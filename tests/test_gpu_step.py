@@ -134,7 +134,8 @@ def test_kernel_timing_counts_forward_launches_only():
     assert szo.szo_kernel_timing_read() == (0.0, 0)
 
 
-def test_grouped_launch_of_a_step_equals_per_matrix_launches_bit_for_bit():
+@pytest.mark.parametrize("dt", [szo.TILE_F16, szo.TILE_BF16])
+def test_grouped_launch_of_a_step_equals_per_matrix_launches_bit_for_bit(dt):
     """Tile configuration 3 runs all forwards of a step (every matrix, both signs) as one grid driven
     by a descriptor table; configuration 2 launches them one by one.  Same tiles, same arithmetic,
     same order of the loss partials: identical scalars and identical updated values."""
@@ -151,7 +152,7 @@ def test_grouped_launch_of_a_step_equals_per_matrix_launches_bit_for_bit():
             ds_.append(d)
         ws = szo.new_workspace()
         scal = torch.zeros(3, dtype=torch.float64, device="cuda")
-        descs = szo.desc_array([d.desc(with_y=False) for d in ds_])
+        descs = szo.desc_array([d.desc(dt, with_y=False) for d in ds_])
         hist = []
         szo.szo_kernel_timing(True)
         for s in range(3):
@@ -167,8 +168,8 @@ def test_grouped_launch_of_a_step_equals_per_matrix_launches_bit_for_bit():
             for s in range(3):
                 r = ozo.zo_step(ref, 31, s, 1e-3, 1e-3)
                 lp, lm, g = hist[s]
-                assert abs(lp - r["loss_plus"]) <= 1e-6 * r["loss_plus"]
-                assert abs(g - r["g"]) <= 1e-2 * max(abs(r["g"]), sg)
+                assert abs(lp - r["loss_plus"]) <= (1e-6 if dt == szo.TILE_F16 else 1e-4) * r["loss_plus"]
+                assert abs(g - r["g"]) <= (1e-2 if dt == szo.TILE_F16 else 1e-1) * max(abs(r["g"]), sg)
     szo.szo_set_tile_config(0)
     (h2, v2), (h3, v3) = results
     for a, b in zip(h2, h3):
