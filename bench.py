@@ -7,7 +7,8 @@ scatter with the Gaussian regenerated in-kernel + MFMA product), the MSE loss
 of each, the SPSA scalar g, and the sparse update of every matrix.  Inputs are
 seeded, synthetic and already resident in HBM when the clock starts.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric, value (ZO steps/s), ms_per_step, the roofline of the dominant kernel
+(achieved vs peak, from per-launch events recorded by the library) and the CPU oracle as a baseline.
 """
 import argparse
 import json
