@@ -132,7 +132,12 @@ int szo_sparse_update(float* sp_val, const uint32_t* sp_idx, int64_t nnz, uint64
  * loss-fusing forward and never write y (desc->y may then be NULL); large steps then run all
  * forwards (every layer, both signs) as one launch driven by a descriptor table that is staged in
  * the workspace, and steps with at most 64 tokens per layer stream the weights once for both signs.
- * descs: host array.  Everything is enqueued on `stream`; no host synchronisation. */
+ * descs: host array, read before the call returns.  Everything is enqueued on `stream`.  The
+ * descriptor tables travel through a ring of four pinned host buffers (allocated on first use,
+ * per host thread); a call waits on the host only if the copy of the call four steps earlier on
+ * this thread has not executed yet.  Because of those buffers and that wait, a fused-loss step is
+ * not meant to be captured into a HIP graph; the single-layer calls above are plain launches.
+ * The workspace must not be shared with a call running concurrently on another stream. */
 #define SZO_STEP_FUSED_LOSS 1
 int szo_zo_step(const szo_linear_desc* descs /* host */, int n, uint64_t seed, uint64_t step,
                 float eps, float lr, double* scalars, void* workspace, int flags, void* stream);

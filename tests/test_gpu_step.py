@@ -176,3 +176,20 @@ def test_grouped_launch_of_a_step_equals_per_matrix_launches_bit_for_bit(dt):
         assert np.array_equal(a, b)
     for a, b in zip(v2, v3):
         assert np.array_equal(a, b)
+
+
+def test_steps_on_a_side_stream_match_the_default_stream():
+    outs = []
+    for use_side in (False, True):
+        szo.szo_set_tile_config(3)
+        _, d = make_pair(71, 130, 320, 384, 64, 5e-3)
+        ws = szo.new_workspace()
+        scal = torch.zeros(3, dtype=torch.float64, device="cuda")
+        torch.cuda.synchronize()
+        st = torch.cuda.Stream() if use_side else torch.cuda.current_stream()
+        for s in range(6):                       # more calls than staging buffers
+            szo.szo_zo_step([d.desc(with_y=False)], 5, s, 1e-3, 1e-3, scal, ws, szo.STEP_FUSED_LOSS, st.cuda_stream)
+        st.synchronize()
+        outs.append((scal.cpu().numpy().copy(), d.sp_val.cpu().numpy().copy()))
+    szo.szo_set_tile_config(0)
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
