@@ -53,21 +53,25 @@ def cpu_baseline(cfg, args, total_flops_per_step):
         threads = os.cpu_count()
     M = args.m or cfg["M"]
     done_flops, t_spent, used = 0.0, 0.0, []
-    for i, (name, N, K) in enumerate(cfg["block"]):
-        m = make_oracle_matrix(synth.matrix_seed(args.data_seed, 0, i), M, N, K, cfg["group"],
-                               cfg["density"], cfg["mask"])
-        t0 = time.perf_counter()
-        ozo.zo_step([m], args.seed, 0, cfg["eps"], cfg["lr"])
-        t_spent += time.perf_counter() - t0
-        done_flops += 2 * 2.0 * M * N * K
-        used.append(name)
+    layers = args.layers or cfg["layers"]
+    for layer in range(layers):                 # whole matrices, in stack order, until the time budget is used
+        for i, (name, N, K) in enumerate(cfg["block"]):
+            m = make_oracle_matrix(synth.matrix_seed(args.data_seed, layer, i), M, N, K, cfg["group"],
+                                   cfg["density"], cfg["mask"])
+            t0 = time.perf_counter()
+            ozo.zo_step([m], args.seed, 0, cfg["eps"], cfg["lr"])
+            t_spent += time.perf_counter() - t0
+            done_flops += 2 * 2.0 * M * N * K
+            used.append(f"L{layer}.{name}")
+            if t_spent >= args.cpu_seconds:
+                break
         if t_spent >= args.cpu_seconds:
             break
     frac = done_flops / total_flops_per_step
     est_step_s = t_spent / frac
     return {"value": 1.0 / est_step_s, "unit": "ZO steps/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"full oracle ZO step (fp64) on matrices {used} of layer 0 at M={M}: {t_spent:.2f} s for "
-                      f"{100 * frac:.3f}% of one step's FLOPs, extrapolated by FLOPs",
+            "sample": f"full oracle ZO step (fp64) on the first {len(used)} matrices of the stack ({used[0]} .. {used[-1]}) "
+                      f"at M={M}: {t_spent:.2f} s for {100 * frac:.3f}% of one step's FLOPs, extrapolated by FLOPs",
             "cpu": platform.processor() or platform.machine(), "os_cpu_count": os.cpu_count()}
 
 
