@@ -391,10 +391,6 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bi
     };
 
     // ---- slices ---------------------------------------------------------------------------------
-    // Dense part: unit u = code word u%4 of row half u/4, DSPU slots per unit.  Words per slot:
-    // 4 | 2,2 | 2,1,1 | 1,1,1,1.  Scatter part (32-slot schedule only): window read, tile read,
-    // add + write, two slots apart; lanes without an entry go through a per-lane sink in LDS so
-    // that the code stays branch-free.
     // Dense part: unit u = code word u%4 of row half u/4; DSPU slots per unit; the unit's four
     // output words are spread 4 | 2,2 | 2,1,1 | 1,1,1,1 over them.  In the 32-slot schedule the
     // three instructions of an output word (and_or, subtract offset, multiply by scale) run in
