@@ -23,8 +23,11 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) skel(float* out, int n
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
   for (int i = tid; i < 2 * (BM + BN) * BK; i += blockDim.x) {
     uint32_t h = (uint32_t)i * 2654435761u + blockIdx.x * 40503u; h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
-    // DATA 0: all 1.0; 1: random fp16 in [-2,2) with random mantissa; 2: zeros
-    lds[i] = DATA == 0 ? 0x3c00 : DATA == 1 ? (uint16_t)((h & 0x83FF) | (((h >> 16) & 3) + 13) << 10) : 0;
+    // DATA 0: all 1.0; 1: random fp16 (random sign, 10 random mantissa bits, exponent 13..16); 2: zeros;
+    // 3: as 1 with the low 3 mantissa bits zero (what a bf16 value converted to fp16 looks like);
+    // 4: as 1 with the low 7 mantissa bits zero
+    const uint16_t rnd = (uint16_t)((h & 0x83FF) | (((h >> 16) & 3) + 13) << 10);
+    lds[i] = DATA == 0 ? 0x3c00 : DATA == 1 ? rnd : DATA == 2 ? 0 : DATA == 3 ? (rnd & 0xFFF8) : (rnd & 0xFF80);
   }
   __syncthreads();
   float16_t acc[WMB][WNB];
@@ -104,6 +107,8 @@ int main() {
   all<0>(out, "all 1.0");
   all<1>(out, "random fp16");
   all<2>(out, "zeros");
+  all<3>(out, "random, 7-bit mantissa (bf16-like) in both operands");
+  all<4>(out, "random, 3-bit mantissa in both operands");
   all<1>(out, "random fp16 again");
   printf("done\n");
   return 0;
