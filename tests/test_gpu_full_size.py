@@ -81,3 +81,50 @@ def test_full_size_fused_loss_matches_separate_loss_and_sampled_oracle_loss():
     yE = _sampled_oracle(o, z, +1, eps, rows_n, rows_m, "E", K)
     got, want = np.mean((y - t) ** 2), np.mean((yE - t) ** 2)
     assert abs(got - want) <= 1e-4 * want
+
+
+@pytest.mark.parametrize("density", [1e-4, 1e-3, 1e-2])
+def test_mistral_up_projection_8192_tokens_sampled(density):
+    """The widest matrix of the Mistral-7B block (14336 x 4096) at 16 x 512 tokens, at the three mask
+    densities of that configuration."""
+    M, N, K = 8192, 14336, 4096
+    szo.szo_set_tile_config(0)
+    o, d = make_pair(8, M, N, K, 128, density, kind="uniform")
+    seed, step, eps = 99, 1, 1e-3
+    z = ophilox.zbar(seed, step, 0, o.sp_idx.size)
+    rng = np.random.default_rng(int(density * 1e6))
+    n_of = o.sp_idx.astype(np.int64) // K
+    hot = np.unique(n_of[rng.integers(0, n_of.size, 24)])
+    rows_n = np.unique(np.concatenate([hot, rng.integers(0, N, 24), [0, N - 1]]))
+    rows_m = np.unique(np.concatenate([rng.integers(0, M, 40), [0, M - 1, 4095, 4096]]))
+    szo.szo_linear_fwd(d.desc(), seed, step, -1, eps)
+    torch.cuda.synchronize()
+    y = d.y[torch.as_tensor(rows_m, device="cuda")][:, torch.as_tensor(rows_n, device="cuda")].cpu().numpy()
+    assert rel_fro(y, _sampled_oracle(o, z, -1, eps, rows_n, rows_m, "E", K)) <= 5e-3
+    assert rel_fro(y, _sampled_oracle(o, z, -1, eps, rows_n, rows_m, "D", K)) <= 2e-5
+
+
+@pytest.mark.parametrize("M", [1, 16, 64])
+def test_opt_ffn_projections_decode_token_counts(M):
+    """OPT-6.7B's two FFN matrices (16384 x 4096 and 4096 x 16384) at 1 / 16 / 64 tokens: one fused step
+    on the few-token path against the oracle (losses, g, updated values)."""
+    from oracle import zo as ozo
+    from helpers import clone, sigma_g
+    szo.szo_set_tile_config(0)
+    o1, d1 = make_pair(9, M, 16384, 4096, 128, 1e-3, nnz_base=0)
+    base = (o1.sp_idx.size + 3) // 4 * 4
+    o2, d2 = make_pair(10, M, 4096, 16384, 128, 1e-3, nnz_base=base)
+    ws = szo.new_workspace()
+    scal = torch.zeros(3, dtype=torch.float64, device="cuda")
+    ref = [clone(o1), clone(o2)]
+    sg = sigma_g([o1, o2])
+    szo.szo_zo_step([d1.desc(with_y=False), d2.desc(with_y=False)], 3, 0, 1e-3, 1e-4, scal, ws, szo.STEP_FUSED_LOSS)
+    lp, lm, g = scal.cpu().numpy()
+    r = ozo.zo_step(ref, 3, 0, 1e-3, 1e-4)
+    assert abs(lp - r["loss_plus"]) <= 1e-4 * r["loss_plus"]
+    assert abs(lm - r["loss_minus"]) <= 1e-4 * r["loss_minus"]
+    assert abs(g - r["g"]) <= 1e-2 * max(abs(r["g"]), sg), (g, r["g"], sg)
+    for om, dd, o in zip(ref, (d1, d2), (o1, o2)):
+        dv_gpu = dd.sp_val.cpu().numpy().astype(np.float64) - o.sp_val
+        dv_ref = om.sp_val.astype(np.float64) - o.sp_val
+        assert np.linalg.norm(dv_gpu - dv_ref) <= 3e-2 * np.linalg.norm(dv_ref) + 1e-12
