@@ -891,7 +891,7 @@ int szo_linear_fwd(const szo_linear_desc* desc, uint64_t seed, uint64_t step, in
   const int rc = validate_desc(desc, sign, true, false);
   if (rc != SZO_OK) return rc;
   if (desc->M == 0 || desc->N == 0) return SZO_OK;
-  if (g_tile_config == 0 && small_m_eligible(desc))
+  if (g_tile_config == 0 && small_m_step_eligible(desc))
     return small_m_launch_one(desc, seed, step, sign == 0 ? 0.0f : eps, sign == 0 ? 1 : sign, false, nullptr, nullptr,
                               (hipStream_t)stream);
   return run_forward(desc, seed, step, sign, eps, nullptr, 0.0, (hipStream_t)stream);
@@ -903,9 +903,9 @@ int szo_linear_fwd_mse(const szo_linear_desc* desc, uint64_t seed, uint64_t step
   if (rc != SZO_OK) return rc;
   if (!loss_acc || !workspace || ((uintptr_t)workspace & 7)) return SZO_EINVAL;
   if (desc->M == 0 || desc->N == 0) return SZO_OK;
-  if (g_tile_config == 0 && small_m_eligible(desc) && scale == 1.0 / ((double)desc->M * (double)desc->N)) {
+  if (g_tile_config == 0 && small_m_step_eligible(desc) && scale == 1.0 / ((double)desc->M * (double)desc->N)) {
     // the few-token kernel computes both signs at once: make the requested one its "+" forward
-    const int nb = small_m_blocks(desc);
+    const int nb = small_m_blocks(desc) * (int)((desc->M + 15) / 16);      // partials of all 16-row slices
     if (2 * nb > kMaxLossPartials) return SZO_EUNSUPPORTED;
     rc = small_m_launch_one(desc, seed, step, (float)sign * eps, 1, true, partial_area(workspace),
                             partial_area(workspace) + nb, (hipStream_t)stream);

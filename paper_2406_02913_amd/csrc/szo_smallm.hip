@@ -557,23 +557,36 @@ static int set_small_attrs() {
 }
 
 // One matrix, descriptor passed in the kernel arguments (no device table needed).
+// Up to 64 token rows: one launch per slice of 16 rows (the kernel multiplies 16 rows at a time).  In loss
+// mode slice i writes its partials at partial_*[i * small_m_blocks(d) ..], scaled by 1 / (M N) of the
+// whole matrix, so that their sum over all slices is the matrix's loss.
 int small_m_launch_one(const szo_linear_desc* d, uint64_t seed, uint64_t step, float eps, int sign, bool loss_mode,
                        double* partial_plus, double* partial_minus, hipStream_t stream) {
   const int rc = set_small_attrs();
   if (rc != SZO_OK) return rc;
-  SmallArgs a{};
-  fill_mat(a.one, d);
-  a.table = nullptr; a.n_mats = 1;
-  a.store_sign = sign; a.loss_mode = loss_mode ? 1 : 0;
-  a.seed = seed; a.step = step; a.eps = eps;
-  a.partial_plus = partial_plus; a.partial_minus = partial_minus;
   const int blocks = small_m_blocks(d);
-  int trc = timing_begin(stream);
-  if (trc != SZO_OK) return trc;
-  if (small_m_fast(d)) small_m_kernel<true><<<blocks, 256, small_lds_bytes(), stream>>>(a);
-  else small_m_kernel<false><<<blocks, 256, small_lds_bytes(), stream>>>(a);
-  SZO_LAUNCH_CHECK();
-  return timing_end(stream);
+  const int slices = (int)((d->M + SM_ROWS - 1) / SM_ROWS);
+  for (int sl = 0; sl < slices; ++sl) {
+    SmallArgs a{};
+    fill_mat(a.one, d);                                     // loss_scale from the whole matrix
+    a.one.x += (size_t)sl * SM_ROWS * (size_t)d->K;
+    if (a.one.target) a.one.target += (size_t)sl * SM_ROWS * (size_t)d->N;
+    if (a.one.y) a.one.y += (size_t)sl * SM_ROWS * (size_t)d->N;
+    a.one.M = (int)std::min<int64_t>(SM_ROWS, d->M - (int64_t)sl * SM_ROWS);
+    a.table = nullptr; a.n_mats = 1;
+    a.store_sign = sign; a.loss_mode = loss_mode ? 1 : 0;
+    a.seed = seed; a.step = step; a.eps = eps;
+    a.partial_plus = partial_plus ? partial_plus + (size_t)sl * blocks : nullptr;
+    a.partial_minus = partial_minus ? partial_minus + (size_t)sl * blocks : nullptr;
+    const int trc = timing_begin(stream);
+    if (trc != SZO_OK) return trc;
+    if (small_m_fast(d)) small_m_kernel<true><<<blocks, 256, small_lds_bytes(), stream>>>(a);
+    else small_m_kernel<false><<<blocks, 256, small_lds_bytes(), stream>>>(a);
+    SZO_LAUNCH_CHECK();
+    const int erc = timing_end(stream);
+    if (erc != SZO_OK) return erc;
+  }
+  return SZO_OK;
 }
 
 // A whole stack in one launch per group size.  The table is assembled on the host, longest K

@@ -18,6 +18,8 @@ SHAPES = [
     (14, 7, 513, 2048, 128, 2e-3),      # ragged M and N, eight chunks
     (19, 16, 128, 1024, 128, 8e-2),     # ~1300 entries per band and chunk: the entry ring wraps inside a chunk
     (20, 3, 64, 4864, 128, 3e-3),       # 19 chunks, one band
+    (21, 40, 320, 512, 128, 5e-3),      # 17..64 tokens: three passes of 16 token rows, the last one ragged
+    (22, 64, 256, 384, 64, 1e-2),       # four passes, plain instantiation
     (15, 16, 320, 256, 32, 1e-2),       # group 32: scale applied per element
     (16, 9, 128, 384, 64, 2e-2),        # group 64
     (17, 16, 256, 256, 128, 0.0),       # k = 0
@@ -71,6 +73,14 @@ def test_few_token_fused_loss_and_step():
         yE = olayer.linear_fwd(o1.x_bits, o1.codes, o1.scales, 128, o1.sp_idx, o1.sp_val, z, sign, 1e-3, "E")
         want = olayer.mse_loss(yE, o1.target_bits)
         assert abs(acc.item() - want) <= 1e-4 * want
+    # single-matrix fused loss with more than 16 tokens: the partials of all 16-row passes add up
+    o3, d3 = make_pair(33, 48, 384, 512, 128, 4e-3, nnz_base=64)
+    acc = torch.zeros(1, dtype=torch.float64, device="cuda")
+    szo.szo_linear_fwd_mse(d3.desc(with_y=False), 9, 2, -1, 1e-3, 1.0 / (d3.M * d3.N), acc, ws)
+    z = ophilox.zbar(9, 2, 64, o3.sp_idx.size)
+    yE = olayer.linear_fwd(o3.x_bits, o3.codes, o3.scales, 128, o3.sp_idx, o3.sp_val, z, -1, 1e-3, "E")
+    want = olayer.mse_loss(yE, o3.target_bits)
+    assert abs(acc.item() - want) <= 1e-4 * want
     # whole steps over two matrices
     scal = torch.zeros(3, dtype=torch.float64, device="cuda")
     a, b = clone(o1), clone(o2)
