@@ -208,7 +208,7 @@ def main():
     szo.szo_kernel_timing(True)
     for s in range(reps):
         one_step(args.warmup + args.steps + s)
-    k_total_ms, launches = szo.szo_kernel_timing_read()
+    (k_total_ms, launches), (u_total_ms, u_launches) = szo.szo_kernel_timing_read2()
     szo.szo_kernel_timing(False)
     k_ms = k_total_ms / launches
     if few:
@@ -234,6 +234,14 @@ def main():
         roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(args.workload)
     roof.update({"kernel": kernel, "avg_launch_us": round(1e3 * k_ms, 2), "launches_timed": launches,
                  "flops_per_launch": launch_flops, "bytes_per_launch": launch_bytes})
+    # the sparse update: 8 bytes per sensitive entry (fp32 value read and written); z is regenerated
+    upd = None
+    if u_launches:
+        u_ms = u_total_ms / u_launches
+        u_bytes = 8.0 * sum(m.nnz for m in mats) * reps / u_launches
+        upd = {"kernel": "sparse_update", "avg_launch_us": round(1e3 * u_ms, 2), "launches_timed": u_launches,
+               "bytes_per_launch": u_bytes, "achieved": round(u_bytes / (u_ms * 1e-3) / 1e9, 1), "unit": "GB/s",
+               "frac_of_hbm_peak": round(u_bytes / (u_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
     step_flops = 2 * fwd_flops
     log(f"[bench] {kernel}: {1e3 * k_ms:.1f} us/launch avg over {launches} launches, {tflops:.1f} TFLOP/s, "
         f"{gbs:.1f} GB/s algorithmic")
@@ -258,6 +266,7 @@ def main():
         "step_tflops": round(step_flops / (ms_per_step * 1e-3) / 1e12, 2),
         "step_frac_of_mfma_peak": round(step_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_MFMA_16BIT_TFLOPS, 4),
         "roofline": roof,
+        "sparse_update": upd,
         "cpu_baseline": base,
     }
     print(json.dumps(out), flush=True)

@@ -198,6 +198,9 @@ int szo_layout_weights(const uint8_t* q, const uint16_t* scales, int64_t N, int6
  * wide state, for one measuring thread; events are created on demand and kept. */
 int szo_kernel_timing(int enable);
 int szo_kernel_timing_read(double* total_ms /* host */, int64_t* launches /* host */);
+/* The same collection split by kind: [0] the forward kernels (what szo_kernel_timing_read returns),
+ * [1] the sparse update kernels, which are bracketed as well while timing is on. */
+int szo_kernel_timing_read2(double total_ms[2] /* host */, int64_t launches[2] /* host */);
 
 /* Host evaluation of Philox-4x32-10 (ten rounds; multipliers 0xD2511F53, 0xCD9E8D57; key
  * increments 0x9E3779B9, 0xBB67AE85). */

@@ -55,10 +55,10 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
                  void* table_dev, double* partial_plus, double* scalars, bool do_forward, bool do_update,
                  hipStream_t stream);
 
-// Optional timing of the forward kernels (szo_kernel_timing): when switched on, every launch of a
-// forward kernel is bracketed by a pair of events on its own stream.  Both calls are no-ops when
-// timing is off.  Defined in szo_kernels.hip.
-int timing_begin(hipStream_t stream);
+// Optional kernel timing (szo_kernel_timing): when switched on, every launch of a forward kernel
+// (kind 0) or of a sparse update kernel (kind 1) is bracketed by a pair of events on its own stream.
+// Both calls are no-ops when timing is off.  Defined in szo_kernels.hip.
+int timing_begin(hipStream_t stream, int kind = 0);
 int timing_end(hipStream_t stream);
 
 // Copies `bytes` (a multiple of 4) of host data into device memory `dst`, in stream order, without

@@ -193,13 +193,14 @@ namespace {
 struct TimingState {
   bool on = false;
   std::vector<hipEvent_t> start, stop;
+  std::vector<int> kind;    // 0 = forward kernel, 1 = sparse update kernel
   size_t used = 0;          // pairs recorded since the last read
   bool open = false;        // a begin without its end
 };
 TimingState g_timing;
 }  // namespace
 
-int timing_begin(hipStream_t stream) {
+int timing_begin(hipStream_t stream, int kind) {
   if (!g_timing.on) return SZO_OK;
   if (g_timing.used == g_timing.start.size()) {
     hipEvent_t a, b;
@@ -207,7 +208,9 @@ int timing_begin(hipStream_t stream) {
     SZO_HIP(hipEventCreate(&b));
     g_timing.start.push_back(a);
     g_timing.stop.push_back(b);
+    g_timing.kind.push_back(0);
   }
+  g_timing.kind[g_timing.used] = kind;
   SZO_HIP(hipEventRecord(g_timing.start[g_timing.used], stream));
   g_timing.open = true;
   return SZO_OK;
@@ -232,19 +235,33 @@ int szo_kernel_timing(int enable) {
   return SZO_OK;
 }
 
-int szo_kernel_timing_read(double* total_ms, int64_t* launches) {
+int szo_kernel_timing_read2(double total_ms[2], int64_t launches[2]) {
   using szo::g_timing;
   if (!total_ms || !launches) return SZO_EINVAL;
-  double sum = 0.0;
+  double sum[2] = {0.0, 0.0};
+  int64_t cnt[2] = {0, 0};
   for (size_t i = 0; i < g_timing.used; ++i) {
     SZO_HIP(hipEventSynchronize(g_timing.stop[i]));
     float ms = 0.0f;
     SZO_HIP(hipEventElapsedTime(&ms, g_timing.start[i], g_timing.stop[i]));
-    sum += (double)ms;
+    const int k = g_timing.kind[i] == 1 ? 1 : 0;
+    sum[k] += (double)ms;
+    cnt[k] += 1;
   }
-  *total_ms = sum;
-  *launches = (int64_t)g_timing.used;
+  total_ms[0] = sum[0]; total_ms[1] = sum[1];
+  launches[0] = cnt[0]; launches[1] = cnt[1];
   g_timing.used = 0;
+  return SZO_OK;
+}
+
+int szo_kernel_timing_read(double* total_ms, int64_t* launches) {
+  if (!total_ms || !launches) return SZO_EINVAL;
+  double ms[2];
+  int64_t n[2];
+  const int rc = szo_kernel_timing_read2(ms, n);
+  if (rc != SZO_OK) return rc;
+  *total_ms = ms[0];
+  *launches = n[0];
   return SZO_OK;
 }
 
@@ -277,9 +294,11 @@ int szo_sparse_update(float* sp_val, const uint32_t* sp_idx, int64_t nnz, uint64
   const int64_t quads = (nnz + 3) / 4;
   const int64_t blocks = (quads + 255) / 256;
   if (blocks > 0x7FFFFFFF) return SZO_EUNSUPPORTED;
+  const int trc = timing_begin((hipStream_t)stream, 1);
+  if (trc != SZO_OK) return trc;
   sparse_update_kernel<<<(unsigned)blocks, 256, 0, (hipStream_t)stream>>>(sp_val, nnz, nnz_base, seed, step, g, lr);
   SZO_LAUNCH_CHECK();
-  return SZO_OK;
+  return timing_end((hipStream_t)stream);
 }
 
 int szo_mse_loss(const float* y, const void* target, int64_t count, double scale, double* loss_acc,

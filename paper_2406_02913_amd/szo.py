@@ -59,6 +59,7 @@ _SIGS = {
     "szo_set_tile_config": (C.c_int, [C.c_int]),
     "szo_kernel_timing": (C.c_int, [C.c_int]),
     "szo_kernel_timing_read": (C.c_int, [C.c_void_p, C.c_void_p]),
+    "szo_kernel_timing_read2": (C.c_int, [C.c_void_p, C.c_void_p]),
     "szo_last_hip_error": (C.c_int, []),
     "szo_version": (C.c_int, []),
 }
@@ -241,6 +242,13 @@ def szo_kernel_timing_read():
     ms, n = C.c_double(0.0), C.c_int64(0)
     _check("szo_kernel_timing_read", lib.szo_kernel_timing_read(C.byref(ms), C.byref(n)))
     return ms.value, n.value
+
+
+def szo_kernel_timing_read2():
+    """((forward ms, forward launches), (sparse update ms, sparse update launches))."""
+    ms, n = (C.c_double * 2)(), (C.c_int64 * 2)()
+    _check("szo_kernel_timing_read2", lib.szo_kernel_timing_read2(ms, n))
+    return (ms[0], n[0]), (ms[1], n[1])
 
 
 def szo_last_hip_error():
