@@ -674,8 +674,10 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
   if (do_update && quads > 0) {
     const int64_t ub = (quads + 255) / 256;
     if (ub > 0x7FFFFFFF) return SZO_EUNSUPPORTED;
+    if ((rc = timing_begin(stream, 1)) != SZO_OK) return rc;
     sparse_update_table_kernel<<<(unsigned)ub, 256, 0, stream>>>(tdev, entries, quads, seed, step, scalars + 2, lr);
     SZO_LAUNCH_CHECK();
+    if ((rc = timing_end(stream)) != SZO_OK) return rc;
   }
   return SZO_OK;
 }
