@@ -1,4 +1,4 @@
-// Few-token path (M <= 16): the forward is bound by streaming the 4-bit weights from HBM, not by
+// Few-token path (16 token rows per pass; callers slice up to 64): the forward is bound by streaming the 4-bit weights from HBM, not by
 // the matrix cores, and the paper's own guideline for this regime (Appendix C.5) is the
 // SparseAddMM association:   y = x Dequantize(Q(w_dense))^T  +  x w_sparse^T.
 // Two consequences shape this kernel:
@@ -13,7 +13,7 @@
 // a streaming-read probe on this chip reaches its ceiling with a few 16-byte loads in flight per
 // wave as long as enough waves are resident, and the resident waves hide each other's stalls.
 // Per chunk a wave
-//   - streams its band's codes, 16 bytes per lane, one chunk ahead, and turns them in registers into
+//   - streams its band's codes, 16 bytes per lane, one 128-column block ahead, and turns them in registers into
 //     the B operand of v_mfma_f32_16x16x32_f16 (no LDS round trip: every weight is used once).
 //     With a quantisation group of 128 the codes are NOT re-centred: 0x6400|c reads 1024+c and
 //     0x5400|(c<<4) reads 64+c, both exact in fp16, and the constant part
