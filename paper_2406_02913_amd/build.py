@@ -18,33 +18,32 @@ COMMON = ["-O3", "-fPIC", "-std=c++17", "-I", os.path.join(ROOT, "include"), "-I
 DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
-def build(verbose=False, extra=()):
-    objs = []
-    for src in HOST_SOURCES:
-        obj = os.path.join(CSRC, src + ".o")
-        cmd = ["g++", "-c", "-ffp-contract=off", "-pthread"] + COMMON + [os.path.join(CSRC, src), "-o", obj]
-        if verbose:
-            print(" ".join(cmd), flush=True)
-        subprocess.check_call(cmd)
-        objs.append(obj)
-    for src in HIP_SOURCES:
-        obj = os.path.join(CSRC, src + ".o")
-        cmd = [HIPCC, "-c"] + COMMON + DEVICE + list(extra) + [os.path.join(CSRC, src), "-o", obj]
-        if verbose:
-            print(" ".join(cmd), flush=True)
-        subprocess.check_call(cmd)
-        objs.append(obj)
-    cmd = [HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs + ["-lpthread"]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
+
+
+def build(verbose=False, extra=()):
+    """Compiles every source (in parallel: the translation units are independent), links the library,
+    and builds the stand-alone measurement probes."""
+    from concurrent.futures import ThreadPoolExecutor
+    jobs, objs = [], []
+    for src in HOST_SOURCES:
+        obj = os.path.join(CSRC, src + ".o")
+        jobs.append(["g++", "-c", "-ffp-contract=off", "-pthread"] + COMMON + [os.path.join(CSRC, src), "-o", obj])
+        objs.append(obj)
+    for src in HIP_SOURCES:
+        obj = os.path.join(CSRC, src + ".o")
+        jobs.append([HIPCC, "-c"] + COMMON + DEVICE + list(extra) + [os.path.join(CSRC, src), "-o", obj])
+        objs.append(obj)
     # stand-alone measurement probes (ceilings quoted in the profile summaries); not linked into the library
     for probe in PROBES:
-        cmd = [HIPCC, "-O3", "-std=c++17"] + DEVICE + [os.path.join(CSRC, "probes", probe + ".hip"),
-                                                        "-o", os.path.join(HERE, "probe_" + probe)]
-        if verbose:
-            print(" ".join(cmd), flush=True)
-        subprocess.check_call(cmd)
+        jobs.append([HIPCC, "-O3", "-std=c++17"] + DEVICE + [os.path.join(CSRC, "probes", probe + ".hip"),
+                                                              "-o", os.path.join(HERE, "probe_" + probe)])
+    with ThreadPoolExecutor(max_workers=min(8, len(jobs))) as pool:
+        list(pool.map(lambda c: _run(c, verbose), jobs))
+    _run([HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs + ["-lpthread"], verbose)
     return LIB
 
 
