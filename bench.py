@@ -101,6 +101,46 @@ def host_rebuild(args):
                       "workload": args.workload, "per_matrix": rows}), flush=True)
 
 
+def vendor_gemm(args):
+    """Not part of the path: torch.matmul (hipBLASLt / rocBLAS) on x [M,K] times W^T with W [N,K] already
+    in 16 bits, i.e. the dense product of the SparseAdd-then-DenseMM form without dequantisation, sparse
+    add, loss or update."""
+    import torch
+    from paper_2406_02913_amd import synth
+    cfg = synth.WORKLOADS[args.workload]
+    M = args.m or cfg["M"]
+    dt = torch.float16 if args.tile == "f16" else torch.bfloat16
+    rows, total_us, total_flops = [], 0.0, 0.0
+    torch.manual_seed(0)
+    for name, N, K in cfg["block"]:
+        for data in ("random", "zeros"):
+            if data == "random":
+                x = torch.randn(M, K, device="cuda").to(dt)
+                w = (0.02 * torch.randn(N, K, device="cuda")).to(dt)
+            else:
+                x = torch.zeros(M, K, device="cuda", dtype=dt)
+                w = torch.zeros(N, K, device="cuda", dtype=dt)
+            for _ in range(30):
+                y = x @ w.t()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(50):
+                y = x @ w.t()
+            e1.record()
+            torch.cuda.synchronize()
+            us = 1e3 * e0.elapsed_time(e1) / 50
+            rows.append({"matrix": name, "M": M, "N": N, "K": K, "operands": data, "us": round(us, 1),
+                         "tflops": round(2.0 * M * N * K / us / 1e6, 1)})
+            if data == "random":
+                total_us += us
+                total_flops += 2.0 * M * N * K
+            del x, w, y
+    print(json.dumps({"vendor_dense_gemm": rows, "dtype": args.tile, "workload": args.workload,
+                      "block_us_random": round(total_us, 1),
+                      "block_tflops_random": round(total_flops / total_us / 1e6, 1)}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -124,6 +164,10 @@ def main():
     ap.add_argument("--host-rebuild", action="store_true",
                     help="instead of the benchmark: time the host-side bookkeeping of a mask change (new mask -> tile "
                          "order -> re-split and re-quantise -> banded layout) for one block of the workload and exit")
+    ap.add_argument("--vendor-gemm", action="store_true",
+                    help="instead of the benchmark: time the vendor library's plain dense 16-bit GEMM (torch.matmul) on "
+                         "the workload's shapes with random and with all-zero operands and exit (context for the "
+                         "roofline: what a dense product on already materialised weights reaches on this machine)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark: copy a buffer of this many MiB five times with a plain copy kernel "
                          "and exit (known traffic, to scale the FETCH_SIZE / WRITE_SIZE counters of a profiler run)")
@@ -140,6 +184,9 @@ def main():
         return
     if args.host_rebuild:
         host_rebuild(args)
+        return
+    if args.vendor_gemm:
+        vendor_gemm(args)
         return
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
