@@ -141,6 +141,51 @@ def vendor_gemm(args):
                       "block_tflops_random": round(total_flops / total_us / 1e6, 1)}), flush=True)
 
 
+def operand_sensitivity(args):
+    """Not the benchmark: the same fused step on a few blocks of the workload, timed with the synthetic
+    operands and again after x and / or the codes have been overwritten with zeros.  Matrix cores draw
+    power by the bits that toggle, so the difference is what the clock management takes; the all-zero
+    figure is what the kernel's instruction schedule alone allows."""
+    import torch
+    from paper_2406_02913_amd import stack, synth, szo
+    torch.cuda.set_device(0)
+    szo.szo_set_tile_config(3 if args.tile_config == 0 else args.tile_config)
+    dt = szo.TILE_F16 if args.tile == "f16" else szo.TILE_BF16
+    mats, cfg = stack.build_stack(args.workload, args.data_seed, "cuda", M=args.m, layers=args.layers or 4,
+                                  density=args.density)
+    descs = szo.desc_array([m.desc(dt, with_y=False) for m in mats])
+    ws = szo.new_workspace()
+    scal = torch.zeros(3, dtype=torch.float64, device="cuda")
+    flops = sum(2 * 2.0 * m.M * m.N * m.K for m in mats)
+    rows = []
+
+    def timed(tag):
+        for s in range(5):
+            szo.szo_zo_step(descs, args.seed, s, cfg["eps"], 0.0, scal, ws, szo.STEP_FUSED_LOSS)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for s in range(20):
+            szo.szo_zo_step(descs, args.seed, s, cfg["eps"], 0.0, scal, ws, szo.STEP_FUSED_LOSS)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 20
+        rows.append({"operands": tag, "ms_per_step": round(ms, 3), "tflops": round(flops / ms / 1e9, 1)})
+
+    timed("synthetic x, synthetic codes")
+    for m in mats:
+        m.x.zero_()
+    timed("zero x, synthetic codes")
+    for m in mats:
+        m.qweight.fill_(0x88)
+    timed("zero x, zero codes")
+    for m in mats:
+        m.x.normal_()
+    timed("random x, zero codes")
+    print(json.dumps({"operand_sensitivity": rows, "workload": args.workload, "blocks": args.layers or 4,
+                      "M": mats[0].M, "dtype": args.tile, "lr": 0.0}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -168,6 +213,10 @@ def main():
                     help="instead of the benchmark: time the vendor library's plain dense 16-bit GEMM (torch.matmul) on "
                          "the workload's shapes with random and with all-zero operands and exit (context for the "
                          "roofline: what a dense product on already materialised weights reaches on this machine)")
+    ap.add_argument("--operand-sensitivity", action="store_true",
+                    help="instead of the benchmark: time the fused step on --layers (default 4) blocks with the synthetic "
+                         "operands and with x and / or the codes zeroed, and exit (how much of the step time is the "
+                         "data-dependent power draw of the matrix cores, how much the kernel's own schedule)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark: copy a buffer of this many MiB five times with a plain copy kernel "
                          "and exit (known traffic, to scale the FETCH_SIZE / WRITE_SIZE counters of a profiler run)")
@@ -187,6 +236,9 @@ def main():
         return
     if args.vendor_gemm:
         vendor_gemm(args)
+        return
+    if args.operand_sensitivity:
+        operand_sensitivity(args)
         return
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
