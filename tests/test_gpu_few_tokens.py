@@ -47,6 +47,26 @@ def test_few_token_forward_matches_oracle(shape):
         assert rel_fro(y, yE) <= tol, (sign, rel_fro(y, yE))
 
 
+def test_few_token_counters_seed_and_step_beyond_32_bits():
+    """y(+) - y(-) = 2 eps x z^T isolates the regenerated Gaussians: entry index, seed and step all use
+    their high words."""
+    szo.szo_set_tile_config(0)
+    base, seed, step, eps = (1 << 35) + 8, (1 << 40) + 77, (1 << 33) + 5, 0.05
+    o, d = make_pair(23, 16, 192, 512, 128, 2e-2, nnz_base=base)
+    z = ophilox.zbar(seed, step, base, o.sp_idx.size)
+    ys = {}
+    for sign in (+1, -1):
+        szo.szo_linear_fwd(d.desc(), seed, step, sign, eps)
+        ys[sign] = d.y.cpu().numpy().astype(np.float64)
+    yp = olayer.linear_fwd(o.x_bits, o.codes, o.scales, 128, o.sp_idx, o.sp_val, z, +1, eps, "E")
+    ym = olayer.linear_fwd(o.x_bits, o.codes, o.scales, 128, o.sp_idx, o.sp_val, z, -1, eps, "E")
+    # z is held in fp16 (5e-4 relative) and the difference of two fp32 outputs carries their rounding
+    assert rel_fro(ys[+1] - ys[-1], yp - ym) <= 3e-3
+    # the same entries with the low words only give different Gaussians: the check can tell
+    z_low = ophilox.zbar(77, 5, 8, o.sp_idx.size)
+    assert np.abs(z - z_low).max() > 1.0
+
+
 def test_few_token_path_agrees_with_the_tiled_kernel():
     o, d = make_pair(21, 16, 384, 512, 128, 1e-2)
     szo.szo_set_tile_config(0)
