@@ -268,11 +268,16 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bi
     const bool band_ok = band < p.bands;
     const uint32_t tp_base = (uint32_t)band * (uint32_t)nk;
     uint32_t tile_lo = 0, band_end = 0;                          // entry range bookkeeping (uniform)
-    if (band_ok) {
-      tile_lo = __builtin_amdgcn_readfirstlane(p.tile_ptr[tp_base]);
-      band_end = __builtin_amdgcn_readfirstlane(p.tile_ptr[tp_base + nk]);
-    }
     uint32_t tp_reg = 0;                                         // lane l: tile_ptr[tp_base + 64*c + 1 + l]
+    uint32_t t_lo = 0, t_end = 0;
+    if (band_ok) {
+      // Three independent loads and (below, after the first codes have been requested too) one wait: the
+      // tile's first K step cannot start before the band's first entries are known, so every memory
+      // round trip here is dead time for the whole workgroup.
+      t_lo = p.tile_ptr[tp_base];
+      t_end = p.tile_ptr[tp_base + nk];
+      tp_reg = p.tile_ptr[min(tp_base + 1u + (uint32_t)lane, tp_base + (uint32_t)nk)];
+    }
     uint32_t win_lo = 0, win_hi = 0;                             // entries [win_lo, win_hi) are in the window
     float* const wv = winVal + wave * kWindow;
     uint16_t* const wp = winPos + wave * kWindow;
@@ -373,7 +378,7 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bi
     auto prepare_scatter = [&](int kt) {
       sc_cnt = 0; big_lo = 0; big_hi = 0;
       if (!band_ok || kt >= nk) return;
-      if ((kt & 63) == 0) {
+      if ((kt & 63) == 0 && kt > 0) {                        // the first 64 boundaries were loaded with tile_lo
         const uint32_t t = tp_base + (uint32_t)kt + 1u + lane;
         tp_reg = (t <= tp_base + (uint32_t)nk) ? p.tile_ptr[t] : band_end;
         asm volatile("" : "+v"(tp_reg));       // consume the load here, so that no wait on it is needed later
@@ -486,6 +491,8 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bi
     __builtin_amdgcn_s_setprio(1);
     load_w(0, 0);
     load_w(0, 1);
+    tile_lo = __builtin_amdgcn_readfirstlane(t_lo);
+    band_end = __builtin_amdgcn_readfirstlane(t_end);
     prepare_scatter(0);
     {
       auto slice = make_slice(0, 1);
