@@ -15,7 +15,7 @@ something that isolates accumulation error from operand rounding.
 """
 import numpy as np
 
-from .quant import dequantize, f32_to_bf16_bits, bf16_bits_to_f64
+from .quant import dequantize, dequantize_lut, f32_to_bf16_bits, bf16_bits_to_f64
 
 
 def _round16(w32, tile_dtype):
@@ -27,10 +27,12 @@ def _round16(w32, tile_dtype):
 
 
 def effective_weight(codes, scales, group, sp_idx, sp_val, z=None, sign=0, eps=0.0,
-                     mode="E", tile_dtype="f16"):
+                     mode="E", tile_dtype="f16", lut=None):
     """SparseAdd(w_sparse + sign*eps*z, Dequantize(Q(w_dense))) as a dense
-    fp64 [N, K] matrix.  sp_idx are flat positions n*K+k, sp_val fp32."""
-    dq = dequantize(codes, scales, group)
+    fp64 [N, K] matrix.  sp_idx are flat positions n*K+k, sp_val fp32.
+    With `lut` (fp16 [N, 16]) the codes are of the non-uniform format and
+    scales / group are not looked at."""
+    dq = dequantize(codes, scales, group) if lut is None else dequantize_lut(codes, lut)
     N, K = dq.shape
     idx = np.asarray(sp_idx, dtype=np.int64)
     eps32 = np.float32(eps)
@@ -52,20 +54,20 @@ def effective_weight(codes, scales, group, sp_idx, sp_val, z=None, sign=0, eps=0
 
 
 def linear_fwd(x_bits, codes, scales, group, sp_idx, sp_val, z=None, sign=0, eps=0.0,
-               mode="E", tile_dtype="f16"):
+               mode="E", tile_dtype="f16", lut=None):
     """y = x W_eff^T in fp64.  x_bits: uint16 bf16 patterns [M, K]."""
     x = bf16_bits_to_f64(x_bits)
-    W = effective_weight(codes, scales, group, sp_idx, sp_val, z, sign, eps, mode, tile_dtype)
+    W = effective_weight(codes, scales, group, sp_idx, sp_val, z, sign, eps, mode, tile_dtype, lut)
     return x @ W.T
 
 
-def linear_fwd_addmm(x_bits, codes, scales, group, sp_idx, sp_val, z=None, sign=0, eps=0.0):
+def linear_fwd_addmm(x_bits, codes, scales, group, sp_idx, sp_val, z=None, sign=0, eps=0.0, lut=None):
     """The other association of Appendix C.5: SparseAddMM(DenseMM(Dequantize(
     Q(w_dense)), x), w_sparse, x) -- dense product first, then one rank-one
     column update per sensitive entry.  Must equal linear_fwd to fp64
     rounding."""
     x = bf16_bits_to_f64(x_bits)
-    dq = dequantize(codes, scales, group)
+    dq = dequantize(codes, scales, group) if lut is None else dequantize_lut(codes, lut)
     N, K = dq.shape
     y = x @ dq.T
     v = np.asarray(sp_val, dtype=np.float32).astype(np.float64)
@@ -78,12 +80,13 @@ def linear_fwd_addmm(x_bits, codes, scales, group, sp_idx, sp_val, z=None, sign=
     return y
 
 
-def linear_fwd_bruteforce(x_bits, codes, scales, group, sp_idx, sp_val, z=None, sign=0, eps=0.0):
+def linear_fwd_bruteforce(x_bits, codes, scales, group, sp_idx, sp_val, z=None, sign=0, eps=0.0, lut=None):
     """Triple loop over (m, n, k) in Python floats; tiny shapes only."""
     x = bf16_bits_to_f64(x_bits)
     M, K = x.shape
     N = codes.shape[0]
-    s = np.asarray(scales, dtype=np.float16).astype(np.float64)
+    if lut is None:
+        s = np.asarray(scales, dtype=np.float16).astype(np.float64)
     extra = {}
     for j, f in enumerate(np.asarray(sp_idx, dtype=np.int64).tolist()):
         v = float(np.float32(sp_val[j]))
@@ -95,8 +98,11 @@ def linear_fwd_bruteforce(x_bits, codes, scales, group, sp_idx, sp_val, z=None, 
         for n in range(N):
             acc = 0.0
             for k in range(K):
-                w = (int(codes[n, k]) - 8) * float(s[n, k // group]) + extra.get(n * K + k, 0.0)
-                acc += float(x[m, k]) * w
+                if lut is None:
+                    w = (int(codes[n, k]) - 8) * float(s[n, k // group])
+                else:
+                    w = float(np.float16(lut[n, int(codes[n, k])]))
+                acc += float(x[m, k]) * (w + extra.get(n * K + k, 0.0))
             y[m, n] = acc
     return y
 

@@ -8,6 +8,16 @@ columns, scale = fp16(max|w| / 7), code = clamp(rint(w / scale), -8, 7),
 stored as code + 8 in a nibble (zero code 8).  Masked coordinates are set to
 zero before the scales are taken, so w_dense is exactly zero on the mask and
 "add the sparse part" equals "overwrite with the sparse part".
+
+A second, non-uniform format (Appendix C.5, "Integration with weight
+quantization method": a non-uniform quantiser is always dequantised first and
+takes the SparseAdd form): per output row a table of 16 fp16 centroids, code =
+index of the nearest centroid.  The paper fixes no codebook construction; the
+reading here is the plainest deterministic one: the centroids of a row are the
+16 order statistics of its dense part (mask zeroed) at ranks (2c+1)K/32, i.e.
+the medians of 16 equal-mass bins, rounded to fp16.  Zero is then in general
+not a centroid, so on the mask the dequantised dense part is a small non-zero
+value and the sparse part is ADDED to it, as the decomposition says.
 """
 import numpy as np
 
@@ -72,3 +82,33 @@ def dequantize(codes, scales, group):
     N, K = codes.shape
     s = np.asarray(scales, dtype=np.float16).astype(np.float64)
     return (codes.astype(np.float64) - 8.0) * np.repeat(s, group, axis=1)
+
+
+def split_and_quantize_lut(W, flat_idx):
+    """Non-uniform 4-bit format.  W: fp32 [N, K], K % 32 == 0.
+
+    Returns (codes uint8 [N, K] in 0..15, lut float16 [N, 16] non-decreasing
+    along each row, sp_val float32 in the order of flat_idx)."""
+    W = np.asarray(W, dtype=np.float32)
+    N, K = W.shape
+    assert K % 32 == 0
+    flat_idx = np.asarray(flat_idx, dtype=np.int64)
+    sp_val = W.reshape(-1)[flat_idx].copy()
+    dense = W.copy()
+    dense.reshape(-1)[flat_idx] = np.float32(0.0)
+    ranks = (2 * np.arange(16) + 1) * (K // 32)
+    lut = np.sort(dense, axis=1)[:, ranks].astype(np.float16)          # RNE to fp16
+    codes = np.empty((N, K), dtype=np.uint8)
+    for r0 in range(0, N, 128):                                        # row blocks only bound the memory used
+        d = dense[r0:r0 + 128].astype(np.float64)
+        t = lut[r0:r0 + 128].astype(np.float64)
+        # nearest centroid; fp32 minus fp16 is exact in fp64; ties go to the lower index
+        codes[r0:r0 + 128] = np.argmin(np.abs(d[:, :, None] - t[:, None, :]), axis=2)
+    return codes, lut, sp_val
+
+
+def dequantize_lut(codes, lut):
+    """Dequantize(Q(w_dense)) for the non-uniform format: lut[n, code[n, k]], fp64."""
+    codes = np.asarray(codes)
+    t = np.asarray(lut, dtype=np.float16).astype(np.float64)
+    return np.take_along_axis(t, codes.astype(np.int64), axis=1)

@@ -28,6 +28,7 @@ class Matrix:
     sp_val: np.ndarray       # float32 [nnz]
     target_bits: np.ndarray  # uint16 bf16 [M, N]
     nnz_base: int = 0
+    lut: np.ndarray = None   # float16 [N, 16]: non-uniform format (scales, group unused)
 
 
 def spsa_scalar(loss_plus, loss_minus, eps):
@@ -45,7 +46,7 @@ def model_loss(mats, seed, step, sign, eps, mode="E", tile_dtype="f16", zs=None,
     for i, m in enumerate(mats):
         z = zs[i] if zs is not None else zbar(seed, step, m.nnz_base, m.sp_idx.size)
         y = linear_fwd(m.x_bits, m.codes, m.scales, m.group, m.sp_idx, m.sp_val,
-                       z=z, sign=sign, eps=eps, mode=mode, tile_dtype=tile_dtype)
+                       z=z, sign=sign, eps=eps, mode=mode, tile_dtype=tile_dtype, lut=m.lut)
         total += loss_fn(y, m.target_bits)
     return total
 
