@@ -35,8 +35,8 @@ def log(*a):
 def algorithmic_bytes_fwd(m, fused=True):
     """Bytes one pass over a matrix must move: codes + scales + sparse (idx, val) + x, and either
     the bf16 target (loss fused into the kernel) or the fp32 y it writes."""
-    return (m.N * m.K // 2 + 2 * m.N * (m.K // m.group) + 8 * m.nnz + 2 * m.M * m.K
-            + (2 if fused else 4) * m.M * m.N)
+    side = 32 * m.N if m.lut is not None else 2 * m.N * (m.K // m.group)    # per-row table | group scales
+    return (m.N * m.K // 2 + side + 8 * m.nnz + 2 * m.M * m.K + (2 if fused else 4) * m.M * m.N)
 
 
 def cpu_baseline(cfg, args, total_flops_per_step):
@@ -57,7 +57,7 @@ def cpu_baseline(cfg, args, total_flops_per_step):
     for layer in range(layers):                 # whole matrices, in stack order, until the time budget is used
         for i, (name, N, K) in enumerate(cfg["block"]):
             m = make_oracle_matrix(synth.matrix_seed(args.data_seed, layer, i), M, N, K, cfg["group"],
-                                   cfg["density"], cfg["mask"])
+                                   cfg["density"], cfg["mask"], fmt=args.format)
             t0 = time.perf_counter()
             ozo.zo_step([m], args.seed, 0, cfg["eps"], cfg["lr"])
             t_spent += time.perf_counter() - t0
@@ -197,6 +197,9 @@ def main():
     ap.add_argument("--m", type=int, default=None, help="override the token count")
     ap.add_argument("--density", type=float, default=None)
     ap.add_argument("--tile", default="f16", choices=["f16", "bf16"])
+    ap.add_argument("--format", default="uniform", choices=["uniform", "lut"],
+                    help="4-bit format of the frozen part: uniform codes with group scales (the workloads' format) or "
+                         "the non-uniform one, a table of 16 fp16 centroids per output row")
     ap.add_argument("--unfused-loss", action="store_true", help="write y and run the separate loss kernel")
     ap.add_argument("--tile-config", type=int, default=0, choices=[0, 1, 2],
                     help="0: the library chooses (few-token path for M <= 64); 1 / 2: force the tiled kernel with "
@@ -266,7 +269,7 @@ def main():
             log(f"[bench] built {count[0]} matrices ({time.perf_counter() - t0:.1f} s)")
 
     mats, cfg = stack.build_stack(args.workload, args.data_seed, "cuda", M=args.m, layers=args.layers,
-                                  density=args.density, progress=progress)
+                                  density=args.density, progress=progress, fmt=args.format)
     if args.density is not None:
         cfg["density"] = args.density
     torch.cuda.synchronize()
@@ -302,7 +305,8 @@ def main():
     # ---- the dominant kernel alone: the library brackets every forward-kernel launch of a few more
     #      steps with events on the launch stream (szo_kernel_timing) ----
     fwd_flops = sum(2.0 * m.M * m.N * m.K for m in mats)
-    few = all(m.M <= 64 for m in mats) and dt == szo.TILE_F16 and args.tile_config == 0   # the library's few-token path
+    few = (all(m.M <= 64 for m in mats) and dt == szo.TILE_F16 and args.tile_config == 0
+           and args.format == "uniform")                                                 # the library's few-token path
     reps = args.steps if args.kernel_reps is None else max(1, args.kernel_reps)
     szo.szo_kernel_timing(True)
     for s in range(reps):
@@ -329,7 +333,8 @@ def main():
     else:
         roof = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None}
-    if (args.layers is None and args.m is None and args.density is None and flags and dt == szo.TILE_F16 and args.tile_config == 0):
+    if (args.layers is None and args.m is None and args.density is None and flags and dt == szo.TILE_F16
+            and args.tile_config == 0 and args.format == "uniform"):
         roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(args.workload)
     roof.update({"kernel": kernel, "avg_launch_us": round(1e3 * k_ms, 2), "launches_timed": launches,
                  "flops_per_launch": launch_flops, "bytes_per_launch": launch_bytes})
@@ -358,7 +363,8 @@ def main():
         "scaling": "weak", "vs_baseline": None,
         "dtype": "f16" if dt == szo.TILE_F16 else "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {len(mats)} matrices ({len(mats) // len(cfg['block'])} block(s) of "
-                               f"{[b[0] for b in cfg['block']]}), M={M} tokens, int4 group {cfg['group']}, "
+                               f"{[b[0] for b in cfg['block']]}), M={M} tokens, "
+                               + (f"int4 group {cfg['group']}, " if args.format == "uniform" else "4-bit table format, ") +
                                f"mask {cfg['density']:g} {cfg['mask']}, eps={eps}, lr={lr}",
                    "loss": "fused into the forward epilogue" if flags else "separate kernel",
                    "tile": args.tile, "accumulate": "f32", "loss_accumulate": "f64"},

@@ -73,7 +73,21 @@ typedef struct szo_linear_desc {
   float*          sp_val;   /* device, fp32  [nnz] same order; read-only in forwards    */
   float*          y;        /* device, fp32  [M,N] output (may be NULL in szo_linear_fwd_mse) */
   const void*     target;   /* device, bf16  [M,N]; only read by the loss-fusing calls  */
+  const void*     lut;      /* device, fp16  [N,16] row-major, 16-byte aligned; SZO_FORMAT_LUT only */
+  int32_t  format;          /* SZO_FORMAT_UNIFORM (0) or SZO_FORMAT_LUT                  */
+  int32_t  reserved;        /* 0                                                         */
 } szo_linear_desc;
+
+/* Formats of the frozen 4-bit part (Section 3.5 allows any post-training quantiser; Appendix C.5,
+ * "Integration with weight quantization method", distinguishes uniform and non-uniform ones and
+ * has both dequantised before the SparseAdd form of the product):
+ *   SZO_FORMAT_UNIFORM  dq[n,k] = (code - 8) * scales[n, k/group]
+ *   SZO_FORMAT_LUT      dq[n,k] = lut[n][code]: 16 fp16 centroids per output row, no scales
+ *                       (`scales` may be NULL and `group` is ignored).  fp16 tile only; such a
+ *                       layer always takes the tiled kernel, whatever its token count.
+ * In both, the sensitive entries are ADDED to the dequantised tile. */
+#define SZO_FORMAT_UNIFORM 0
+#define SZO_FORMAT_LUT 1
 
 /* Banded device layout of the frozen quantised part.  The weights are read exactly once per
  * forward, by waves that each own a band of 64 consecutive rows of W, so codes and scales are
@@ -177,6 +191,15 @@ int szo_tcsr_build(int64_t N, int64_t K, const uint32_t* flat_sorted, int64_t nn
 int szo_quantize_pack(const float* W, int64_t N, int64_t K, int group, const uint32_t* mask_flat,
                       int64_t nnz, uint8_t* q_out, uint16_t* scales_out, float* sp_val_out);
 
+/* The same decomposition with the non-uniform format (SZO_FORMAT_LUT).  The paper fixes no
+ * codebook; this one is the plainest deterministic choice: masked weights are set to zero, a
+ * row's 16 centroids are its order statistics at ranks (2c+1)K/32, c = 0..15 (the medians of 16
+ * equal-mass bins), rounded to fp16, and a weight's code is the index of the nearest centroid
+ * (distance in fp64, ties to the lower index).  Needs K % 32 == 0.  lut_out: host fp16 bit
+ * patterns [N,16], non-decreasing along a row; q_out as in szo_quantize_pack. */
+int szo_quantize_pack_lut(const float* W, int64_t N, int64_t K, const uint32_t* mask_flat,
+                          int64_t nnz, uint8_t* q_out, uint16_t* lut_out, float* sp_val_out);
+
 /* Sizes of the banded device arrays: bytes of qweight, elements of scales (0 on bad shapes). */
 size_t szo_qweight_bytes(int64_t N, int64_t K);
 size_t szo_scales_count(int64_t N, int64_t K, int group);
@@ -184,7 +207,8 @@ size_t szo_scales_count(int64_t N, int64_t K, int group);
 /* Row-major host arrays (q [N,K/2], scales fp16 bits [N,K/group], as written by
  * szo_quantize_pack) -> banded device layout described above, into host buffers of
  * szo_qweight_bytes / szo_scales_count elements that the caller then copies to the device.
- * Pure data movement.  Errors: SZO_EINVAL on null pointers, K % 64 != 0 or K % group != 0. */
+ * Pure data movement.  scales and scales_banded may both be NULL (SZO_FORMAT_LUT: codes only;
+ * group is then ignored).  Errors: SZO_EINVAL on null pointers, K % 64 != 0 or K % group != 0. */
 int szo_layout_weights(const uint8_t* q, const uint16_t* scales, int64_t N, int64_t K, int group,
                        uint8_t* q_banded, uint16_t* scales_banded);
 

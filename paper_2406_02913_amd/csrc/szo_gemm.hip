@@ -62,6 +62,7 @@ struct FwdParams {
   double loss_scale;
   int first_block;          // grouped launch: id of this entry's first workgroup (a multiple of 8)
   int pad_;
+  const uint16_t* lut;      // fp16 [N,16], table format only
 };
 
 // floor(v / d) for 32-bit v with a precomputed multiplier (Granlund-Montgomery, round-up form).
@@ -176,7 +177,7 @@ template <> struct Frag<SZO_TILE_BF16> {
 // `bid` is the workgroup's id inside this forward (0 .. grid_m*grid_n - 1); its residue mod 8 is the
 // XCD the workgroup runs on, both in a launch of its own and in a grouped launch (entries start at
 // multiples of 8).
-template <int WAVES_M, int WAVES_N, int WMB, int WNB, int DT, bool FUSE_LOSS>
+template <int WAVES_M, int WAVES_N, int WMB, int WNB, int DT, bool FUSE_LOSS, int FMT>
 __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bid) {
   constexpr int NWAVES = WAVES_M * WAVES_N;
   constexpr int BM = 32 * WMB * WAVES_M, BN = 32 * WNB * WAVES_N;
@@ -395,6 +396,107 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bi
       }
     };
 
+    if constexpr (FMT == SZO_FORMAT_LUT) {
+      // ---- table format: dq[n,k] = lut[n][code] (non-uniform 4-bit quantisers, Appendix C.5) -------
+      // gfx950 has no register-indexed look-up, so the table of a row is held as four byte planes (low
+      // and high bytes of entries 0-7 and of entries 8-15, two registers each) and looked up with the
+      // byte-permute instruction, four codes at a time: low 3 bits of the codes select inside a plane,
+      // bit 3 picks the plane.  That only pays if a lane keeps ONE row's table for the whole K loop:
+      // lane l stages row l of the band, all 64 columns of a tile (32 bytes of codes, two 16-byte loads).
+      static_assert(DT == SZO_TILE_F16 && SCATTER_IN_SLOTS, "table format: fp16 tile, 32-slot schedule");
+      const int lrow = wave * 64 + lane;                           // row of the weight tile
+      const uint8_t* const qr = p.qweight + ((size_t)min(band, p.bands - 1) * (size_t)nk * 64 + (size_t)lane) * 32;
+      u32x4 qv[2];
+      auto load_qv = [&](int kt, int h) {
+        qv[h] = *reinterpret_cast<const u32x4*>(qr + (size_t)min(kt, nk - 1) * (64 * BK / 2) + 16 * h);
+      };
+      uint32_t lo_a0, lo_a1, lo_b0, lo_b1, hi_a0, hi_a1, hi_b0, hi_b1;
+      {
+        // rows past N re-read the last row's table: their outputs are never used
+        const u32x4* const lp = reinterpret_cast<const u32x4*>(p.lut + (size_t)min(n0 + lrow, p.N - 1) * 16);
+        const u32x4 a = lp[0], b = lp[1];                          // entries 0-7 and 8-15, two per word
+        lo_a0 = __builtin_amdgcn_perm(a[1], a[0], 0x06040200u); lo_a1 = __builtin_amdgcn_perm(a[3], a[2], 0x06040200u);
+        hi_a0 = __builtin_amdgcn_perm(a[1], a[0], 0x07050301u); hi_a1 = __builtin_amdgcn_perm(a[3], a[2], 0x07050301u);
+        lo_b0 = __builtin_amdgcn_perm(b[1], b[0], 0x06040200u); lo_b1 = __builtin_amdgcn_perm(b[3], b[2], 0x06040200u);
+        hi_b0 = __builtin_amdgcn_perm(b[1], b[0], 0x07050301u); hi_b1 = __builtin_amdgcn_perm(b[3], b[2], 0x07050301u);
+      }
+      // Slots 3d, 3d+1, 3d+2 turn code word d (columns 8d .. 8d+7) into chunk d of the row:
+      //   selectors and plane masks  ->  eight look-ups and four selects  ->  interleave and store.
+      // Even codes (0,2,4,6) sit in the low nibbles of the word's bytes, odd ones in the high nibbles;
+      // the chunk keeps the element order (0,4)(1,5)(2,6)(3,7) that the activations are staged in.
+      // Slots 24, 27 and 30 scatter the tile's sensitive entries as in the uniform format.
+      uint32_t sel_e = 0, sel_o = 0, m_e = 0, m_o = 0, lo_e = 0, hi_e = 0, lo_o = 0, hi_o = 0;
+      u32x4 outw;
+      uint32_t sc_pos = 0xFFFFu;
+      float sc_val = 0.0f, sc_old = 0.0f;
+      uint16_t* sc_addr = nullptr;
+      auto make_slice = [&](int dst, int load_kt) {
+        return [&, dst, load_kt](int s) {
+          if (s < 24) {
+            const int d = s / 3, ph = s % 3;
+            if (ph == 0) {
+              const uint32_t q = qv[d >> 2][d & 3];
+              sel_e = q & 0x07070707u;
+              sel_o = (q >> 4) & 0x07070707u;
+              // 0xFF in the bytes whose code has bit 3 set: byte 1 of the constant, else byte 0
+              m_e = __builtin_amdgcn_perm(0u, 0x0000FF00u, (q >> 3) & 0x01010101u);
+              m_o = __builtin_amdgcn_perm(0u, 0x0000FF00u, (q >> 7) & 0x01010101u);
+              if ((d & 3) == 3) load_qv(load_kt, d >> 2);          // codes consumed: reload in place
+            } else if (ph == 1) {
+              auto pick = [](uint32_t m, uint32_t b, uint32_t a) { return (m & b) | (~m & a); };
+              lo_e = pick(m_e, __builtin_amdgcn_perm(lo_b1, lo_b0, sel_e), __builtin_amdgcn_perm(lo_a1, lo_a0, sel_e));
+              hi_e = pick(m_e, __builtin_amdgcn_perm(hi_b1, hi_b0, sel_e), __builtin_amdgcn_perm(hi_a1, hi_a0, sel_e));
+              lo_o = pick(m_o, __builtin_amdgcn_perm(lo_b1, lo_b0, sel_o), __builtin_amdgcn_perm(lo_a1, lo_a0, sel_o));
+              hi_o = pick(m_o, __builtin_amdgcn_perm(hi_b1, hi_b0, sel_o), __builtin_amdgcn_perm(hi_a1, hi_a0, sel_o));
+            } else {
+              outw[0] = __builtin_amdgcn_perm(hi_e, lo_e, 0x06020400u);      // codes 0, 4
+              outw[1] = __builtin_amdgcn_perm(hi_o, lo_o, 0x06020400u);      // codes 1, 5
+              outw[2] = __builtin_amdgcn_perm(hi_e, lo_e, 0x07030501u);      // codes 2, 6
+              outw[3] = __builtin_amdgcn_perm(hi_o, lo_o, 0x07030501u);      // codes 3, 7
+              *reinterpret_cast<u32x4*>(ldsB + dst * BN * BK + chunk_off(lrow, d)) = outw;
+            }
+          }
+          const bool active = (uint32_t)lane < sc_cnt;
+          if (s == 24) {
+            const uint32_t e = active ? sc_e0 + lane : 0u;
+            sc_pos = wp[e];
+            sc_val = wv[e];
+          } else if (s == 27) {                         // every dense word of the tile is written by slot 23
+            const bool ok = active && sc_pos != 0xFFFFu;
+            sc_addr = ok ? ldsB + dst * BN * BK + sc_pos : sink16 + wave * 64 + lane;
+            sc_val = ok ? sc_val : 0.0f;
+            sc_old = Frag<DT>::load(sc_addr);
+          } else if (s == 30) {
+            Frag<DT>::store(sc_addr, sc_old + sc_val);
+          }
+        };
+      };
+
+      __builtin_amdgcn_s_setprio(1);
+      load_qv(0, 0);
+      load_qv(0, 1);
+      tile_lo = __builtin_amdgcn_readfirstlane(t_lo);
+      band_end = __builtin_amdgcn_readfirstlane(t_end);
+      prepare_scatter(0);
+      {
+        auto slice = make_slice(0, 1);
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s) slice(s);
+      }
+      if (big_hi > big_lo) scatter_range(big_lo, big_hi, 0);
+      for (int kt = 0; kt < nk; kt += 2) {
+        __syncthreads();                       // tile kt complete in buffer 0; buffer 1 no longer read
+        prepare_scatter(kt + 1);
+        run_tile(0, make_slice(1, kt + 2));
+        if (big_hi > big_lo) scatter_range(big_lo, big_hi, 1);
+        if (kt + 1 < nk) {
+          __syncthreads();
+          prepare_scatter(kt + 2);
+          run_tile(1, make_slice(0, kt + 3));
+          if (big_hi > big_lo) scatter_range(big_lo, big_hi, 0);
+        }
+      }
+    } else {
     // ---- slices ---------------------------------------------------------------------------------
     // Dense part: unit u = code word u%4 of row half u/4; DSPU slots per unit; the unit's four
     // output words are spread 4 | 2,2 | 2,1,1 | 1,1,1,1 over them.  In the 32-slot schedule the
@@ -512,6 +614,7 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bi
         if (big_hi > big_lo) scatter_range(big_lo, big_hi, 0);
       }
     }
+    }  // uniform format
   } else {
     // =============================== activation wave ===========================================
     const int xt = tid - 64 * W_WAVES;
@@ -661,9 +764,9 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bi
   }
 }
 
-template <int WAVES_M, int WAVES_N, int WMB, int WNB, int DT, bool FUSE_LOSS>
+template <int WAVES_M, int WAVES_N, int WMB, int WNB, int DT, bool FUSE_LOSS, int FMT>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdParams p) {
-  linear_fwd_body<WAVES_M, WAVES_N, WMB, WNB, DT, FUSE_LOSS>(p, (int)blockIdx.x);
+  linear_fwd_body<WAVES_M, WAVES_N, WMB, WNB, DT, FUSE_LOSS, FMT>(p, (int)blockIdx.x);
 }
 
 // Grouped launch: every forward of a step (all matrices, both signs) in one grid, so that the only
@@ -671,7 +774,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdP
 // `table` holds one FwdParams per forward, ordered by first_block; a workgroup finds its entry by
 // binary search and reads it through the constant address space (scalar loads into scalar registers).
 // Workgroups between an entry's last tile and the next multiple of 8 have nothing to do.
-template <int WAVES_M, int WAVES_N, int WMB, int WNB, int DT, bool FUSE_LOSS>
+template <int WAVES_M, int WAVES_N, int WMB, int WNB, int DT, bool FUSE_LOSS, int FMT>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_table_kernel(const FwdParams* table, int n_entries) {
   constexpr int W = (int)(sizeof(FwdParams) / 4), FB = (int)(offsetof(FwdParams, first_block) / 4);
   static_assert(sizeof(FwdParams) % 4 == 0 && offsetof(FwdParams, first_block) % 4 == 0, "table entry is read as words");
@@ -687,7 +790,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_table_kerne
   const FwdParams p = __builtin_bit_cast(FwdParams, raw);
   const int bid = (int)blockIdx.x - p.first_block;
   if (bid >= p.grid_m * p.grid_n) return;
-  linear_fwd_body<WAVES_M, WAVES_N, WMB, WNB, DT, FUSE_LOSS>(p, bid);
+  linear_fwd_body<WAVES_M, WAVES_N, WMB, WNB, DT, FUSE_LOSS, FMT>(p, bid);
 }
 
 // ---- host side -----------------------------------------------------------------------------
@@ -705,15 +808,19 @@ static int validate_desc(const szo_linear_desc* d, int sign, bool need_y, bool n
   if (d->M < 0 || d->N < 0 || d->K <= 0 || d->nnz < 0) return SZO_EINVAL;
   if (sign < -1 || sign > 1) return SZO_EINVAL;
   if (d->tile_dtype != SZO_TILE_F16 && d->tile_dtype != SZO_TILE_BF16) return SZO_EINVAL;
-  if (d->group <= 0 || d->K % d->group) return SZO_EINVAL;
+  if (d->format != SZO_FORMAT_UNIFORM && d->format != SZO_FORMAT_LUT) return SZO_EINVAL;
+  const bool table_format = d->format == SZO_FORMAT_LUT;
+  if (!table_format && (d->group <= 0 || d->K % d->group)) return SZO_EINVAL;
   if (d->nnz_base & 3) return SZO_EINVAL;
-  if (d->group != 32 && d->group != 64 && d->group != 128) return SZO_EUNSUPPORTED;
+  if (!table_format && d->group != 32 && d->group != 64 && d->group != 128) return SZO_EUNSUPPORTED;
+  if (table_format && d->tile_dtype != SZO_TILE_F16) return SZO_EUNSUPPORTED;
   if (d->K % BK) return SZO_EUNSUPPORTED;
   if ((uint64_t)d->N * (uint64_t)d->K > 0xFFFFFFFFull) return SZO_EUNSUPPORTED;
   if (d->M > 0x7FFFFFFF || d->N > 0x7FFFFFFF || d->nnz > 0xFFFFFFFFll) return SZO_EUNSUPPORTED;
   if ((uint64_t)d->M * (uint64_t)d->N > 0xFFFFFFFFull) return SZO_EUNSUPPORTED;
   if (d->M == 0 || d->N == 0) return SZO_OK;
-  if (!d->x || !d->qweight || !d->scales || !d->tile_ptr) return SZO_EINVAL;
+  if (!d->x || !d->qweight || !d->tile_ptr) return SZO_EINVAL;
+  if (table_format ? (!d->lut || ((uintptr_t)d->lut & 15)) : !d->scales) return SZO_EINVAL;
   if (d->nnz > 0 && (!d->sp_idx || !d->sp_val)) return SZO_EINVAL;
   if (need_y && !d->y) return SZO_EINVAL;
   if (need_target && !d->target) return SZO_EINVAL;
@@ -724,7 +831,7 @@ static int validate_desc(const szo_linear_desc* d, int sign, bool need_y, bool n
   return SZO_OK;
 }
 
-template <int WAVES_M, int WAVES_N, int WMB, int WNB, int DT, bool FUSE>
+template <int WAVES_M, int WAVES_N, int WMB, int WNB, int DT, bool FUSE, int FMT = SZO_FORMAT_UNIFORM>
 static int launch(FwdParams& p, hipStream_t stream) {
   constexpr int BM = 32 * WMB * WAVES_M, BN = 32 * WNB * WAVES_N;
   p.grid_m = (p.M + BM - 1) / BM;
@@ -734,7 +841,7 @@ static int launch(FwdParams& p, hipStream_t stream) {
   constexpr size_t main_bytes = 2 * (size_t)(BM + BN) * BK * sizeof(uint16_t) + (size_t)(BN / 64) * (kWindow * 6 + 128);
   constexpr size_t target_bytes = FUSE ? (size_t)BM * (BN * 2 + 32) : 0;      // staged target tile of the fused loss
   constexpr size_t lds_bytes = main_bytes > target_bytes ? main_bytes : target_bytes;
-  auto kern = linear_fwd_kernel<WAVES_M, WAVES_N, WMB, WNB, DT, FUSE>;
+  auto kern = linear_fwd_kernel<WAVES_M, WAVES_N, WMB, WNB, DT, FUSE, FMT>;
   static bool attr_set = false;     // per instantiation
   if (!attr_set) {
     SZO_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
@@ -748,8 +855,9 @@ static int launch(FwdParams& p, hipStream_t stream) {
 }
 
 // Which workgroup tile a shape runs with, and how many workgroups (= loss partials) that makes.
-static int plan_tiles(int M, int N, int* blocks_out) {
+static int plan_tiles(int M, int N, int format, int* blocks_out) {
   int cfg = g_tile_config;
+  if (format == SZO_FORMAT_LUT) cfg = 2;          // the table format exists for the 256x256 tile only
   if (cfg == 0) {
     const int64_t big_blocks = (int64_t)((M + 255) / 256) * ((N + 255) / 256);
     cfg = big_blocks >= 192 ? 2 : 1;
@@ -764,7 +872,7 @@ static int plan_tiles(int M, int N, int* blocks_out) {
 template <int DT, bool FUSE>
 static int dispatch_tile(FwdParams& p, hipStream_t stream) {
   int blocks;
-  if (plan_tiles(p.M, p.N, &blocks) == 2) return launch<2, 4, 4, 2, DT, FUSE>(p, stream);
+  if (plan_tiles(p.M, p.N, SZO_FORMAT_UNIFORM, &blocks) == 2) return launch<2, 4, 4, 2, DT, FUSE>(p, stream);
   return launch<2, 2, 2, 2, DT, FUSE>(p, stream);
 }
 
@@ -776,6 +884,7 @@ static int fill_params(FwdParams& p, const szo_linear_desc* d, uint64_t seed, ui
   p.x = (const uint16_t*)d->x;
   p.qweight = d->qweight;
   p.scales = (const uint16_t*)d->scales;
+  p.lut = (const uint16_t*)d->lut;
   p.tile_ptr = d->tile_ptr;
   p.sp_idx = d->sp_idx;
   p.sp_val = d->sp_val;
@@ -783,7 +892,7 @@ static int fill_params(FwdParams& p, const szo_linear_desc* d, uint64_t seed, ui
   p.target = (const uint16_t*)d->target;
   p.M = (int)d->M; p.N = (int)d->N; p.K = (int)d->K;
   p.nnz = (uint32_t)d->nnz;
-  p.group_shift = ilog2_exact(d->group);
+  p.group_shift = d->format == SZO_FORMAT_LUT ? 0 : ilog2_exact(d->group);
   p.ktiles = p.K / BK;
   p.bands = (p.N + SZO_TILE_ROWS - 1) / SZO_TILE_ROWS;
   {
@@ -808,6 +917,9 @@ static int run_forward(const szo_linear_desc* d, uint64_t seed, uint64_t step, i
   FwdParams p;
   const int frc = fill_params(p, d, seed, step, sign, eps, partials, scale);
   if (frc != SZO_OK) return frc;
+  if (d->format == SZO_FORMAT_LUT)
+    return fuse ? launch<2, 4, 4, 2, SZO_TILE_F16, true, SZO_FORMAT_LUT>(p, stream)
+                : launch<2, 4, 4, 2, SZO_TILE_F16, false, SZO_FORMAT_LUT>(p, stream);
   if (d->tile_dtype == SZO_TILE_F16)
     return fuse ? dispatch_tile<SZO_TILE_F16, true>(p, stream) : dispatch_tile<SZO_TILE_F16, false>(p, stream);
   return fuse ? dispatch_tile<SZO_TILE_BF16, true>(p, stream) : dispatch_tile<SZO_TILE_BF16, false>(p, stream);
@@ -815,13 +927,13 @@ static int run_forward(const szo_linear_desc* d, uint64_t seed, uint64_t step, i
 
 static double* partial_area(void* workspace) { return (double*)((char*)workspace + kWorkspaceHeader); }
 
-template <int DT>
+template <int DT, int FMT = SZO_FORMAT_UNIFORM>
 static int launch_table(const FwdParams* table_dev, int entries, int64_t blocks, hipStream_t stream) {
   constexpr int BM = 256, BN = 256;
   constexpr size_t main_bytes = 2 * (size_t)(BM + BN) * BK * sizeof(uint16_t) + (size_t)(BN / 64) * (kWindow * 6 + 128);
   constexpr size_t target_bytes = (size_t)BM * (BN * 2 + 32);
   constexpr size_t lds_bytes = main_bytes > target_bytes ? main_bytes : target_bytes;
-  auto kern = linear_fwd_table_kernel<2, 4, 4, 2, DT, true>;
+  auto kern = linear_fwd_table_kernel<2, 4, 4, 2, DT, true, FMT>;
   static bool attr_set = false;
   if (!attr_set) {
     SZO_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
@@ -836,7 +948,7 @@ static int launch_table(const FwdParams* table_dev, int entries, int64_t blocks,
 
 // Both forwards of every matrix of a step as ONE launch of 256x256 tiles with the loss fused.
 // Returns SZO_EUNSUPPORTED when the stack does not qualify (the caller then launches per matrix):
-// mixed tile types, a table that does not fit the workspace, or too few tiles to fill the chip.
+// mixed tile types or formats, a table that does not fit the workspace, or too few tiles to fill the chip.
 // On success *partials_per_sign is the number of loss partials of one sign: the "+" partials are
 // partials[0 .. T), the "-" partials partials[T .. 2T).
 static int grouped_forwards(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t step, float eps,
@@ -847,7 +959,7 @@ static int grouped_forwards(const szo_linear_desc* descs, int n, uint64_t seed, 
   for (int i = 0; i < n; ++i) {
     const szo_linear_desc* d = &descs[i];
     if (d->M == 0 || d->N == 0) continue;
-    if (d->tile_dtype != descs[0].tile_dtype) return SZO_EUNSUPPORTED;
+    if (d->tile_dtype != descs[0].tile_dtype || d->format != descs[0].format) return SZO_EUNSUPPORTED;
     T += (int64_t)((d->M + 255) / 256) * ((d->N + 255) / 256);
     ++live;
   }
@@ -877,6 +989,8 @@ static int grouped_forwards(const szo_linear_desc* descs, int n, uint64_t seed, 
   int rc = stage_table(table.data(), sizeof(FwdParams) * table.size(), table_dev, stream);
   if (rc != SZO_OK) return rc;
   *partials_per_sign = T;
+  if (descs[0].format == SZO_FORMAT_LUT)
+    return launch_table<SZO_TILE_F16, SZO_FORMAT_LUT>((const FwdParams*)table_dev, (int)table.size(), first_block, stream);
   if (descs[0].tile_dtype == SZO_TILE_F16)
     return launch_table<SZO_TILE_F16>((const FwdParams*)table_dev, (int)table.size(), first_block, stream);
   return launch_table<SZO_TILE_BF16>((const FwdParams*)table_dev, (int)table.size(), first_block, stream);
@@ -920,7 +1034,7 @@ int szo_linear_fwd_mse(const szo_linear_desc* desc, uint64_t seed, uint64_t step
     return reduce_partials(partial_area(workspace), nb, loss_acc, (hipStream_t)stream);
   }
   int blocks;
-  plan_tiles((int)desc->M, (int)desc->N, &blocks);
+  plan_tiles((int)desc->M, (int)desc->N, desc->format, &blocks);
   if (blocks < 0 || blocks > kMaxLossPartials) return SZO_EUNSUPPORTED;
   rc = run_forward(desc, seed, step, sign, eps, partial_area(workspace), scale, (hipStream_t)stream);
   if (rc != SZO_OK) return rc;
@@ -939,7 +1053,7 @@ int szo_zo_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t ste
     if (descs[i].nnz > 0 && ((uintptr_t)descs[i].sp_val & 15)) return SZO_EINVAL;
     if (descs[i].M == 0 || descs[i].N == 0) continue;
     int blocks;
-    plan_tiles((int)descs[i].M, (int)descs[i].N, &blocks);
+    plan_tiles((int)descs[i].M, (int)descs[i].N, descs[i].format, &blocks);
     if (blocks < 0) return SZO_EUNSUPPORTED;
     total += blocks;
   }
@@ -979,7 +1093,7 @@ int szo_zo_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t ste
         const double scale = 1.0 / ((double)d->M * (double)d->N);
         if (fuse) {
           int blocks;
-          plan_tiles((int)d->M, (int)d->N, &blocks);
+          plan_tiles((int)d->M, (int)d->N, d->format, &blocks);
           rc = run_forward(d, seed, step, sign, eps, part, scale, s);
           part += blocks;
         } else {

@@ -251,6 +251,60 @@ int szo_quantize_pack(const float* W, int64_t N, int64_t K, int group, const uin
   return bad ? SZO_EINVAL : SZO_OK;
 }
 
+int szo_quantize_pack_lut(const float* W, int64_t N, int64_t K, const uint32_t* mask_flat, int64_t nnz,
+                          uint8_t* q_out, uint16_t* lut_out, float* sp_val_out) {
+  if (!W || !q_out || !lut_out || N <= 0 || K <= 0 || nnz < 0) return SZO_EINVAL;
+  if (nnz > 0 && (!mask_flat || !sp_val_out)) return SZO_EINVAL;
+  if (K % 32) return SZO_EINVAL;
+  if ((uint64_t)N * (uint64_t)K > 0xFFFFFFFFull) return SZO_EUNSUPPORTED;
+  const uint64_t total = (uint64_t)N * (uint64_t)K;
+  std::vector<uint32_t> row_start((size_t)N + 1, 0u);
+  for (int64_t j = 0; j < nnz; ++j) {
+    if (mask_flat[j] >= total) return SZO_EINVAL;
+    sp_val_out[j] = W[mask_flat[j]];
+    row_start[mask_flat[j] / (uint64_t)K + 1] += 1u;
+  }
+  for (int64_t n = 0; n < N; ++n) row_start[(size_t)n + 1] += row_start[(size_t)n];
+  std::vector<uint32_t> cols((size_t)nnz);
+  {
+    std::vector<uint32_t> fill(row_start.begin(), row_start.end() - 1);
+    for (int64_t j = 0; j < nnz; ++j) cols[fill[mask_flat[j] / (uint64_t)K]++] = (uint32_t)(mask_flat[j] % (uint64_t)K);
+  }
+  int bad = 0;
+  parallel_rows(N, 8 * K, [&](int64_t lo, int64_t hi) {
+    std::vector<float> row((size_t)K), sorted((size_t)K);
+    for (int64_t n = lo; n < hi; ++n) {
+      std::memcpy(row.data(), W + n * K, sizeof(float) * (size_t)K);
+      for (uint32_t p = row_start[(size_t)n]; p < row_start[(size_t)n + 1]; ++p) row[cols[p]] = 0.0f;
+      sorted = row;
+      std::sort(sorted.begin(), sorted.end());
+      double centroid[16];
+      for (int c = 0; c < 16; ++c) {
+        const uint16_t b = f32_to_f16_bits(sorted[(size_t)((2 * c + 1) * (K / 32))]);
+        if ((b & 0x7C00u) == 0x7C00u) bad = 1;
+        lut_out[n * 16 + c] = b;
+        centroid[c] = (double)f16_bits_to_f32(b);
+      }
+      uint8_t* q = q_out + n * (K / 2);
+      for (int64_t k = 0; k < K; k += 2) {
+        int code[2];
+        for (int h = 0; h < 2; ++h) {
+          const double w = (double)row[(size_t)(k + h)];
+          int best = 0;
+          double bd = std::fabs(w - centroid[0]);
+          for (int c = 1; c < 16; ++c) {
+            const double d = std::fabs(w - centroid[c]);
+            if (d < bd) { bd = d; best = c; }                 // strict: ties keep the lower index
+          }
+          code[h] = best;
+        }
+        q[k / 2] = (uint8_t)(code[0] | (code[1] << 4));
+      }
+    }
+  });
+  return bad ? SZO_EINVAL : SZO_OK;
+}
+
 size_t szo_qweight_bytes(int64_t N, int64_t K) {
   if (N <= 0 || K <= 0 || K % 64) return 0;
   return (size_t)((N + 63) / 64) * 64 * (size_t)(K / 2);
@@ -263,9 +317,10 @@ size_t szo_scales_count(int64_t N, int64_t K, int group) {
 
 int szo_layout_weights(const uint8_t* q, const uint16_t* scales, int64_t N, int64_t K, int group,
                        uint8_t* q_banded, uint16_t* scales_banded) {
-  if (!q || !scales || !q_banded || !scales_banded || N <= 0 || K <= 0 || group <= 0) return SZO_EINVAL;
-  if (K % 64 || K % group) return SZO_EINVAL;
-  const int64_t bands = (N + 63) / 64, ktiles = K / 64, groups = K / group;
+  if (!q || !q_banded || N <= 0 || K <= 0) return SZO_EINVAL;
+  if ((scales == nullptr) != (scales_banded == nullptr)) return SZO_EINVAL;
+  if (K % 64 || (scales && (group <= 0 || K % group))) return SZO_EINVAL;
+  const int64_t bands = (N + 63) / 64, ktiles = K / 64, groups = scales ? K / group : 0;
   parallel_rows(bands, 64 * K, [&](int64_t lo, int64_t hi) {
     for (int64_t b = lo; b < hi; ++b) {
       for (int64_t t = 0; t < ktiles; ++t) {

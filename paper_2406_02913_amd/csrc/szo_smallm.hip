@@ -507,7 +507,7 @@ static size_t small_lds_bytes() {
 
 bool small_m_eligible(const szo_linear_desc* d) {
   return d->M >= 1 && d->M <= SM_ROWS && d->N >= 1 && (d->K % 128) == 0 && d->group >= 32 &&
-         d->tile_dtype == SZO_TILE_F16 &&
+         d->tile_dtype == SZO_TILE_F16 && d->format == SZO_FORMAT_UNIFORM &&
          (uint64_t)((d->N + 63) / 64 * 64) * (uint64_t)d->K / 2 < (1ull << 32);   // 32-bit code offsets
 }
 

@@ -17,6 +17,7 @@ OK, EINVAL, EUNSUPPORTED, ELAUNCH = 0, -1, -2, -3
 TILE_F16, TILE_BF16 = 0, 1
 TILE_ROWS, TILE_COLS = 64, 64
 STEP_FUSED_LOSS = 1
+FORMAT_UNIFORM, FORMAT_LUT = 0, 1
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
@@ -30,7 +31,8 @@ class LinearDesc(C.Structure):
                 ("nnz", C.c_int64), ("nnz_base", C.c_uint64),
                 ("x", C.c_void_p), ("qweight", C.c_void_p), ("scales", C.c_void_p),
                 ("tile_ptr", C.c_void_p), ("sp_idx", C.c_void_p), ("sp_val", C.c_void_p),
-                ("y", C.c_void_p), ("target", C.c_void_p)]
+                ("y", C.c_void_p), ("target", C.c_void_p),
+                ("lut", C.c_void_p), ("format", C.c_int32), ("reserved", C.c_int32)]
 
 
 _P = C.POINTER
@@ -51,6 +53,8 @@ _SIGS = {
     "szo_tcsr_build": (C.c_int, [C.c_int64, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]),
     "szo_quantize_pack": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_void_p, C.c_int64,
                                      C.c_void_p, C.c_void_p, C.c_void_p]),
+    "szo_quantize_pack_lut": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int64,
+                                         C.c_void_p, C.c_void_p, C.c_void_p]),
     "szo_qweight_bytes": (C.c_size_t, [C.c_int64, C.c_int64]),
     "szo_scales_count": (C.c_size_t, [C.c_int64, C.c_int64, C.c_int]),
     "szo_layout_weights": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_void_p, C.c_void_p]),
@@ -106,9 +110,11 @@ def _stream(stream):
 
 
 def make_desc(M, N, K, group, nnz, nnz_base, x, qweight, scales, tile_ptr, sp_idx, sp_val,
-              y=None, target=None, tile_dtype=TILE_F16):
+              y=None, target=None, tile_dtype=TILE_F16, lut=None):
+    """With `lut` (device fp16 [N,16]) the layer is of the non-uniform format; scales may then be None."""
     return LinearDesc(M, N, K, group, tile_dtype, nnz, nnz_base, _dev(x), _dev(qweight), _dev(scales),
-                      _dev(tile_ptr), _dev(sp_idx), _dev(sp_val), _dev(y), _dev(target))
+                      _dev(tile_ptr), _dev(sp_idx), _dev(sp_val), _dev(y), _dev(target),
+                      _dev(lut), FORMAT_UNIFORM if lut is None else FORMAT_LUT, 0)
 
 
 # ---- hot calls -------------------------------------------------------------------------------
@@ -197,6 +203,19 @@ def szo_quantize_pack(W, group, mask_flat):
     return q, scales.view(np.float16), sp_val
 
 
+def szo_quantize_pack_lut(W, mask_flat):
+    """-> (q u8 [N,K/2], lut fp16 [N,16], sp_val fp32 [nnz])."""
+    W, wp = _host(W, np.float32)
+    N, K = W.shape
+    mask, mp = _host(mask_flat, np.uint32)
+    q = np.empty((N, K // 2), dtype=np.uint8)
+    lut = np.empty((N, 16), dtype=np.uint16)
+    sp_val = np.empty(mask.size, dtype=np.float32)
+    _check("szo_quantize_pack_lut", lib.szo_quantize_pack_lut(wp, N, K, mp, mask.size, q.ctypes.data,
+                                                              lut.ctypes.data, sp_val.ctypes.data))
+    return q, lut.view(np.float16), sp_val
+
+
 def szo_qweight_bytes(N, K):
     return int(lib.szo_qweight_bytes(N, K))
 
@@ -206,9 +225,14 @@ def szo_scales_count(N, K, group):
 
 
 def szo_layout_weights(q, scales, group):
-    """Row-major host arrays -> (q_banded u8 [bytes], scales_banded fp16 [count])."""
+    """Row-major host arrays -> (q_banded u8 [bytes], scales_banded fp16 [count]).
+    scales None (non-uniform format): codes only, -> (q_banded, None)."""
     q, qp = _host(q, np.uint8)
     N, K = q.shape[0], q.shape[1] * 2
+    if scales is None:
+        qb = np.empty(szo_qweight_bytes(N, K), dtype=np.uint8)
+        _check("szo_layout_weights", lib.szo_layout_weights(qp, None, N, K, 0, qb.ctypes.data, None))
+        return qb, None
     sc, sp = _host(np.asarray(scales).view(np.uint16), np.uint16)
     qb = np.empty(szo_qweight_bytes(N, K), dtype=np.uint8)
     sb = np.empty(szo_scales_count(N, K, group), dtype=np.uint16)

@@ -7,7 +7,7 @@ from paper_2406_02913_amd import synth
 
 
 def make_oracle_matrix(seed, M, N, K, group, density=1e-3, kind="uniform", nnz=None,
-                       nnz_base=0, mask_seed=None, sigma=0.02):
+                       nnz_base=0, mask_seed=None, sigma=0.02, fmt="uniform"):
     x = synth.activations(seed, M, K)
     W = synth.dense_weight(seed, N, K, sigma)
     t = synth.target(seed, M, N)
@@ -15,9 +15,14 @@ def make_oracle_matrix(seed, M, N, K, group, density=1e-3, kind="uniform", nnz=N
     ms = seed + 1000 if mask_seed is None else mask_seed
     flat = (omask.mask_uniform if kind == "uniform" else omask.mask_heavy_tail)(N, K, k, ms)
     tile_ptr, sp_idx, perm = omask.tcsr_build(N, K, flat)
-    codes, scales, sp_val = oquant.split_and_quantize(W, sp_idx.astype(np.int64), group)
+    lut = None
+    if fmt == "lut":
+        codes, lut, sp_val = oquant.split_and_quantize_lut(W, sp_idx.astype(np.int64))
+        scales = None
+    else:
+        codes, scales, sp_val = oquant.split_and_quantize(W, sp_idx.astype(np.int64), group)
     m = Matrix(x_bits=x, codes=codes, scales=scales, group=group, sp_idx=sp_idx,
-               sp_val=sp_val, target_bits=t, nnz_base=nnz_base)
+               sp_val=sp_val, target_bits=t, nnz_base=nnz_base, lut=lut)
     m.tile_ptr = tile_ptr
     m.W = W
     m.flat_sorted = flat
@@ -25,7 +30,7 @@ def make_oracle_matrix(seed, M, N, K, group, density=1e-3, kind="uniform", nnz=N
 
 
 def clone(m):
-    c = Matrix(m.x_bits, m.codes, m.scales, m.group, m.sp_idx, m.sp_val.copy(), m.target_bits, m.nnz_base)
+    c = Matrix(m.x_bits, m.codes, m.scales, m.group, m.sp_idx, m.sp_val.copy(), m.target_bits, m.nnz_base, m.lut)
     for a in ("tile_ptr", "W", "flat_sorted"):
         if hasattr(m, a):
             setattr(c, a, getattr(m, a))
@@ -54,21 +59,24 @@ def banded_scales(scales_rowmajor_bits):
     return out.reshape(-1)
 
 
-def make_pair(seed, M, N, K, group, density=1e-3, kind="uniform", nnz=None, nnz_base=0, device="cuda"):
+def make_pair(seed, M, N, K, group, density=1e-3, kind="uniform", nnz=None, nnz_base=0, device="cuda", fmt="uniform"):
     """The same layer twice: oracle-side (numpy) and device-side (libszo host
     set-up + torch memory).  Asserts that mask, tile order, codes, scales and
     sparse values agree bit for bit before anything is computed."""
     from paper_2406_02913_amd import stack
-    o = make_oracle_matrix(seed, M, N, K, group, density, kind, nnz, nnz_base)
-    d = stack.build_linear(seed, M, N, K, group, density, kind, nnz, nnz_base, device=device, keep_host=True)
+    o = make_oracle_matrix(seed, M, N, K, group, density, kind, nnz, nnz_base, fmt=fmt)
+    d = stack.build_linear(seed, M, N, K, group, density, kind, nnz, nnz_base, device=device, keep_host=True, fmt=fmt)
     h = d.host
     assert np.array_equal(h["flat"], o.flat_sorted.astype(np.uint32))
     assert np.array_equal(h["tile_ptr"], o.tile_ptr) and np.array_equal(h["sp_idx"], o.sp_idx)
     assert np.array_equal(h["qweight"], oquant.pack_codes(o.codes))
-    assert np.array_equal(h["scales"].view(np.uint16), o.scales.view(np.uint16))
     assert np.array_equal(h["sp_val"], o.sp_val)
     assert np.array_equal(h["qweight_banded"], banded_codes(oquant.pack_codes(o.codes)))
-    assert np.array_equal(h["scales_banded"].view(np.uint16), banded_scales(o.scales.view(np.uint16)))
+    if fmt == "lut":
+        assert np.array_equal(h["lut"].view(np.uint16), o.lut.view(np.uint16))
+    else:
+        assert np.array_equal(h["scales"].view(np.uint16), o.scales.view(np.uint16))
+        assert np.array_equal(h["scales_banded"].view(np.uint16), banded_scales(o.scales.view(np.uint16)))
     return o, d
 
 
@@ -83,6 +91,6 @@ def sigma_g(mats):
     from oracle import layer
     tot = 0.0
     for m in mats:
-        y0 = layer.linear_fwd(m.x_bits, m.codes, m.scales, m.group, m.sp_idx, m.sp_val)
+        y0 = layer.linear_fwd(m.x_bits, m.codes, m.scales, m.group, m.sp_idx, m.sp_val, lut=m.lut)
         tot += float(np.sum(layer.mse_grad_on_mask(m.x_bits, y0, m.target_bits, m.sp_idx, m.codes.shape[1]) ** 2))
     return float(np.sqrt(tot))

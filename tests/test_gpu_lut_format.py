@@ -1,0 +1,144 @@
+"""GPU parity of the non-uniform (look-up table) 4-bit format: forward, fused loss, whole steps
+(grouped and per-matrix launches), validation."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import layer as olayer, philox as ophilox, zo as ozo
+from paper_2406_02913_amd import szo
+from helpers import make_pair, clone, rel_fro, sigma_g
+
+pytestmark = pytest.mark.gpu
+
+# (seed, M, N, K, density)
+SHAPES = [
+    (41, 64, 256, 256, 1e-3),         # one tile
+    (42, 100, 200, 320, 1e-2),        # ragged M and N: rows past N re-read the last row's table
+    (43, 300, 513, 1024, 1e-3),       # several tiles each way, one row past a tile boundary
+    (44, 1, 128, 64, 5e-2),           # a single token, a single K step
+    (45, 257, 130, 192, 0.0),         # k = 0: plain look-up-then-matmul
+    (46, 70, 192, 4160, 1e-1),        # 65 column tiles and > 64 entries per tile (scatter after the loop)
+]
+
+
+@pytest.fixture(autouse=True)
+def _auto_tile_config():
+    yield
+    szo.szo_set_tile_config(0)
+
+
+def _run(d, sign, eps, seed, step):
+    d.y.fill_(float("nan"))
+    szo.szo_linear_fwd(d.desc(), seed, step, sign, eps)
+    torch.cuda.synchronize()
+    return d.y.cpu().numpy()
+
+
+@pytest.mark.parametrize("tile_cfg", [0, 1])      # the table format always runs its own 256x256 kernel
+@pytest.mark.parametrize("shape", SHAPES)
+def test_forward_matches_oracle(shape, tile_cfg):
+    szo.szo_set_tile_config(tile_cfg)
+    s, M, N, K, dens = shape
+    o, d = make_pair(s, M, N, K, 128, dens, nnz_base=8, fmt="lut")
+    seed, step, eps = 4321, 2, 1e-3
+    z = ophilox.zbar(seed, step, 8, o.sp_idx.size)
+    for sign in (+1, -1, 0):
+        y = _run(d, sign, eps, seed, step)
+        assert np.isfinite(y).all()
+        yD = olayer.linear_fwd(o.x_bits, o.codes, None, 0, o.sp_idx, o.sp_val, z, sign, eps, "D", "f16", lut=o.lut)
+        yE = olayer.linear_fwd(o.x_bits, o.codes, None, 0, o.sp_idx, o.sp_val, z, sign, eps, "E", lut=o.lut)
+        # against D only the fp32 accumulation order differs: the table values are copied, not computed
+        assert rel_fro(y, yD) <= 2e-5, (sign, rel_fro(y, yD))
+        assert rel_fro(y, yE) <= 5e-3, (sign, rel_fro(y, yE))
+        assert np.max(np.abs(y - yD)) <= 1e-4 * np.sqrt(K) * 0.02 * 4 + 1e-6
+
+
+def test_every_code_of_every_row_is_looked_up():
+    # x = one-hot rows pick single weights: y[m, n] = W_eff[n, k_m] exactly (one product, no sum)
+    o, d = make_pair(47, 64, 192, 64, 128, 0.0, fmt="lut")
+    x = np.zeros((64, 64), dtype=np.uint16)
+    x[np.arange(64), np.arange(64)] = 0x3F80                      # bf16 1.0
+    d.x.copy_(torch.from_numpy(x.view(np.int16)).view(torch.bfloat16).cuda())
+    y = _run(d, 0, 0.0, 1, 0)
+    want = o.lut.astype(np.float32)[np.arange(192)[:, None], o.codes.astype(np.int64)]    # [N, K]
+    assert np.array_equal(y, want.T)
+    assert len(np.unique(o.codes)) == 16
+
+
+def test_fused_loss_and_step_match_oracle():
+    o1, d1 = make_pair(48, 96, 320, 256, 128, 5e-3, nnz_base=0, fmt="lut")
+    b2 = (o1.sp_idx.size + 3) // 4 * 4
+    o2, d2 = make_pair(49, 200, 256, 512, 128, 2e-3, nnz_base=b2, fmt="lut")
+    seed, eps, lr = 11, 1e-3, 1e-3
+    ws = szo.new_workspace()
+    # single fused-loss call
+    acc = torch.zeros(1, dtype=torch.float64, device="cuda")
+    szo.szo_linear_fwd_mse(d1.desc(with_y=False), seed, 0, +1, eps, 1.0 / (96 * 320), acc, ws)
+    z = ophilox.zbar(seed, 0, 0, o1.sp_idx.size)
+    yE = olayer.linear_fwd(o1.x_bits, o1.codes, None, 0, o1.sp_idx, o1.sp_val, z, +1, eps, "E", lut=o1.lut)
+    LE = olayer.mse_loss(yE, o1.target_bits)
+    assert abs(acc.item() - LE) <= 5e-3 * LE
+    sg = sigma_g([o1, o2])
+    results = {}
+    for cfg in (0, 3):                            # per-matrix launches, then everything as one grouped launch
+        szo.szo_set_tile_config(cfg)
+        da, db = make_pair(48, 96, 320, 256, 128, 5e-3, nnz_base=0, fmt="lut")[1], make_pair(49, 200, 256, 512, 128, 2e-3, nnz_base=b2, fmt="lut")[1]
+        scal = torch.zeros(3, dtype=torch.float64, device="cuda")
+        a, b = clone(o1), clone(o2)
+        descs = szo.desc_array([da.desc(with_y=False), db.desc(with_y=False)])
+        got = []
+        for s in range(3):
+            szo.szo_zo_step(descs, seed, s, eps, lr, scal, ws, szo.STEP_FUSED_LOSS)
+            lp, lm, g = scal.cpu().numpy()
+            r = ozo.zo_step([a, b], seed, s, eps, lr)
+            assert abs(lp - r["loss_plus"]) <= 5e-3 * r["loss_plus"]
+            assert abs(g - r["g"]) <= 1e-2 * max(abs(r["g"]), sg), (cfg, s, g, r["g"])
+            got.append((lp, lm, g))
+        for om, dd, oo in ((a, da, o1), (b, db, o2)):
+            dv_gpu = dd.sp_val.cpu().numpy().astype(np.float64) - oo.sp_val
+            dv_ref = om.sp_val.astype(np.float64) - oo.sp_val
+            assert np.linalg.norm(dv_gpu - dv_ref) <= 3e-2 * np.linalg.norm(dv_ref)
+        results[cfg] = (got, da.sp_val.cpu().numpy(), db.sp_val.cpu().numpy())
+    # same kernel body either way: bit-identical
+    assert results[0][0] == results[3][0]
+    assert np.array_equal(results[0][1], results[3][1]) and np.array_equal(results[0][2], results[3][2])
+
+
+def test_unfused_step_and_few_tokens_take_the_tiled_kernel():
+    # 16 tokens: the uniform format would take the few-token path; the table format must still be right
+    o, d = make_pair(50, 16, 256, 512, 128, 1e-2, fmt="lut")
+    seed, eps, lr = 5, 1e-3, 1e-3
+    ws = szo.new_workspace()
+    scal = torch.zeros(3, dtype=torch.float64, device="cuda")
+    om = clone(o)
+    sg = sigma_g([o])
+    for flags in (0, szo.STEP_FUSED_LOSS):
+        szo.szo_zo_step([d.desc()], seed, 0, eps, 0.0, scal, ws, flags)
+        lp, lm, g = scal.cpu().numpy()
+        r = ozo.zo_step([clone(om)], seed, 0, eps, 0.0)
+        assert abs(lp - r["loss_plus"]) <= 5e-3 * r["loss_plus"]
+        assert abs(g - r["g"]) <= 1e-2 * max(abs(r["g"]), sg)
+
+
+def test_validation_of_the_table_format():
+    o, d = make_pair(51, 64, 128, 128, 128, 1e-2, fmt="lut")
+    desc = d.desc()
+    assert desc.format == szo.FORMAT_LUT and desc.scales is None
+    desc.tile_dtype = szo.TILE_BF16
+    assert szo.lib.szo_linear_fwd(ctypes.byref(desc), 0, 0, 1, 1e-3, None) == szo.EUNSUPPORTED
+    desc = d.desc()
+    desc.lut = None
+    assert szo.lib.szo_linear_fwd(ctypes.byref(desc), 0, 0, 1, 1e-3, None) == szo.EINVAL
+    desc = d.desc()
+    desc.format = 7
+    assert szo.lib.szo_linear_fwd(ctypes.byref(desc), 0, 0, 1, 1e-3, None) == szo.EINVAL
+    # a step must not mix formats in one grouped launch, but still runs (per-matrix launches)
+    ou, du = make_pair(52, 64, 128, 128, 128, 1e-2, nnz_base=(o.sp_idx.size + 3) // 4 * 4)
+    szo.szo_set_tile_config(3)
+    ws = szo.new_workspace()
+    scal = torch.zeros(3, dtype=torch.float64, device="cuda")
+    szo.szo_zo_step([d.desc(), du.desc()], 3, 0, 1e-3, 0.0, scal, ws, szo.STEP_FUSED_LOSS)
+    r = ozo.zo_step([clone(o), clone(ou)], 3, 0, 1e-3, 0.0)
+    assert abs(scal[0].item() - r["loss_plus"]) <= 5e-3 * r["loss_plus"]

@@ -21,14 +21,35 @@ def test_every_declared_symbol_is_exported():
     assert declared == set(szo.EXPORTS)
     for name in declared:
         assert getattr(szo.lib, name) is not None
-    assert szo.szo_version() == 1
+    assert szo.szo_version() == 2
     assert szo.szo_workspace_bytes() >= 64 + 8 * 1024
 
 
 def test_descriptor_layout_matches_header():
-    # 3*8 + 2*4 + 8 + 8 + 8 pointers*8
-    assert ctypes.sizeof(szo.LinearDesc) == 24 + 8 + 16 + 64
+    # 3*8 + 2*4 + 8 + 8 + 8 pointers*8 + table pointer + format + reserved
+    assert ctypes.sizeof(szo.LinearDesc) == 24 + 8 + 16 + 64 + 8 + 4 + 4
     assert szo.LinearDesc.x.offset == 48 and szo.LinearDesc.target.offset == 104
+    assert szo.LinearDesc.lut.offset == 112 and szo.LinearDesc.format.offset == 120
+
+
+@pytest.mark.parametrize("N,K,dens,seed", [(130, 64, 0.02, 21), (256, 1024, 1e-2, 22), (64, 4096, 1e-3, 23)])
+def test_table_format_quantiser_bit_exact(N, K, dens, seed):
+    from oracle import quant as oq
+    from helpers import banded_codes
+    W = synth.dense_weight(seed, N, K)
+    k = int(dens * N * K + 0.5)
+    flat = omask.mask_uniform(N, K, k, seed)
+    _, sp_idx, _ = omask.tcsr_build(N, K, flat)
+    codes, lut, sp_val = oq.split_and_quantize_lut(W, sp_idx.astype(np.int64))
+    q, lut_c, sp_c = szo.szo_quantize_pack_lut(W, sp_idx)
+    assert np.array_equal(q, oq.pack_codes(codes))
+    assert np.array_equal(lut_c.view(np.uint16), lut.view(np.uint16))
+    assert np.array_equal(sp_c, sp_val)
+    qb, none = szo.szo_layout_weights(q, None, 0)
+    assert none is None and np.array_equal(qb, banded_codes(q))
+    W2 = W[:, :48]                                   # K % 32 != 0
+    with pytest.raises(szo.SzoError):
+        szo.szo_quantize_pack_lut(np.ascontiguousarray(W2), np.zeros(0, np.uint32))
 
 
 def test_philox_host_known_answers_and_oracle():
