@@ -18,6 +18,9 @@ What is computed, and where the paper defines it:
   the sparse product" form used as a cross-check.
 * The counter-based Gaussian (Philox-4x32-10 + Box-Muller) that plays the
   role of the random-seed trick of Section 3.5.
+* Two 4-bit formats for the frozen dense part (Section 3.5 allows any
+  quantiser; Appendix C.5 separates uniform from non-uniform ones): uniform
+  codes with group scales, and a per-row table of 16 centroids.
 
 Pins (see tests/test_oracle_*.py): Philox known-answer vectors; Gaussian
 moments and the two SPSA moment identities of Section 3.1 / Appendix
@@ -25,7 +28,10 @@ moments and the two SPSA moment identities of Section 3.1 / Appendix
 reduces to a textbook dequantise-then-matmul; brute-force triple loop;
 eps = 0 gives g = 0; linear loss gives g = c.z in closed form; +eps, -2eps,
 +eps restores the sparse values; brute-force dense SPSA on tiny shapes;
-g converges to z.grad(L) as eps -> 0.
+g converges to z.grad(L) as eps -> 0.  Table format: rows with 16 levels are
+reproduced bit for bit; brute-force nearest centroid with the tie rule; the
+quantisation map is monotone; bins carry equal mass; the three forward forms
+agree and the sparse part is added on top of the dense code.
 
 Parity unpinned: the 10-step trajectory of the tiny configuration has no
 printed worked example in the paper; it is pinned GPU-vs-oracle only.

@@ -24,14 +24,16 @@ def _sampled_oracle(o, z, sign, eps, rows_n, rows_m, mode, K):
     pos = {int(n): i for i, n in enumerate(rows_n)}
     keep = np.isin(n_of, rows_n)
     sub_idx = np.array([pos[int(n)] for n in n_of[keep]], dtype=np.int64) * K + k_of[keep]
-    return olayer.linear_fwd(o.x_bits[rows_m], o.codes[rows_n], o.scales[rows_n], o.group, sub_idx,
-                             o.sp_val[keep], None if z is None else z[keep], sign, eps, mode, "f16")
+    return olayer.linear_fwd(o.x_bits[rows_m], o.codes[rows_n], None if o.scales is None else o.scales[rows_n],
+                             o.group, sub_idx, o.sp_val[keep], None if z is None else z[keep], sign, eps, mode, "f16",
+                             lut=None if o.lut is None else o.lut[rows_n])
 
 
-@pytest.mark.parametrize("name,M,N,K", [("gate", 4096, 11008, 4096), ("down", 4096, 4096, 11008)])
-def test_full_size_forward_sampled(name, M, N, K):
+@pytest.mark.parametrize("name,M,N,K,fmt", [("gate", 4096, 11008, 4096, "uniform"), ("down", 4096, 4096, 11008, "uniform"),
+                                            ("down", 4096, 4096, 11008, "lut")])
+def test_full_size_forward_sampled(name, M, N, K, fmt):
     szo.szo_set_tile_config(0)                                   # what bench.py runs
-    o, d = make_pair(5 if name == "gate" else 6, M, N, K, 128, 1e-3, kind="heavy_tail", nnz_base=1 << 33)
+    o, d = make_pair(5 if name == "gate" else 6, M, N, K, 128, 1e-3, kind="heavy_tail", nnz_base=1 << 33, fmt=fmt)
     seed, step, eps = 2024, 3, 1e-3
     z = ophilox.zbar(seed, step, 1 << 33, o.sp_idx.size)        # counters beyond 32 bits
     rng = np.random.default_rng(N + K)
