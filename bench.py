@@ -305,8 +305,7 @@ def main():
     # ---- the dominant kernel alone: the library brackets every forward-kernel launch of a few more
     #      steps with events on the launch stream (szo_kernel_timing) ----
     fwd_flops = sum(2.0 * m.M * m.N * m.K for m in mats)
-    few = (all(m.M <= 64 for m in mats) and dt == szo.TILE_F16 and args.tile_config == 0
-           and args.format == "uniform")                                                 # the library's few-token path
+    few = all(m.M <= 64 for m in mats) and dt == szo.TILE_F16 and args.tile_config == 0   # the library's few-token path
     reps = args.steps if args.kernel_reps is None else max(1, args.kernel_reps)
     szo.szo_kernel_timing(True)
     for s in range(reps):

@@ -138,12 +138,37 @@ __device__ __forceinline__ uint32_t sm_stage_x_word(u32x4 u, int w) {
   return __builtin_bit_cast(uint32_t, h);
 }
 
-// FAST = quantisation group of 128: the scales of a block's four subtiles are prefetched with one
-// 8-byte load and applied to each block's partial product, and the codes stay un-centred as
-// described at the top.  Otherwise the scale is read from memory where it is needed
-// and applied to every element before the product (a plain, slower path for the other group sizes).
-template <bool FAST>
+// Eight codes of one row -> eight fp16 table values in the order (0,4)(1,5)(2,6)(3,7).  The row's table of 16
+// entries is held as four byte planes T = {low bytes of entries 0-7, high bytes of 0-7, low bytes of 8-15,
+// high bytes of 8-15}, two registers each: the byte permute looks up four codes at a time by their low
+// three bits, and bit 3 picks the plane through a byte mask.
+__device__ __forceinline__ half8_t sm_lut_word(uint32_t q, const uint32_t (&T)[8]) {
+  const uint32_t sel_e = q & 0x07070707u, sel_o = (q >> 4) & 0x07070707u;         // even codes 0,2,4,6 | odd codes 1,3,5,7
+  const uint32_t m_e = __builtin_amdgcn_perm(0u, 0x0000FF00u, (q >> 3) & 0x01010101u);   // 0xFF where the code is >= 8
+  const uint32_t m_o = __builtin_amdgcn_perm(0u, 0x0000FF00u, (q >> 7) & 0x01010101u);
+  auto pick = [](uint32_t m, uint32_t b, uint32_t a) { return (m & b) | (~m & a); };
+  const uint32_t lo_e = pick(m_e, __builtin_amdgcn_perm(T[5], T[4], sel_e), __builtin_amdgcn_perm(T[1], T[0], sel_e));
+  const uint32_t hi_e = pick(m_e, __builtin_amdgcn_perm(T[7], T[6], sel_e), __builtin_amdgcn_perm(T[3], T[2], sel_e));
+  const uint32_t lo_o = pick(m_o, __builtin_amdgcn_perm(T[5], T[4], sel_o), __builtin_amdgcn_perm(T[1], T[0], sel_o));
+  const uint32_t hi_o = pick(m_o, __builtin_amdgcn_perm(T[7], T[6], sel_o), __builtin_amdgcn_perm(T[3], T[2], sel_o));
+  const u32x4 w = {__builtin_amdgcn_perm(hi_e, lo_e, 0x06020400u),      // codes 0, 4
+                   __builtin_amdgcn_perm(hi_o, lo_o, 0x06020400u),      // codes 1, 5
+                   __builtin_amdgcn_perm(hi_e, lo_e, 0x07030501u),      // codes 2, 6
+                   __builtin_amdgcn_perm(hi_o, lo_o, 0x07030501u)};     // codes 3, 7
+  return __builtin_bit_cast(half8_t, w);
+}
+
+// MODE 1 (uniform format, quantisation group of 128): the scales of a block's four subtiles are
+// prefetched with one 8-byte load and applied to each block's partial product, and the codes stay
+// un-centred as described at the top.  MODE 0 (the other group sizes): the scale is read from memory
+// where it is needed and applied to every element before the product (a plain, slower path).
+// MODE 2 (table format): dq = lut[row][code]; a lane keeps the tables of its four rows in registers
+// (32 of them; it needs neither scales nor the constants of the un-centred codes, so it still fits
+// the register budget of three workgroups per CU).
+constexpr int SM_PLAIN = 0, SM_FAST = 1, SM_LUT = 2;
+template <int MODE>
 __global__ void __launch_bounds__(256, SM_MIN_BLOCKS) small_m_kernel(SmallArgs a) {
+  constexpr bool FAST = MODE == SM_FAST, LUT = MODE == SM_LUT;
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
   _Float16* const xs = reinterpret_cast<_Float16*>(smem);                        // [2][16][SM_XSTRIDE]
   uint16_t* const winp = reinterpret_cast<uint16_t*>(xs + 2 * SM_ROWS * SM_XSTRIDE);   // [4 bands][SM_CAP] packed position (see refill)
@@ -227,6 +252,21 @@ __global__ void __launch_bounds__(256, SM_MIN_BLOCKS) small_m_kernel(SmallArgs a
     qoff[s] = (bsafe * (uint32_t)ktiles * 64u + (uint32_t)(16 * s + nn)) * 32u + (uint32_t)(jj >> 1) * 2048u + (uint32_t)(jj & 1) * 16u;
   const int gshift = mt.group_shift;
   const uint32_t soff = (bsafe * (uint32_t)(K >> gshift) * 64u + (uint32_t)nn * 4u) * 2u;
+  // table format: the tables of rows nn, nn+16, nn+32, nn+48 of the band (mt.scales is the table array);
+  // rows past N re-read the last row's table, their outputs are never used
+  uint32_t tb[LUT ? 4 : 1][8];
+  if (LUT) {
+#pragma unroll
+    for (int s = 0; s < (LUT ? 4 : 1); ++s) {
+      const int n = min((int)bsafe * 64 + 16 * s + nn, N - 1);
+      const auto* lp = reinterpret_cast<const u32x4 __attribute__((address_space(1)))*>(g_scales + (size_t)n * 16);
+      const u32x4 lo = lp[0], hi = lp[1];                   // entries 0-7 and 8-15, two per word
+      tb[s][0] = __builtin_amdgcn_perm(lo[1], lo[0], 0x06040200u); tb[s][1] = __builtin_amdgcn_perm(lo[3], lo[2], 0x06040200u);
+      tb[s][2] = __builtin_amdgcn_perm(lo[1], lo[0], 0x07050301u); tb[s][3] = __builtin_amdgcn_perm(lo[3], lo[2], 0x07050301u);
+      tb[s][4] = __builtin_amdgcn_perm(hi[1], hi[0], 0x06040200u); tb[s][5] = __builtin_amdgcn_perm(hi[3], hi[2], 0x06040200u);
+      tb[s][6] = __builtin_amdgcn_perm(hi[1], hi[0], 0x07050301u); tb[s][7] = __builtin_amdgcn_perm(hi[3], hi[2], 0x07050301u);
+    }
+  }
   // ---- x staging: piece = 8 columns (16 bytes of bf16) of one row; thread handles pieces
   //      (row tid>>5, columns 8*(tid&31)..) and the same columns of row 8 + (tid>>5) ----
   // Loads are unconditional, from clamped addresses, and out-of-range parts are zeroed only when the
@@ -350,10 +390,10 @@ __global__ void __launch_bounds__(256, SM_MIN_BLOCKS) small_m_kernel(SmallArgs a
         const int slot = (kbl & kRingMask) * 4 + s;
         const u32x4 q = qbuf[slot];
         load_q(slot, 2 * c + kbl + SM_RING);                // the slot is free: fetch the block SM_RING ahead
-        _Float16 sh;
+        _Float16 sh = (_Float16)0.0f;
         if (FAST) {
           sh = __builtin_bit_cast(half4_t, sc[kbl])[s];
-        } else {
+        } else if (!LUT) {
           const uint32_t gi = (uint32_t)min((kc + kbl * 128 + 32 * jj) >> gshift, (K >> gshift) - 1);
           sh = __builtin_bit_cast(_Float16, *reinterpret_cast<const uint16_t __attribute__((address_space(1)))*>(
               reinterpret_cast<const uint8_t __attribute__((address_space(1)))*>(g_scales) + (size_t)gi * 128 + soff + 2 * s));
@@ -362,7 +402,7 @@ __global__ void __launch_bounds__(256, SM_MIN_BLOCKS) small_m_kernel(SmallArgs a
         float4_t tmp = init;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-          const half8_t b = sm_dequant_word<FAST>(q[t], magic_lo, magic_hi, s2);
+          const half8_t b = LUT ? sm_lut_word(q[t], tb[LUT ? s : 0]) : sm_dequant_word<FAST>(q[t], magic_lo, magic_hi, s2);
           tmp = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[t], b, tmp, 0, 0, 0);
         }
         if (FAST) {
@@ -506,13 +546,28 @@ static size_t small_lds_bytes() {
 }
 
 bool small_m_eligible(const szo_linear_desc* d) {
-  return d->M >= 1 && d->M <= SM_ROWS && d->N >= 1 && (d->K % 128) == 0 && d->group >= 32 &&
-         d->tile_dtype == SZO_TILE_F16 && d->format == SZO_FORMAT_UNIFORM &&
+  return d->M >= 1 && d->M <= SM_ROWS && d->N >= 1 && (d->K % 128) == 0 &&
+         (d->format == SZO_FORMAT_LUT || d->group >= 32) && d->tile_dtype == SZO_TILE_F16 &&
          (uint64_t)((d->N + 63) / 64 * 64) * (uint64_t)d->K / 2 < (1ull << 32);   // 32-bit code offsets
 }
 
-// group of 128 (one scale per 128-column block): the fast instantiation
-static bool small_m_fast(const szo_linear_desc* d) { return d->group == 128; }
+// Which instantiation a matrix runs with: uniform format with a group of 128 (one scale per
+// 128-column block) takes the fast one, the table format its own, everything else the plain one.
+static int small_m_mode(const szo_linear_desc* d) {
+  if (d->format == SZO_FORMAT_LUT) return SM_LUT;
+  return d->group == 128 ? SM_FAST : SM_PLAIN;
+}
+// position of a mode in a step's table and launch order
+static int small_m_class(const szo_linear_desc* d) {
+  const int m = small_m_mode(d);
+  return m == SM_FAST ? 0 : m == SM_LUT ? 1 : 2;
+}
+
+static void small_m_launch(int mode, int blocks, const SmallArgs& a, hipStream_t stream) {
+  if (mode == SM_FAST) small_m_kernel<SM_FAST><<<blocks, 256, small_lds_bytes(), stream>>>(a);
+  else if (mode == SM_LUT) small_m_kernel<SM_LUT><<<blocks, 256, small_lds_bytes(), stream>>>(a);
+  else small_m_kernel<SM_PLAIN><<<blocks, 256, small_lds_bytes(), stream>>>(a);
+}
 
 // The step also takes matrices with up to 64 tokens: they run as up to four 16-token slices, each a
 // pass of its own over the weights (still cheaper than the tiled kernel at these sizes).
@@ -528,14 +583,15 @@ int small_m_blocks(const szo_linear_desc* d) { return (int)((d->N + SM_BN - 1) /
 size_t small_m_table_bytes(int n) { return sizeof(SmallMat) * (size_t)n; }
 
 static void fill_mat(SmallMat& m, const szo_linear_desc* d) {
-  m.x = (const uint16_t*)d->x; m.qweight = d->qweight; m.scales = (const uint16_t*)d->scales;
+  m.x = (const uint16_t*)d->x; m.qweight = d->qweight;
+  m.scales = (const uint16_t*)(d->format == SZO_FORMAT_LUT ? d->lut : d->scales);
   m.tile_ptr = d->tile_ptr; m.sp_idx = d->sp_idx; m.sp_val = d->sp_val;
   m.target = (const uint16_t*)d->target; m.y = d->y;
   m.nnz_base = d->nnz_base;
   m.loss_scale = 1.0 / ((double)d->M * (double)d->N);
   m.N = (int)d->N; m.K = (int)d->K; m.M = (int)d->M; m.nnz = (uint32_t)d->nnz;
   int gs = 0;
-  while ((1 << gs) < d->group) ++gs;
+  while (d->format == SZO_FORMAT_UNIFORM && (1 << gs) < d->group) ++gs;
   m.group_shift = gs;
   int l = 0;
   while ((1ull << l) < (uint64_t)m.K) ++l;
@@ -547,9 +603,11 @@ static void fill_mat(SmallMat& m, const szo_linear_desc* d) {
 static int set_small_attrs() {
   static bool attr_set = false;
   if (!attr_set) {
-    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_FAST>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)small_lds_bytes()));
-    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_PLAIN>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)small_lds_bytes()));
+    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_LUT>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)small_lds_bytes()));
     attr_set = true;
   }
@@ -580,8 +638,7 @@ int small_m_launch_one(const szo_linear_desc* d, uint64_t seed, uint64_t step, f
     a.partial_minus = partial_minus ? partial_minus + (size_t)sl * blocks : nullptr;
     const int trc = timing_begin(stream);
     if (trc != SZO_OK) return trc;
-    if (small_m_fast(d)) small_m_kernel<true><<<blocks, 256, small_lds_bytes(), stream>>>(a);
-    else small_m_kernel<false><<<blocks, 256, small_lds_bytes(), stream>>>(a);
+    small_m_launch(small_m_mode(d), blocks, a, stream);
     SZO_LAUNCH_CHECK();
     const int erc = timing_end(stream);
     if (erc != SZO_OK) return erc;
@@ -589,7 +646,7 @@ int small_m_launch_one(const szo_linear_desc* d, uint64_t seed, uint64_t step, f
   return SZO_OK;
 }
 
-// A whole stack in one launch per group size.  The table is assembled on the host, longest K
+// A whole stack in one launch per instantiation.  The table is assembled on the host, longest K
 // first (their workgroups run longest, so they should start first), copied into `table_dev`
 // (device, small_m_table_bytes(n)) with an asynchronous copy on the stream, and also drives one
 // grouped sparse update when `do_update` is set.  With `do_forward` false only the table is staged
@@ -606,26 +663,26 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
   static thread_local std::vector<SmallMat> host_table;
   host_table.resize((size_t)max_entries);
   SmallMat* const host = host_table.data();
-  // order: matrices of the fast instantiation first (by K descending), then the others (by K descending)
+  // order: by instantiation (fast, table format, plain), inside each by K descending
   int order[4096];
   for (int i = 0; i < n; ++i) order[i] = i;
+  auto sort_key = [&](int o) { return ((int64_t)(2 - small_m_class(&descs[o])) << 40) + descs[o].K; };
   for (int i = 1; i < n; ++i) {                       // insertion sort: n is a few hundred
     const int o = order[i];
-    const int64_t key = (small_m_fast(&descs[o]) ? (int64_t)1 << 40 : 0) + descs[o].K;
+    const int64_t key = sort_key(o);
     int j = i - 1;
     while (j >= 0) {
-      const int64_t kj = (small_m_fast(&descs[order[j]]) ? (int64_t)1 << 40 : 0) + descs[order[j]].K;
-      if (kj >= key) break;
+      if (sort_key(order[j]) >= key) break;
       order[j + 1] = order[j];
       --j;
     }
     order[j + 1] = o;
   }
-  int n128 = 0, blocks128 = 0, blocks_other = 0, partials = 0, entries = 0;
+  int class_entries[3] = {0, 0, 0}, class_blocks[3] = {0, 0, 0}, partials = 0, entries = 0;
   int64_t quads = 0;
   for (int r = 0; r < n; ++r) {
     const szo_linear_desc* d = &descs[order[r]];
-    const bool g128 = small_m_fast(d);
+    const int cls = small_m_class(d);
     // forward: one table entry per slice of 16 token rows; update only: one entry per matrix
     const int slices = do_forward ? (int)((d->M + SM_ROWS - 1) / SM_ROWS) : 1;
     for (int sl = 0; sl < slices; ++sl) {
@@ -636,11 +693,12 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
         m.target += (size_t)sl * SM_ROWS * (size_t)d->N;
         m.M = (int)std::min<int64_t>(SM_ROWS, d->M - (int64_t)sl * SM_ROWS);
       }
-      m.first_block = g128 ? blocks128 : blocks_other;
+      m.first_block = class_blocks[cls];
       m.partial_base = partials;
       m.first_quad = quads;          // every slice of a matrix: the update finds the last one, once
       const int b = small_m_blocks(d);
-      if (g128) { blocks128 += b; ++n128; } else blocks_other += b;
+      class_blocks[cls] += b;
+      ++class_entries[cls];
       partials += b;
     }
     quads += ((int64_t)d->nnz + 3) / 4;
@@ -653,19 +711,16 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
   a.seed = seed; a.step = step; a.eps = eps;
   a.partial_plus = partial_plus; a.partial_minus = partial_plus + partials;
   const SmallMat* tdev = (const SmallMat*)table_dev;
-  if (do_forward && blocks128 > 0) {
-    a.table = tdev; a.n_mats = n128;
-    if ((rc = timing_begin(stream)) != SZO_OK) return rc;
-    small_m_kernel<true><<<blocks128, 256, small_lds_bytes(), stream>>>(a);
-    SZO_LAUNCH_CHECK();
-    if ((rc = timing_end(stream)) != SZO_OK) return rc;
-  }
-  if (do_forward && blocks_other > 0) {
-    a.table = tdev + n128; a.n_mats = entries - n128;
-    if ((rc = timing_begin(stream)) != SZO_OK) return rc;
-    small_m_kernel<false><<<blocks_other, 256, small_lds_bytes(), stream>>>(a);
-    SZO_LAUNCH_CHECK();
-    if ((rc = timing_end(stream)) != SZO_OK) return rc;
+  int first_entry = 0;
+  for (int cls = 0; cls < 3; ++cls) {
+    if (do_forward && class_blocks[cls] > 0) {
+      a.table = tdev + first_entry; a.n_mats = class_entries[cls];
+      if ((rc = timing_begin(stream)) != SZO_OK) return rc;
+      small_m_launch(cls == 0 ? SM_FAST : cls == 1 ? SM_LUT : SM_PLAIN, class_blocks[cls], a, stream);
+      SZO_LAUNCH_CHECK();
+      if ((rc = timing_end(stream)) != SZO_OK) return rc;
+    }
+    first_entry += class_entries[cls];
   }
   if (do_forward) {
     rc = reduce_step(partial_plus, partials, eps, scalars, stream);

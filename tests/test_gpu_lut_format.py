@@ -106,20 +106,86 @@ def test_fused_loss_and_step_match_oracle():
     assert np.array_equal(results[0][1], results[3][1]) and np.array_equal(results[0][2], results[3][2])
 
 
-def test_unfused_step_and_few_tokens_take_the_tiled_kernel():
-    # 16 tokens: the uniform format would take the few-token path; the table format must still be right
-    o, d = make_pair(50, 16, 256, 512, 128, 1e-2, fmt="lut")
+# (seed, M, N, K, density): the few-token kernel's table-format instantiation (M <= 64)
+FEW = [
+    (61, 16, 256, 128, 1e-2),         # one strip, one 128-column block
+    (62, 16, 512, 1152, 1e-3),        # 4.5 chunks: ragged last chunk
+    (63, 1, 200, 256, 5e-2),          # one token, ragged N (rows past N re-read the last row's table), refills
+    (64, 7, 513, 2048, 2e-3),         # ragged M and N
+    (65, 40, 320, 512, 5e-3),         # three passes of 16 token rows
+    (66, 16, 256, 256, 0.0),          # k = 0
+]
+
+
+@pytest.mark.parametrize("shape", FEW)
+def test_few_token_forward_matches_oracle(shape):
+    s, M, N, K, dens = shape
+    szo.szo_set_tile_config(0)
+    o, d = make_pair(s, M, N, K, 128, dens, nnz_base=12, fmt="lut")
+    seed, step, eps = 77, 5, 1e-3
+    z = ophilox.zbar(seed, step, 12, o.sp_idx.size)
+    tiled = {}
+    for sign in (+1, -1, 0):
+        y = _run(d, sign, eps, seed, step)
+        assert np.isfinite(y).all()
+        yE = olayer.linear_fwd(o.x_bits, o.codes, None, 0, o.sp_idx, o.sp_val, z, sign, eps, "E", lut=o.lut)
+        # table values are exact in the tile; what is left is fp32 accumulation and the sparse values in fp16
+        assert rel_fro(y, yE) <= 2e-4, (sign, rel_fro(y, yE))
+        tiled[sign] = y
+    szo.szo_set_tile_config(2)                    # the tiled kernel on the same layer: another kernel, same answer
+    for sign in (+1, -1):
+        y2 = _run(d, sign, eps, seed, step)
+        assert rel_fro(tiled[sign], y2) <= 2e-4 and not np.array_equal(tiled[sign], y2)
+
+
+def test_few_token_step_with_all_three_instantiations():
+    # one step over a table-format layer, a group-128 layer and a group-64 layer: three launches, one g
+    szo.szo_set_tile_config(0)
+    o1, d1 = make_pair(67, 16, 256, 512, 128, 1e-2, nnz_base=0, fmt="lut")
+    b2 = (o1.sp_idx.size + 3) // 4 * 4
+    o2, d2 = make_pair(68, 48, 320, 256, 128, 5e-3, nnz_base=b2)
+    b3 = b2 + (o2.sp_idx.size + 3) // 4 * 4
+    o3, d3 = make_pair(69, 16, 128, 384, 64, 1e-2, nnz_base=b3)
     seed, eps, lr = 5, 1e-3, 1e-3
     ws = szo.new_workspace()
     scal = torch.zeros(3, dtype=torch.float64, device="cuda")
-    om = clone(o)
-    sg = sigma_g([o])
-    for flags in (0, szo.STEP_FUSED_LOSS):
-        szo.szo_zo_step([d.desc()], seed, 0, eps, 0.0, scal, ws, flags)
+    a, b, c = clone(o1), clone(o2), clone(o3)
+    sg = sigma_g([o1, o2, o3])
+    descs = szo.desc_array([d3.desc(with_y=False), d1.desc(with_y=False), d2.desc(with_y=False)])   # any order
+    szo.szo_kernel_timing(True)
+    for s in range(3):
+        szo.szo_zo_step(descs, seed, s, eps, lr, scal, ws, szo.STEP_FUSED_LOSS)
         lp, lm, g = scal.cpu().numpy()
-        r = ozo.zo_step([clone(om)], seed, 0, eps, 0.0)
+        r = ozo.zo_step([c, a, b], seed, s, eps, lr)
         assert abs(lp - r["loss_plus"]) <= 5e-3 * r["loss_plus"]
-        assert abs(g - r["g"]) <= 1e-2 * max(abs(r["g"]), sg)
+        assert abs(g - r["g"]) <= 1e-2 * max(abs(r["g"]), sg), (s, g, r["g"])
+    _, launches = szo.szo_kernel_timing_read()
+    szo.szo_kernel_timing(False)
+    assert launches == 9                          # few-token path: one launch per instantiation and step
+    for om, dd, oo in ((a, d1, o1), (b, d2, o2), (c, d3, o3)):
+        dv_gpu = dd.sp_val.cpu().numpy().astype(np.float64) - oo.sp_val
+        dv_ref = om.sp_val.astype(np.float64) - oo.sp_val
+        assert np.linalg.norm(dv_gpu - dv_ref) <= 3e-2 * np.linalg.norm(dv_ref)
+
+
+def test_few_token_single_calls_with_loss():
+    szo.szo_set_tile_config(0)
+    o, d = make_pair(70, 40, 256, 512, 128, 1e-2, fmt="lut")
+    seed, eps = 5, 1e-3
+    ws = szo.new_workspace()
+    z = ophilox.zbar(seed, 0, 0, o.sp_idx.size)
+    for sign in (+1, -1):
+        acc = torch.zeros(1, dtype=torch.float64, device="cuda")
+        szo.szo_linear_fwd_mse(d.desc(with_y=False), seed, 0, sign, eps, 1.0 / (40 * 256), acc, ws)
+        yE = olayer.linear_fwd(o.x_bits, o.codes, None, 0, o.sp_idx, o.sp_val, z, sign, eps, "E", lut=o.lut)
+        LE = olayer.mse_loss(yE, o.target_bits)
+        assert abs(acc.item() - LE) <= 1e-4 * LE
+    # unfused step (separate loss kernel) on the same layer
+    scal = torch.zeros(3, dtype=torch.float64, device="cuda")
+    szo.szo_zo_step([d.desc()], seed, 0, eps, 0.0, scal, ws, 0)
+    r = ozo.zo_step([clone(o)], seed, 0, eps, 0.0)
+    assert abs(scal[0].item() - r["loss_plus"]) <= 5e-3 * r["loss_plus"]
+    assert abs(scal[2].item() - r["g"]) <= 1e-2 * max(abs(r["g"]), sigma_g([o]))
 
 
 def test_validation_of_the_table_format():
