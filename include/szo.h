@@ -83,8 +83,7 @@ typedef struct szo_linear_desc {
  * has both dequantised before the SparseAdd form of the product):
  *   SZO_FORMAT_UNIFORM  dq[n,k] = (code - 8) * scales[n, k/group]
  *   SZO_FORMAT_LUT      dq[n,k] = lut[n][code]: 16 fp16 centroids per output row, no scales
- *                       (`scales` may be NULL and `group` is ignored).  fp16 tile only; such a
- *                       layer always takes the tiled kernel, whatever its token count.
+ *                       (`scales` may be NULL and `group` is ignored).  fp16 tile only.
  * In both, the sensitive entries are ADDED to the dequantised tile. */
 #define SZO_FORMAT_UNIFORM 0
 #define SZO_FORMAT_LUT 1
