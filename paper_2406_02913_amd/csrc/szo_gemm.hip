@@ -1108,7 +1108,7 @@ int szo_zo_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t ste
     if (rc != SZO_OK) return rc;
   }
   // one grouped update launch for the whole stack (per-matrix launches when the table does not fit)
-  if (small_m_table_bytes(n) <= kTableBytesPerMatrix * (size_t)kMaxStepMatrices)
+  if (n <= kMaxStepMatrices && small_m_table_bytes(n) <= kTableBytesPerMatrix * (size_t)kMaxStepMatrices)
     return small_m_step(descs, n, seed, step, eps, lr, (char*)workspace + kWorkspaceTableOffset, nullptr, scalars,
                         false, true, s);
   for (int i = 0; i < n; ++i) {

@@ -656,7 +656,7 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
                  hipStream_t stream) {
   int rc = set_small_attrs();
   if (rc != SZO_OK) return rc;
-  if (n > 4096) return SZO_EUNSUPPORTED;
+  if (n > kMaxStepMatrices) return SZO_EUNSUPPORTED;
   int max_entries = 0;
   for (int i = 0; i < n; ++i) max_entries += do_forward ? (int)((descs[i].M + SM_ROWS - 1) / SM_ROWS) : 1;
   if (small_m_table_bytes(max_entries) > kTableBytesPerMatrix * (size_t)kMaxStepMatrices) return SZO_EUNSUPPORTED;
@@ -664,7 +664,7 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
   host_table.resize((size_t)max_entries);
   SmallMat* const host = host_table.data();
   // order: by instantiation (fast, table format, plain), inside each by K descending
-  int order[4096];
+  int order[kMaxStepMatrices];
   for (int i = 0; i < n; ++i) order[i] = i;
   auto sort_key = [&](int o) { return ((int64_t)(2 - small_m_class(&descs[o])) << 40) + descs[o].K; };
   for (int i = 1; i < n; ++i) {                       // insertion sort: n is a few hundred

@@ -193,3 +193,27 @@ def test_steps_on_a_side_stream_match_the_default_stream():
         outs.append((scal.cpu().numpy().copy(), d.sp_val.cpu().numpy().copy()))
     szo.szo_set_tile_config(0)
     assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
+
+
+def test_more_matrices_than_one_descriptor_table_holds():
+    # 4100 layers (the tables of the grouped launches hold 4096): the step falls back to one launch per
+    # matrix for the forwards and for the updates and still forms one g over all of them
+    o, d = make_pair(12, 32, 64, 64, 32, 2e-2)
+    n = 4100
+    descs, mats = [], []
+    for i in range(n):
+        dd = d.desc(with_y=False)
+        dd.nnz_base = 128 * i
+        descs.append(dd)
+        om = clone(o)
+        om.nnz_base = 128 * i
+        mats.append(om)
+    ws = szo.new_workspace()
+    scal = torch.zeros(3, dtype=torch.float64, device="cuda")
+    before = d.sp_val.clone()
+    szo.szo_zo_step(descs, 21, 0, 1e-3, 0.0, scal, ws, szo.STEP_FUSED_LOSS)      # lr = 0: the shared values stay
+    lp, lm, g = scal.cpu().numpy()
+    r = ozo.zo_step(mats, 21, 0, 1e-3, 0.0)
+    assert abs(lp - r["loss_plus"]) <= 5e-3 * r["loss_plus"] and abs(lm - r["loss_minus"]) <= 5e-3 * r["loss_minus"]
+    assert abs(g - r["g"]) <= 1e-2 * max(abs(r["g"]), sigma_g(mats[:1]) * np.sqrt(n))
+    assert torch.equal(before, d.sp_val)
