@@ -174,6 +174,15 @@ def test_hot_calls_validate_before_touching_the_gpu():
     assert szo.lib.szo_linear_fwd(None, 0, 0, 1, 1e-3, None) == szo.EINVAL
     d.tile_dtype, d.M = 0, 0
     assert szo.lib.szo_linear_fwd(ctypes.byref(d), 0, 0, 1, 1e-3, None) == szo.OK            # empty: no-op
+    # table format: group is not looked at, the table pointer and the fp16 tile are required
+    t = szo.LinearDesc(M=8, N=64, K=128, group=0, tile_dtype=1, nnz=0, nnz_base=0, format=szo.FORMAT_LUT)
+    assert szo.lib.szo_linear_fwd(ctypes.byref(t), 0, 0, 1, 1e-3, None) == szo.EUNSUPPORTED  # bf16 tile
+    t.tile_dtype = 0
+    assert szo.lib.szo_linear_fwd(ctypes.byref(t), 0, 0, 1, 1e-3, None) == szo.EINVAL        # null pointers
+    t.format = 2
+    assert szo.lib.szo_linear_fwd(ctypes.byref(t), 0, 0, 1, 1e-3, None) == szo.EINVAL        # unknown format
+    t.format, t.M = szo.FORMAT_LUT, 0
+    assert szo.lib.szo_linear_fwd(ctypes.byref(t), 0, 0, 1, 1e-3, None) == szo.OK            # empty: no-op
     assert szo.lib.szo_mse_loss(None, None, 5, 1.0, None, None, None) == szo.EINVAL
     assert szo.lib.szo_sparse_update(None, None, 4, 2, 0, 0, None, 0.1, None) == szo.EINVAL
     assert szo.lib.szo_spsa_g(None, None, 0.1, None, None) == szo.EINVAL
