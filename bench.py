@@ -366,7 +366,7 @@ def main():
                                + (f"int4 group {cfg['group']}, " if args.format == "uniform" else "4-bit table format, ") +
                                f"mask {cfg['density']:g} {cfg['mask']}, eps={eps}, lr={lr}",
                    "loss": "fused into the forward epilogue" if flags else "separate kernel",
-                   "tile": args.tile, "accumulate": "f32", "loss_accumulate": "f64"},
+                   "tile": args.tile, "format": args.format, "accumulate": "f32", "loss_accumulate": "f64"},
         "step_tflops": round(step_flops / (ms_per_step * 1e-3) / 1e12, 2),
         "step_frac_of_mfma_peak": round(step_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_MFMA_16BIT_TFLOPS, 4),
         "roofline": roof,
