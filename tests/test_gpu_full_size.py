@@ -130,3 +130,45 @@ def test_opt_ffn_projections_decode_token_counts(M):
         dv_gpu = dd.sp_val.cpu().numpy().astype(np.float64) - o.sp_val
         dv_ref = om.sp_val.astype(np.float64) - o.sp_val
         assert np.linalg.norm(dv_gpu - dv_ref) <= 3e-2 * np.linalg.norm(dv_ref) + 1e-12
+
+
+def test_llama_block_step_in_the_benchmarks_launch_configuration():
+    """One whole Llama-2-7B block at 4096 tokens through szo_zo_step exactly as bench.py runs it (library's
+    choice of tiles: all 14 forwards in one table-driven launch, loss fused, grouped update).  Its losses
+    must equal the per-matrix fused-loss calls (same kernel body, checked against the oracle above) up to
+    the order in which the fp64 partials are added, g must follow from them, and every sensitive value
+    must move by exactly -lr g z with the oracle's z."""
+    from paper_2406_02913_amd import synth
+    szo.szo_set_tile_config(0)
+    cfg = synth.WORKLOADS["c3"]
+    M = cfg["M"]
+    pairs, base = [], 0
+    for i, (name, N, K) in enumerate(cfg["block"]):
+        o, d = make_pair(synth.matrix_seed(0, 0, i), M, N, K, cfg["group"], cfg["density"], kind=cfg["mask"], nnz_base=base)
+        base += (o.sp_idx.size + 3) // 4 * 4
+        pairs.append((o, d))
+    seed, step, eps, lr = 2024, 7, cfg["eps"], 1e-2
+    ws = szo.new_workspace()
+    lp = torch.zeros(1, dtype=torch.float64, device="cuda")
+    lm = torch.zeros(1, dtype=torch.float64, device="cuda")
+    for o, d in pairs:
+        szo.szo_linear_fwd_mse(d.desc(with_y=False), seed, step, +1, eps, 1.0 / (M * d.N), lp, ws)
+        szo.szo_linear_fwd_mse(d.desc(with_y=False), seed, step, -1, eps, 1.0 / (M * d.N), lm, ws)
+    before = [d.sp_val.cpu().numpy().copy() for _, d in pairs]
+    scal = torch.zeros(3, dtype=torch.float64, device="cuda")
+    szo.szo_kernel_timing(True)
+    szo.szo_zo_step([d.desc(with_y=False) for _, d in pairs], seed, step, eps, lr, scal, ws, szo.STEP_FUSED_LOSS)
+    _, launches = szo.szo_kernel_timing_read()
+    szo.szo_kernel_timing(False)
+    assert launches == 1                                        # the grouped launch, as in the benchmark
+    Lp, Lm, g = scal.cpu().numpy()
+    assert abs(Lp - lp.item()) <= 1e-12 * Lp and abs(Lm - lm.item()) <= 1e-12 * Lm
+    assert g == (Lp - Lm) / (2.0 * float(np.float32(eps)))
+    step_size = float(np.float32(lr)) * g
+    for (o, d), v0 in zip(pairs, before):
+        z = ophilox.zbar(seed, step, o.nnz_base, o.sp_idx.size)
+        want = v0.astype(np.float64) - step_size * z
+        got = d.sp_val.cpu().numpy()
+        # the kernel forms c = fp32(lr g) and fma(-c, z32, v) with its own fp32 z: a few ulps of the update
+        assert np.max(np.abs(got - want)) <= 1e-5 * abs(step_size) * 6 + np.spacing(np.float32(0.1))
+        assert np.max(np.abs(got - v0)) > 0
