@@ -1,0 +1,72 @@
+"""Seeded sweep over shapes, group sizes, densities, formats and tile configurations inside the
+documented limits: every case is one forward per sign against the oracle, plus one fused step."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import layer as olayer, philox as ophilox, zo as ozo
+from paper_2406_02913_amd import szo
+from helpers import make_pair, clone, rel_fro, sigma_g
+
+pytestmark = pytest.mark.gpu
+
+
+def _cases(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        fmt = "lut" if rng.random() < 0.4 else "uniform"
+        group = int(rng.choice([32, 64, 128]))
+        K = int(rng.integers(1, 17)) * 64
+        if K % group:
+            K = (K + group - 1) // group * group
+        M = int(rng.choice([1, 2, 15, 16, 17, 33, 64, 65, 100, 255, 256, 257, 300, 520]))
+        N = int(rng.choice([1, 5, 63, 64, 65, 130, 255, 256, 257, 300, 511, 640]))
+        dens = float(rng.choice([0.0, 1e-3, 1e-2, 5e-2]))
+        kind = "heavy_tail" if (N >= 100 and dens <= 1e-2 and rng.random() < 0.5) else "uniform"   # hot rows hold k/2
+        cfg = int(rng.choice([0, 1, 2, 3]))
+        out.append((1000 + i, M, N, K, group, dens, kind, fmt, cfg))
+    return out
+
+
+@pytest.fixture(autouse=True)
+def _auto_tile_config():
+    yield
+    szo.szo_set_tile_config(0)
+
+
+@pytest.mark.parametrize("case", _cases(96, 20240611), ids=lambda c: "-".join(str(v) for v in c[1:]))
+def test_random_case(case):
+    s, M, N, K, G, dens, kind, fmt, cfg = case
+    o, d = make_pair(s, M, N, K, G, dens, kind=kind, nnz_base=4 * (s % 7), fmt=fmt)
+    szo.szo_set_tile_config(cfg)
+    seed, step, eps = 31 + s, s % 5, 1e-3
+    z = ophilox.zbar(seed, step, o.nnz_base, o.sp_idx.size)
+    scales = None if fmt == "lut" else o.scales
+    for sign in (+1, -1):
+        d.y.fill_(float("nan"))
+        szo.szo_linear_fwd(d.desc(), seed, step, sign, eps)
+        torch.cuda.synchronize()
+        y = d.y.cpu().numpy()
+        assert np.isfinite(y).all()
+        yE = olayer.linear_fwd(o.x_bits, o.codes, scales, G, o.sp_idx, o.sp_val, z, sign, eps, "E", lut=o.lut)
+        # relative to the outputs' natural size 0.02 sqrt(K) per element when the few outputs of a tiny
+        # case happen to cancel (a 1 x 1 output can be anything)
+        floor = 0.02 * np.sqrt(float(K) * M * N)
+        assert np.linalg.norm(y - yE) <= 5e-3 * max(np.linalg.norm(yE), floor), (sign, rel_fro(y, yE))
+    ws = szo.new_workspace()
+    scal = torch.zeros(3, dtype=torch.float64, device="cuda")
+    om = clone(o)
+    szo.szo_zo_step([d.desc(with_y=False)], seed, step, eps, 1e-3, scal, ws, szo.STEP_FUSED_LOSS)
+    lp, lm, g = scal.cpu().numpy()
+    r = ozo.zo_step([om], seed, step, eps, 1e-3)
+    assert abs(lp - r["loss_plus"]) <= 5e-3 * r["loss_plus"] and abs(lm - r["loss_minus"]) <= 5e-3 * r["loss_minus"]
+    sg = sigma_g([o])
+    assert abs(g - r["g"]) <= 1e-2 * max(abs(r["g"]), sg), (g, r["g"])
+    if o.sp_idx.size == 0:              # k = 0: the device side keeps a small placeholder array
+        return
+    # the update is -lr g z: it inherits g's error, which is bounded relative to max(|g|, sigma_g)
+    dv_gpu = d.sp_val.cpu().numpy().astype(np.float64) - o.sp_val
+    dv_ref = om.sp_val.astype(np.float64) - o.sp_val
+    tol = 1e-2 * max(abs(r["g"]), sg) / max(abs(r["g"]), 1e-300) + 1e-2
+    assert np.linalg.norm(dv_gpu - dv_ref) <= tol * np.linalg.norm(dv_ref) + 1e-12
