@@ -25,7 +25,8 @@ def _cases(n, seed):
         dens = float(rng.choice([0.0, 1e-3, 1e-2, 5e-2]))
         kind = "heavy_tail" if (N >= 100 and dens <= 1e-2 and rng.random() < 0.5) else "uniform"   # hot rows hold k/2
         cfg = int(rng.choice([0, 1, 2, 3]))
-        out.append((1000 + i, M, N, K, group, dens, kind, fmt, cfg))
+        dt = "bf16" if (fmt == "uniform" and rng.random() < 0.25) else "f16"
+        out.append((1000 + i, M, N, K, group, dens, kind, fmt, cfg, dt))
     return out
 
 
@@ -37,7 +38,8 @@ def _auto_tile_config():
 
 @pytest.mark.parametrize("case", _cases(96, 20240611), ids=lambda c: "-".join(str(v) for v in c[1:]))
 def test_random_case(case):
-    s, M, N, K, G, dens, kind, fmt, cfg = case
+    s, M, N, K, G, dens, kind, fmt, cfg, dtname = case
+    dt = szo.TILE_BF16 if dtname == "bf16" else szo.TILE_F16
     o, d = make_pair(s, M, N, K, G, dens, kind=kind, nnz_base=4 * (s % 7), fmt=fmt)
     szo.szo_set_tile_config(cfg)
     seed, step, eps = 31 + s, s % 5, 1e-3
@@ -45,7 +47,7 @@ def test_random_case(case):
     scales = None if fmt == "lut" else o.scales
     for sign in (+1, -1):
         d.y.fill_(float("nan"))
-        szo.szo_linear_fwd(d.desc(), seed, step, sign, eps)
+        szo.szo_linear_fwd(d.desc(dt), seed, step, sign, eps)
         torch.cuda.synchronize()
         y = d.y.cpu().numpy()
         assert np.isfinite(y).all()
@@ -57,16 +59,18 @@ def test_random_case(case):
     ws = szo.new_workspace()
     scal = torch.zeros(3, dtype=torch.float64, device="cuda")
     om = clone(o)
-    szo.szo_zo_step([d.desc(with_y=False)], seed, step, eps, 1e-3, scal, ws, szo.STEP_FUSED_LOSS)
+    szo.szo_zo_step([d.desc(dt, with_y=False)], seed, step, eps, 1e-3, scal, ws, szo.STEP_FUSED_LOSS)
     lp, lm, g = scal.cpu().numpy()
     r = ozo.zo_step([om], seed, step, eps, 1e-3)
     assert abs(lp - r["loss_plus"]) <= 5e-3 * r["loss_plus"] and abs(lm - r["loss_minus"]) <= 5e-3 * r["loss_minus"]
     sg = sigma_g([o])
-    assert abs(g - r["g"]) <= 1e-2 * max(abs(r["g"]), sg), (g, r["g"])
+    # the bf16 tile cannot hold w + eps z to the estimator's 1e-2 budget (8-bit significand): 1e-1 there
+    gtol = 1e-2 if dtname == "f16" else 1e-1
+    assert abs(g - r["g"]) <= gtol * max(abs(r["g"]), sg), (g, r["g"])
     if o.sp_idx.size == 0:              # k = 0: the device side keeps a small placeholder array
         return
     # the update is -lr g z: it inherits g's error, which is bounded relative to max(|g|, sigma_g)
     dv_gpu = d.sp_val.cpu().numpy().astype(np.float64) - o.sp_val
     dv_ref = om.sp_val.astype(np.float64) - o.sp_val
-    tol = 1e-2 * max(abs(r["g"]), sg) / max(abs(r["g"]), 1e-300) + 1e-2
+    tol = gtol * max(abs(r["g"]), sg) / max(abs(r["g"]), 1e-300) + 1e-2
     assert np.linalg.norm(dv_gpu - dv_ref) <= tol * np.linalg.norm(dv_ref) + 1e-12
