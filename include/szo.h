@@ -238,7 +238,9 @@ int szo_debug_zbar(uint64_t nnz_base, int64_t nnz, uint64_t seed, uint64_t step,
 /* Tuning/testing hook: which workgroup tile the forward uses.  0 = chosen from the shape
  * (default; also enables the few-token path for M <= 64), 1 = 128x128 outputs with 4 waves,
  * 2 = 256x256 outputs with 8 waves, 3 = as 2 and szo_zo_step always launches all forwards of a
- * step as one grid (with 0 and 2 it does so only when the step has at least 192 tiles).
+ * step as one grid (with 0 and 2 it does so only when the step has at least 192 tiles), 4 = as 0
+ * and the few-token path takes 32 token rows per pass for every layer with more than 16 tokens
+ * (by default only in launches large enough to fill the chip more than twice over).
  * Process-wide, not thread-safe; results do not depend on it beyond fp32 summation order. */
 int szo_set_tile_config(int config);
 

@@ -795,7 +795,9 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_table_kerne
 
 // ---- host side -----------------------------------------------------------------------------
 
-static int g_tile_config = 0;      // 0 = choose by shape, 1 = 128x128 (4 waves), 2 = 256x256 (8 waves), 3 = 2 + always group the step
+static int g_tile_config = 0;      // 0 = choose by shape, 1 = 128x128 (4 waves), 2 = 256x256 (8 waves), 3 = 2 + always group the step,
+                                   // 4 = as 0 with the few-token path's 32-row passes forced (see small_m_force_wide)
+static bool few_token_enabled() { return g_tile_config == 0 || g_tile_config == 4; }
 
 static int ilog2_exact(int v) {
   int s = 0;
@@ -856,7 +858,7 @@ static int launch(FwdParams& p, hipStream_t stream) {
 
 // Which workgroup tile a shape runs with, and how many workgroups (= loss partials) that makes.
 static int plan_tiles(int M, int N, int format, int* blocks_out) {
-  int cfg = g_tile_config;
+  int cfg = g_tile_config == 4 ? 0 : g_tile_config;
   if (format == SZO_FORMAT_LUT) cfg = 2;          // the table format exists for the 256x256 tile only
   if (cfg == 0) {
     const int64_t big_blocks = (int64_t)((M + 255) / 256) * ((N + 255) / 256);
@@ -1003,8 +1005,9 @@ using namespace szo;
 extern "C" {
 
 int szo_set_tile_config(int config) {
-  if (config < 0 || config > 3) return SZO_EINVAL;
+  if (config < 0 || config > 4) return SZO_EINVAL;
   g_tile_config = config;
+  small_m_force_wide(config == 4);
   return SZO_OK;
 }
 
@@ -1012,7 +1015,7 @@ int szo_linear_fwd(const szo_linear_desc* desc, uint64_t seed, uint64_t step, in
   const int rc = validate_desc(desc, sign, true, false);
   if (rc != SZO_OK) return rc;
   if (desc->M == 0 || desc->N == 0) return SZO_OK;
-  if (g_tile_config == 0 && small_m_step_eligible(desc))
+  if (few_token_enabled() && small_m_step_eligible(desc))
     return small_m_launch_one(desc, seed, step, sign == 0 ? 0.0f : eps, sign == 0 ? 1 : sign, false, nullptr, nullptr,
                               (hipStream_t)stream);
   return run_forward(desc, seed, step, sign, eps, nullptr, 0.0, (hipStream_t)stream);
@@ -1024,9 +1027,9 @@ int szo_linear_fwd_mse(const szo_linear_desc* desc, uint64_t seed, uint64_t step
   if (rc != SZO_OK) return rc;
   if (!loss_acc || !workspace || ((uintptr_t)workspace & 7)) return SZO_EINVAL;
   if (desc->M == 0 || desc->N == 0) return SZO_OK;
-  if (g_tile_config == 0 && small_m_step_eligible(desc) && scale == 1.0 / ((double)desc->M * (double)desc->N)) {
+  if (few_token_enabled() && small_m_step_eligible(desc) && scale == 1.0 / ((double)desc->M * (double)desc->N)) {
     // the few-token kernel computes both signs at once: make the requested one its "+" forward
-    const int nb = small_m_blocks(desc) * (int)((desc->M + 15) / 16);      // partials of all 16-row slices
+    const int nb = small_m_blocks(desc) * small_m_slices(desc);           // partials of all slices
     if (2 * nb > kMaxLossPartials) return SZO_EUNSUPPORTED;
     rc = small_m_launch_one(desc, seed, step, (float)sign * eps, 1, true, partial_area(workspace),
                             partial_area(workspace) + nb, (hipStream_t)stream);
@@ -1059,7 +1062,7 @@ int szo_zo_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t ste
   }
   int rc;
   // Few-token stacks: one pass over the weights serves both forwards of the step.
-  bool few = fuse && g_tile_config == 0 && n > 0 && n <= kMaxStepMatrices;
+  bool few = fuse && few_token_enabled() && n > 0 && n <= kMaxStepMatrices;
   for (int i = 0; few && i < n; ++i) few = small_m_step_eligible(&descs[i]);
   if (few) {
     return small_m_step(descs, n, seed, step, eps, lr, (char*)workspace + kWorkspaceTableOffset,

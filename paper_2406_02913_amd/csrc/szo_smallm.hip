@@ -1,5 +1,5 @@
-// Few-token path (16 token rows per pass; callers slice up to 64): the forward is bound by streaming the 4-bit weights from HBM, not by
-// the matrix cores, and the paper's own guideline for this regime (Appendix C.5) is the
+// Few-token path (16 or 32 token rows per pass; the host slices up to 64 tokens): the forward is bound by
+// streaming the 4-bit weights from HBM, not by the matrix cores, and the paper's own guideline for this regime (Appendix C.5) is the
 // SparseAddMM association:   y = x Dequantize(Q(w_dense))^T  +  x w_sparse^T.
 // Two consequences shape this kernel:
 //   * the dense product does not depend on the perturbation, so ONE pass over the weights
@@ -8,7 +8,7 @@
 //     a = x v^T  (added to the dense part) and  b = x z^T:  y(+-) = dense + a +- eps b.
 //
 // One workgroup = 256 output columns (4 bands of 64 rows of W, one wave each) x all of K, walked in
-// chunks of 256 columns of x that are staged in LDS as fp16 (16 token rows, zero padded).  The
+// chunks of 256 columns of x that are staged in LDS as fp16 (16 or 32 token rows, zero padded).  The
 // kernel is written for several small waves per SIMD (~150 registers, ~30 KB of LDS per workgroup):
 // a streaming-read probe on this chip reaches its ceiling with a few 16-byte loads in flight per
 // wave as long as enough waves are resident, and the resident waves hide each other's stalls.
@@ -66,7 +66,7 @@ struct SmallMat {
   uint64_t nnz_base;
   double loss_scale;
   int N, K;
-  int M;                    // token rows of this entry (<= 16): a matrix with more tokens is split into slices
+  int M;                    // token rows of this entry (<= 16 or <= 32, by instantiation): longer matrices are split into slices
   uint32_t nnz;
   int group_shift;
   uint32_t div_mul;
@@ -165,13 +165,17 @@ __device__ __forceinline__ half8_t sm_lut_word(uint32_t q, const uint32_t (&T)[8
 // MODE 2 (table format): dq = lut[row][code]; a lane keeps the tables of its four rows in registers
 // (32 of them; it needs neither scales nor the constants of the un-centred codes, so it still fits
 // the register budget of three workgroups per CU).
+// R = 16-row blocks of tokens per pass (1 or 2).  With R = 2 every dequantised operand is multiplied with
+// two blocks of token rows, so that matrices with 17..64 tokens stream their weights half as often;
+// it costs 48 more registers (accumulators and activation operands), i.e. two workgroups per CU.
 constexpr int SM_PLAIN = 0, SM_FAST = 1, SM_LUT = 2;
-template <int MODE>
-__global__ void __launch_bounds__(256, SM_MIN_BLOCKS) small_m_kernel(SmallArgs a) {
+template <int MODE, int R>
+__global__ void __launch_bounds__(256, R == 1 ? SM_MIN_BLOCKS : 2) small_m_kernel(SmallArgs a) {
   constexpr bool FAST = MODE == SM_FAST, LUT = MODE == SM_LUT;
+  constexpr int ROWS = SM_ROWS * R;                          // token rows of one pass
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-  _Float16* const xs = reinterpret_cast<_Float16*>(smem);                        // [2][16][SM_XSTRIDE]
-  uint16_t* const winp = reinterpret_cast<uint16_t*>(xs + 2 * SM_ROWS * SM_XSTRIDE);   // [4 bands][SM_CAP] packed position (see refill)
+  _Float16* const xs = reinterpret_cast<_Float16*>(smem);                        // [2][ROWS][SM_XSTRIDE]
+  uint16_t* const winp = reinterpret_cast<uint16_t*>(xs + 2 * ROWS * SM_XSTRIDE);      // [4 bands][SM_CAP] packed position (see refill)
   uint16_t* const winv = winp + 4 * SM_CAP;                                        // fp16 bits of v
   uint16_t* const winz = winv + 4 * SM_CAP;                                        // fp16 bits of z
 
@@ -236,9 +240,11 @@ __global__ void __launch_bounds__(256, SM_MIN_BLOCKS) small_m_kernel(SmallArgs a
   uint16_t* const my_winv = winv + wave * SM_CAP;
   uint16_t* const my_winz = winz + wave * SM_CAP;
 
-  float4_t acc[4], accz[4];                                 // dense + x v^T ;  x z^T
+  float4_t acc[R][4], accz[R][4];                           // per block of 16 token rows: dense + x v^T ;  x z^T
 #pragma unroll
-  for (int s = 0; s < 4; ++s) { acc[s] = float4_t{0.0f, 0.0f, 0.0f, 0.0f}; accz[s] = float4_t{0.0f, 0.0f, 0.0f, 0.0f}; }
+  for (int rb = 0; rb < R; ++rb)
+#pragma unroll
+    for (int s = 0; s < 4; ++s) { acc[rb][s] = float4_t{0.0f, 0.0f, 0.0f, 0.0f}; accz[rb][s] = float4_t{0.0f, 0.0f, 0.0f, 0.0f}; }
 
   // Banded layout (see the header): the band's 64 rows of one 64-column tile are 2 KB in a row, so
   // the 16 rows x 32 bytes that the lanes of one k-group pair read are contiguous, and a lane's four
@@ -268,14 +274,14 @@ __global__ void __launch_bounds__(256, SM_MIN_BLOCKS) small_m_kernel(SmallArgs a
     }
   }
   // ---- x staging: piece = 8 columns (16 bytes of bf16) of one row; thread handles pieces
-  //      (row tid>>5, columns 8*(tid&31)..) and the same columns of row 8 + (tid>>5) ----
+  //      (row tid>>5, columns 8*(tid&31)..) and the same columns of rows 8 i + (tid>>5), i < 2 R ----
   // Loads are unconditional, from clamped addresses, and out-of-range parts are zeroed only when the
   // registers are stored to LDS: a branch or an early use here would make every later wait a full drain.
-  u32x4 xr[2];
+  u32x4 xr[2 * R];
   auto load_x = [&](int c) {
     const int col = min(c * SM_KC + 8 * (tid & 31), K - 8);
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < 2 * R; ++i) {
       const int m = min((tid >> 5) + 8 * i, M - 1);
       xr[i] = *reinterpret_cast<const u32x4 __attribute__((address_space(1)))*>(g_x + (size_t)m * K + col);
     }
@@ -284,13 +290,13 @@ __global__ void __launch_bounds__(256, SM_MIN_BLOCKS) small_m_kernel(SmallArgs a
     const int ch = tid & 31, buf = c & 1;
     const bool col_ok = c * SM_KC + 8 * ch < K;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < 2 * R; ++i) {
       const int m = (tid >> 5) + 8 * i;
       const bool ok = col_ok && m < M;
       u32x4 o;
 #pragma unroll
       for (int w = 0; w < 4; ++w) o[w] = ok ? sm_stage_x_word(xr[i], w) : 0u;
-      *reinterpret_cast<u32x4*>(xs + (buf * SM_ROWS + m) * SM_XSTRIDE + 8 * ch) = o;
+      *reinterpret_cast<u32x4*>(xs + (buf * ROWS + m) * SM_XSTRIDE + 8 * ch) = o;
     }
   };
 
@@ -300,12 +306,13 @@ __global__ void __launch_bounds__(256, SM_MIN_BLOCKS) small_m_kernel(SmallArgs a
 #endif
   // slot (b % SM_RING)*4 + s: subtile s of 128-column block b.  With two blocks in flight the stream
   // keeps running while the wave is busy with the sparse part and the barrier of a chunk.
-  u32x4 qbuf[4 * SM_RING];
+  constexpr int RING = SM_RING;             // (two blocks in flight measured no faster with R = 2 either)
+  u32x4 qbuf[4 * RING];
   auto load_q = [&](int slot, int gkb) {
     qbuf[slot] = *reinterpret_cast<const u32x4 __attribute__((address_space(1)))*>(g_q + (size_t)min(gkb, nkb_total - 1) * 4096 + qoff[slot & 3]);
   };
 #pragma unroll
-  for (int i = 0; i < 4 * SM_RING; ++i) load_q(i, i >> 2);
+  for (int i = 0; i < 4 * RING; ++i) load_q(i, i >> 2);
   u32x2 sc[2] = {u32x2{0u, 0u}, u32x2{0u, 0u}};             // FAST: block kbl of the chunk: the lane's four scales (s = 0..3)
   auto load_scales = [&](int c) {
 #pragma unroll
@@ -366,30 +373,36 @@ __global__ void __launch_bounds__(256, SM_MIN_BLOCKS) small_m_kernel(SmallArgs a
 
   for (int c = 0; c < nchunks; ++c) {
     const int kc = c * SM_KC;
-    const _Float16* const xc = xs + (c & 1) * SM_ROWS * SM_XSTRIDE;
+    const _Float16* const xc = xs + (c & 1) * ROWS * SM_XSTRIDE;
     const uint32_t tp2 = tp_at(c + 2);
 
     // ---- dense: stream this band's codes ----
 #pragma unroll
     for (int kbl = 0; kbl < 2; ++kbl) {
       // blocks past the end of K multiply clamped codes with the zeros staged for x: no branch needed
-      half8_t af[4];
+      half8_t af[R][4];
 #pragma unroll
-      for (int t = 0; t < 4; ++t)
-        af[t] = *reinterpret_cast<const half8_t*>(xc + nn * SM_XSTRIDE + kbl * 128 + 32 * jj + 8 * t);
+      for (int rb = 0; rb < R; ++rb)
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+          af[rb][t] = *reinterpret_cast<const half8_t*>(xc + (16 * rb + nn) * SM_XSTRIDE + kbl * 128 + 32 * jj + 8 * t);
       // FAST: minus the constant part of the un-centred codes, sum_k x[m,k] (1032 | 72) over the block, from
       // one more MFMA chain against a constant operand; it seeds the four subtiles' chains.
-      float4_t init = {0.0f, 0.0f, 0.0f, 0.0f};
-      if (FAST) {
+      float4_t init[R];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) init = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[t], minus_offsets, init, 0, 0, 0);
+      for (int rb = 0; rb < R; ++rb) {
+        init[rb] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
+        if (FAST) {
+#pragma unroll
+          for (int t = 0; t < 4; ++t) init[rb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[rb][t], minus_offsets, init[rb], 0, 0, 0);
+        }
       }
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
-        constexpr int kRingMask = SM_RING - 1;
+        constexpr int kRingMask = RING - 1;
         const int slot = (kbl & kRingMask) * 4 + s;
         const u32x4 q = qbuf[slot];
-        load_q(slot, 2 * c + kbl + SM_RING);                // the slot is free: fetch the block SM_RING ahead
+        load_q(slot, 2 * c + kbl + RING);                   // the slot is free: fetch the block RING ahead
         _Float16 sh = (_Float16)0.0f;
         if (FAST) {
           sh = __builtin_bit_cast(half4_t, sc[kbl])[s];
@@ -399,19 +412,25 @@ __global__ void __launch_bounds__(256, SM_MIN_BLOCKS) small_m_kernel(SmallArgs a
               reinterpret_cast<const uint8_t __attribute__((address_space(1)))*>(g_scales) + (size_t)gi * 128 + soff + 2 * s));
         }
         const half2_t s2 = {sh, sh};
-        float4_t tmp = init;
+        float4_t tmp[R];
+#pragma unroll
+        for (int rb = 0; rb < R; ++rb) tmp[rb] = init[rb];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
           const half8_t b = LUT ? sm_lut_word(q[t], tb[LUT ? s : 0]) : sm_dequant_word<FAST>(q[t], magic_lo, magic_hi, s2);
-          tmp = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[t], b, tmp, 0, 0, 0);
+#pragma unroll
+          for (int rb = 0; rb < R; ++rb) tmp[rb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[rb][t], b, tmp[rb], 0, 0, 0);
         }
-        if (FAST) {
-          const float sf = (float)sh;                        // column nn of the subtile: the lane's own row of W
 #pragma unroll
-          for (int r = 0; r < 4; ++r) acc[s][r] = fmaf(tmp[r], sf, acc[s][r]);
-        } else {
+        for (int rb = 0; rb < R; ++rb) {
+          if (FAST) {
+            const float sf = (float)sh;                      // column nn of the subtile: the lane's own row of W
 #pragma unroll
-          for (int r = 0; r < 4; ++r) acc[s][r] += tmp[r];
+            for (int r = 0; r < 4; ++r) acc[rb][s][r] = fmaf(tmp[rb][r], sf, acc[rb][s][r]);
+          } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[rb][s][r] += tmp[rb][r];
+          }
         }
         // keep the subtiles in program order: hoisting the later ones' loads and unpacking costs registers,
         // and the latency they would hide is covered by the other resident waves
@@ -438,7 +457,7 @@ __global__ void __launch_bounds__(256, SM_MIN_BLOCKS) small_m_kernel(SmallArgs a
         const u32x2 vw = *reinterpret_cast<const u32x2*>(my_winv + ring);
         const u32x2 zw = *reinterpret_cast<const u32x2*>(my_winz + ring);
         const uint32_t rel = e0 - j_lo;                      // wraps for entries before the chunk's first
-        half4_t ax;
+        half4_t ax[R];
         uint32_t mlo[4], mhi[4];                            // entry i: 0xFFFF in halfword s of (mlo, mhi) iff this lane
 #pragma unroll                                              // owns the entry's row in subtile s
         for (int i = 0; i < 4; ++i) {
@@ -446,7 +465,9 @@ __global__ void __launch_bounds__(256, SM_MIN_BLOCKS) small_m_kernel(SmallArgs a
           const int sh = 16 * (i & 1);
           // Entries outside [j_lo, j_hi) are masked out below; their column field is < 256 whatever the
           // window holds, so the gather stays inside the staged row.
-          ax[i] = xrow[__builtin_amdgcn_ubfe(w, sh, 8)];
+          const uint32_t col = __builtin_amdgcn_ubfe(w, sh, 8);
+#pragma unroll
+          for (int rb = 0; rb < R; ++rb) ax[rb][i] = xrow[16 * rb * SM_XSTRIDE + col];
           const bool mine = rel + (uint32_t)i < span && __builtin_amdgcn_ubfe(w, sh + 8, 4) == (uint32_t)nn;
           const uint32_t s16 = (w >> (sh + 8)) & 0x30u;     // 16 * subtile
           const uint64_t m = (uint64_t)0xFFFFu << s16;
@@ -464,8 +485,11 @@ __global__ void __launch_bounds__(256, SM_MIN_BLOCKS) small_m_kernel(SmallArgs a
             bv[h] = vw[h] & mask;
             bz[h] = zw[h] & mask;
           }
-          acc[s] = __builtin_amdgcn_mfma_f32_16x16x16f16(ax, __builtin_bit_cast(half4_t, bv), acc[s], 0, 0, 0);
-          accz[s] = __builtin_amdgcn_mfma_f32_16x16x16f16(ax, __builtin_bit_cast(half4_t, bz), accz[s], 0, 0, 0);
+#pragma unroll
+          for (int rb = 0; rb < R; ++rb) {
+            acc[rb][s] = __builtin_amdgcn_mfma_f32_16x16x16f16(ax[rb], __builtin_bit_cast(half4_t, bv), acc[rb][s], 0, 0, 0);
+            accz[rb][s] = __builtin_amdgcn_mfma_f32_16x16x16f16(ax[rb], __builtin_bit_cast(half4_t, bz), accz[rb][s], 0, 0, 0);
+          }
         }
       }
     }
@@ -475,24 +499,26 @@ __global__ void __launch_bounds__(256, SM_MIN_BLOCKS) small_m_kernel(SmallArgs a
     __syncthreads();                                        // next chunk's x complete; this chunk's no longer read
   }
 
-  // ---- epilogue: accumulator s, register r = token row 4*jj + r, column 16*s + nn of the band ----
+  // ---- epilogue: accumulator (rb, s), register r = token row 16*rb + 4*jj + r, column 16*s + nn of the band ----
   double lp = 0.0, lm = 0.0;
+#pragma unroll
+  for (int rb = 0; rb < R; ++rb)
 #pragma unroll
   for (int s = 0; s < 4; ++s) {
     const int nl = 16 * s + nn, n = n0 + wave * 64 + nl;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const int m = 4 * jj + r;
+      const int m = 16 * rb + 4 * jj + r;
       if (m < M && n < N) {
-        const float pz = a.eps * accz[s][r];
-        const float yp = acc[s][r] + pz, ym = acc[s][r] - pz;
+        const float pz = a.eps * accz[rb][s][r];
+        const float yp = acc[rb][s][r] + pz, ym = acc[rb][s][r] - pz;
         if (a.loss_mode) {
           const float t = __uint_as_float((uint32_t)g_target[(size_t)m * N + n] << 16);
           const float dp = yp - t, dm = ym - t;
           lp += (double)(dp * dp);
           lm += (double)(dm * dm);
         } else {
-          g_y[(size_t)m * N + n] = a.store_sign > 0 ? yp : a.store_sign < 0 ? ym : acc[s][r];
+          g_y[(size_t)m * N + n] = a.store_sign > 0 ? yp : a.store_sign < 0 ? ym : acc[rb][s][r];
         }
       }
     }
@@ -541,8 +567,18 @@ __global__ void __launch_bounds__(256) sparse_update_table_kernel(const SmallMat
 
 // ---- host side -----------------------------------------------------------------------------
 
-static size_t small_lds_bytes() {
-  return (size_t)2 * SM_ROWS * SM_XSTRIDE * 2 + (size_t)3 * 4 * SM_CAP * 2;
+static size_t small_lds_bytes(int r) {
+  return (size_t)2 * SM_ROWS * r * SM_XSTRIDE * 2 + (size_t)3 * 4 * SM_CAP * 2;
+}
+// Blocks of 16 token rows per pass for a matrix of a launch.  Two (half as many passes over the weights)
+// only pay when the launch is large: two-block workgroups run two to a CU instead of three, and a launch
+// that fits the chip in one go (measured: a single decoder block) is faster as more, smaller passes side
+// by side.  `launch_wgs16` = workgroups the whole launch would have with 16 rows per pass.
+constexpr int64_t kSmallWideWorkgroups = 1536;              // two rounds of the 768 workgroups the chip holds
+static bool g_force_wide = false;
+void small_m_force_wide(bool on) { g_force_wide = on; }
+static int small_m_rblocks(const szo_linear_desc* d, int64_t launch_wgs16) {
+  return (d->M > SM_ROWS && (g_force_wide || launch_wgs16 > kSmallWideWorkgroups)) ? 2 : 1;
 }
 
 bool small_m_eligible(const szo_linear_desc* d) {
@@ -557,16 +593,26 @@ static int small_m_mode(const szo_linear_desc* d) {
   if (d->format == SZO_FORMAT_LUT) return SM_LUT;
   return d->group == 128 ? SM_FAST : SM_PLAIN;
 }
-// position of a mode in a step's table and launch order
-static int small_m_class(const szo_linear_desc* d) {
+// position of an instantiation (mode, row blocks) in a step's table and launch order
+constexpr int kSmallClasses = 6;
+static int small_m_class(const szo_linear_desc* d, int rblocks) {
   const int m = small_m_mode(d);
-  return m == SM_FAST ? 0 : m == SM_LUT ? 1 : 2;
+  return 2 * (m == SM_FAST ? 0 : m == SM_LUT ? 1 : 2) + (rblocks - 1);
 }
+static int class_mode(int cls) { return cls / 2 == 0 ? SM_FAST : cls / 2 == 1 ? SM_LUT : SM_PLAIN; }
+static int class_rblocks(int cls) { return cls % 2 + 1; }
 
-static void small_m_launch(int mode, int blocks, const SmallArgs& a, hipStream_t stream) {
-  if (mode == SM_FAST) small_m_kernel<SM_FAST><<<blocks, 256, small_lds_bytes(), stream>>>(a);
-  else if (mode == SM_LUT) small_m_kernel<SM_LUT><<<blocks, 256, small_lds_bytes(), stream>>>(a);
-  else small_m_kernel<SM_PLAIN><<<blocks, 256, small_lds_bytes(), stream>>>(a);
+static void small_m_launch(int mode, int r, int blocks, const SmallArgs& a, hipStream_t stream) {
+  const size_t lds = small_lds_bytes(r);
+  if (r == 1) {
+    if (mode == SM_FAST) small_m_kernel<SM_FAST, 1><<<blocks, 256, lds, stream>>>(a);
+    else if (mode == SM_LUT) small_m_kernel<SM_LUT, 1><<<blocks, 256, lds, stream>>>(a);
+    else small_m_kernel<SM_PLAIN, 1><<<blocks, 256, lds, stream>>>(a);
+  } else {
+    if (mode == SM_FAST) small_m_kernel<SM_FAST, 2><<<blocks, 256, lds, stream>>>(a);
+    else if (mode == SM_LUT) small_m_kernel<SM_LUT, 2><<<blocks, 256, lds, stream>>>(a);
+    else small_m_kernel<SM_PLAIN, 2><<<blocks, 256, lds, stream>>>(a);
+  }
 }
 
 // The step also takes matrices with up to 64 tokens: they run as up to four 16-token slices, each a
@@ -579,6 +625,16 @@ bool small_m_step_eligible(const szo_linear_desc* d) {
 }
 
 int small_m_blocks(const szo_linear_desc* d) { return (int)((d->N + SM_BN - 1) / SM_BN); }
+
+static int64_t small_m_wgs16(const szo_linear_desc* d) {
+  return (int64_t)small_m_blocks(d) * ((d->M + SM_ROWS - 1) / SM_ROWS);
+}
+static int slices_of(const szo_linear_desc* d, int rblocks) {
+  const int rows = SM_ROWS * rblocks;
+  return (int)((d->M + rows - 1) / rows);
+}
+// passes of a single-matrix call
+int small_m_slices(const szo_linear_desc* d) { return slices_of(d, small_m_rblocks(d, small_m_wgs16(d))); }
 
 size_t small_m_table_bytes(int n) { return sizeof(SmallMat) * (size_t)n; }
 
@@ -603,19 +659,19 @@ static void fill_mat(SmallMat& m, const szo_linear_desc* d) {
 static int set_small_attrs() {
   static bool attr_set = false;
   if (!attr_set) {
-    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_FAST>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)small_lds_bytes()));
-    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_PLAIN>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)small_lds_bytes()));
-    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_LUT>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)small_lds_bytes()));
+    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_FAST, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds_bytes(1)));
+    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_PLAIN, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds_bytes(1)));
+    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_LUT, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds_bytes(1)));
+    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_FAST, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds_bytes(2)));
+    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_PLAIN, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds_bytes(2)));
+    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_LUT, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds_bytes(2)));
     attr_set = true;
   }
   return SZO_OK;
 }
 
 // One matrix, descriptor passed in the kernel arguments (no device table needed).
-// Up to 64 token rows: one launch per slice of 16 rows (the kernel multiplies 16 rows at a time).  In loss
+// Up to 64 token rows: one launch per slice of 16 rows (up to 16 tokens) or 32 rows (more).  In loss
 // mode slice i writes its partials at partial_*[i * small_m_blocks(d) ..], scaled by 1 / (M N) of the
 // whole matrix, so that their sum over all slices is the matrix's loss.
 int small_m_launch_one(const szo_linear_desc* d, uint64_t seed, uint64_t step, float eps, int sign, bool loss_mode,
@@ -623,14 +679,16 @@ int small_m_launch_one(const szo_linear_desc* d, uint64_t seed, uint64_t step, f
   const int rc = set_small_attrs();
   if (rc != SZO_OK) return rc;
   const int blocks = small_m_blocks(d);
-  const int slices = (int)((d->M + SM_ROWS - 1) / SM_ROWS);
+  const int rblocks = small_m_rblocks(d, small_m_wgs16(d));
+  const int rows = SM_ROWS * rblocks;
+  const int slices = slices_of(d, rblocks);
   for (int sl = 0; sl < slices; ++sl) {
     SmallArgs a{};
     fill_mat(a.one, d);                                     // loss_scale from the whole matrix
-    a.one.x += (size_t)sl * SM_ROWS * (size_t)d->K;
-    if (a.one.target) a.one.target += (size_t)sl * SM_ROWS * (size_t)d->N;
-    if (a.one.y) a.one.y += (size_t)sl * SM_ROWS * (size_t)d->N;
-    a.one.M = (int)std::min<int64_t>(SM_ROWS, d->M - (int64_t)sl * SM_ROWS);
+    a.one.x += (size_t)sl * rows * (size_t)d->K;
+    if (a.one.target) a.one.target += (size_t)sl * rows * (size_t)d->N;
+    if (a.one.y) a.one.y += (size_t)sl * rows * (size_t)d->N;
+    a.one.M = (int)std::min<int64_t>(rows, d->M - (int64_t)sl * rows);
     a.table = nullptr; a.n_mats = 1;
     a.store_sign = sign; a.loss_mode = loss_mode ? 1 : 0;
     a.seed = seed; a.step = step; a.eps = eps;
@@ -638,7 +696,7 @@ int small_m_launch_one(const szo_linear_desc* d, uint64_t seed, uint64_t step, f
     a.partial_minus = partial_minus ? partial_minus + (size_t)sl * blocks : nullptr;
     const int trc = timing_begin(stream);
     if (trc != SZO_OK) return trc;
-    small_m_launch(small_m_mode(d), blocks, a, stream);
+    small_m_launch(small_m_mode(d), rblocks, blocks, a, stream);
     SZO_LAUNCH_CHECK();
     const int erc = timing_end(stream);
     if (erc != SZO_OK) return erc;
@@ -657,16 +715,21 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
   int rc = set_small_attrs();
   if (rc != SZO_OK) return rc;
   if (n > kMaxStepMatrices) return SZO_EUNSUPPORTED;
+  int64_t wgs16 = 0;
+  for (int i = 0; i < n; ++i) wgs16 += small_m_wgs16(&descs[i]);
+  auto rblocks_of = [&](const szo_linear_desc* d) { return small_m_rblocks(d, wgs16); };
   int max_entries = 0;
-  for (int i = 0; i < n; ++i) max_entries += do_forward ? (int)((descs[i].M + SM_ROWS - 1) / SM_ROWS) : 1;
+  for (int i = 0; i < n; ++i) max_entries += do_forward ? slices_of(&descs[i], rblocks_of(&descs[i])) : 1;
   if (small_m_table_bytes(max_entries) > kTableBytesPerMatrix * (size_t)kMaxStepMatrices) return SZO_EUNSUPPORTED;
   static thread_local std::vector<SmallMat> host_table;
   host_table.resize((size_t)max_entries);
   SmallMat* const host = host_table.data();
-  // order: by instantiation (fast, table format, plain), inside each by K descending
+  // order: by instantiation (fast, table format, plain; 16 rows before 32), inside each by K descending
   int order[kMaxStepMatrices];
   for (int i = 0; i < n; ++i) order[i] = i;
-  auto sort_key = [&](int o) { return ((int64_t)(2 - small_m_class(&descs[o])) << 40) + descs[o].K; };
+  auto sort_key = [&](int o) {
+    return ((int64_t)(kSmallClasses - 1 - small_m_class(&descs[o], rblocks_of(&descs[o]))) << 40) + descs[o].K;
+  };
   for (int i = 1; i < n; ++i) {                       // insertion sort: n is a few hundred
     const int o = order[i];
     const int64_t key = sort_key(o);
@@ -678,20 +741,22 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
     }
     order[j + 1] = o;
   }
-  int class_entries[3] = {0, 0, 0}, class_blocks[3] = {0, 0, 0}, partials = 0, entries = 0;
+  int class_entries[kSmallClasses] = {}, class_blocks[kSmallClasses] = {}, partials = 0, entries = 0;
   int64_t quads = 0;
   for (int r = 0; r < n; ++r) {
     const szo_linear_desc* d = &descs[order[r]];
-    const int cls = small_m_class(d);
-    // forward: one table entry per slice of 16 token rows; update only: one entry per matrix
-    const int slices = do_forward ? (int)((d->M + SM_ROWS - 1) / SM_ROWS) : 1;
+    const int rblocks = rblocks_of(d);
+    const int cls = small_m_class(d, rblocks);
+    // forward: one table entry per slice of 16 or 32 token rows; update only: one entry per matrix
+    const int rows = SM_ROWS * rblocks;
+    const int slices = do_forward ? slices_of(d, rblocks) : 1;
     for (int sl = 0; sl < slices; ++sl) {
       SmallMat& m = host[entries++];
       fill_mat(m, d);
       if (do_forward) {
-        m.x += (size_t)sl * SM_ROWS * (size_t)d->K;
-        m.target += (size_t)sl * SM_ROWS * (size_t)d->N;
-        m.M = (int)std::min<int64_t>(SM_ROWS, d->M - (int64_t)sl * SM_ROWS);
+        m.x += (size_t)sl * rows * (size_t)d->K;
+        m.target += (size_t)sl * rows * (size_t)d->N;
+        m.M = (int)std::min<int64_t>(rows, d->M - (int64_t)sl * rows);
       }
       m.first_block = class_blocks[cls];
       m.partial_base = partials;
@@ -712,11 +777,11 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
   a.partial_plus = partial_plus; a.partial_minus = partial_plus + partials;
   const SmallMat* tdev = (const SmallMat*)table_dev;
   int first_entry = 0;
-  for (int cls = 0; cls < 3; ++cls) {
+  for (int cls = 0; cls < kSmallClasses; ++cls) {
     if (do_forward && class_blocks[cls] > 0) {
       a.table = tdev + first_entry; a.n_mats = class_entries[cls];
       if ((rc = timing_begin(stream)) != SZO_OK) return rc;
-      small_m_launch(cls == 0 ? SM_FAST : cls == 1 ? SM_LUT : SM_PLAIN, class_blocks[cls], a, stream);
+      small_m_launch(class_mode(cls), class_rblocks(cls), class_blocks[cls], a, stream);
       SZO_LAUNCH_CHECK();
       if ((rc = timing_end(stream)) != SZO_OK) return rc;
     }

@@ -10,6 +10,12 @@ from helpers import make_pair, clone, rel_fro, sigma_g
 
 pytestmark = pytest.mark.gpu
 
+
+@pytest.fixture(autouse=True)
+def _auto_tile_config():
+    yield
+    szo.szo_set_tile_config(0)
+
 # (seed, M, N, K, group, density)
 SHAPES = [
     (11, 16, 256, 128, 128, 1e-2),      # one strip, one 128-column block (half a chunk: plain instantiation)
@@ -27,10 +33,11 @@ SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("shape", SHAPES)
-def test_few_token_forward_matches_oracle(shape):
+# configuration 4: 32 token rows per pass wherever there are more than 16 (otherwise only in large launches)
+@pytest.mark.parametrize("shape,cfg", [(sh, 0) for sh in SHAPES] + [(sh, 4) for sh in SHAPES if sh[1] > 16])
+def test_few_token_forward_matches_oracle(shape, cfg):
     s, M, N, K, G, dens = shape
-    szo.szo_set_tile_config(0)
+    szo.szo_set_tile_config(cfg)
     o, d = make_pair(s, M, N, K, G, dens, nnz_base=12)
     seed, step, eps = 77, 5, 1e-3
     z = ophilox.zbar(seed, step, 12, o.sp_idx.size)
@@ -164,10 +171,12 @@ def test_one_full_size_block_at_16_tokens_two_steps():
         assert np.linalg.norm(dv_gpu - dv_ref) <= 3e-2 * np.linalg.norm(dv_ref) + 1e-12
 
 
-def test_step_with_up_to_64_tokens_runs_as_16_token_slices():
-    """17..64 tokens: the step streams the weights once per slice of 16 token rows; matrices of
-    different token counts may share a step, and the sparse values are updated exactly once."""
-    szo.szo_set_tile_config(0)
+@pytest.mark.parametrize("cfg", [0, 4])
+def test_step_with_up_to_64_tokens_runs_as_slices(cfg):
+    """17..64 tokens: the step streams the weights once per slice of 16 token rows, or of 32 in launches
+    that are large (configuration 4 forces that); matrices of different token counts may share a step,
+    and the sparse values are updated exactly once."""
+    szo.szo_set_tile_config(cfg)
     o1, d1 = make_pair(51, 64, 320, 512, 128, 2e-3, nnz_base=0)
     b2 = (o1.sp_idx.size + 3) // 4 * 4
     o2, d2 = make_pair(52, 40, 256, 384, 64, 5e-3, nnz_base=b2)          # ragged last slice, plain instantiation
@@ -189,7 +198,9 @@ def test_step_with_up_to_64_tokens_runs_as_16_token_slices():
         assert abs(g - r["g"]) <= 1e-2 * max(abs(r["g"]), sg), (s, g, r["g"], sg)
     _, launches = szo.szo_kernel_timing_read()
     szo.szo_kernel_timing(False)
-    assert launches == 6                       # few-token path: one launch per instantiation and step
+    # few-token path: one launch per instantiation and step: group 128 and group 64 with 16 rows per pass,
+    # or group 128 x 32 rows, group 64 x 32 rows and group 128 x 16 rows
+    assert launches == (6 if cfg == 0 else 9)
     for om, dd, o in zip(ref, ds_, os_):
         dv_gpu = dd.sp_val.cpu().numpy().astype(np.float64) - o.sp_val
         dv_ref = om.sp_val.astype(np.float64) - o.sp_val

@@ -117,10 +117,11 @@ FEW = [
 ]
 
 
-@pytest.mark.parametrize("shape", FEW)
-def test_few_token_forward_matches_oracle(shape):
+# configuration 4: 32 token rows per pass wherever there are more than 16 (otherwise only in large launches)
+@pytest.mark.parametrize("shape,cfg", [(sh, 0) for sh in FEW] + [(sh, 4) for sh in FEW if sh[1] > 16])
+def test_few_token_forward_matches_oracle(shape, cfg):
     s, M, N, K, dens = shape
-    szo.szo_set_tile_config(0)
+    szo.szo_set_tile_config(cfg)
     o, d = make_pair(s, M, N, K, 128, dens, nnz_base=12, fmt="lut")
     seed, step, eps = 77, 5, 1e-3
     z = ophilox.zbar(seed, step, 12, o.sp_idx.size)
@@ -138,9 +139,10 @@ def test_few_token_forward_matches_oracle(shape):
         assert rel_fro(tiled[sign], y2) <= 2e-4 and not np.array_equal(tiled[sign], y2)
 
 
-def test_few_token_step_with_all_three_instantiations():
+@pytest.mark.parametrize("cfg", [0, 4])
+def test_few_token_step_with_all_three_instantiations(cfg):
     # one step over a table-format layer, a group-128 layer and a group-64 layer: three launches, one g
-    szo.szo_set_tile_config(0)
+    szo.szo_set_tile_config(cfg)
     o1, d1 = make_pair(67, 16, 256, 512, 128, 1e-2, nnz_base=0, fmt="lut")
     b2 = (o1.sp_idx.size + 3) // 4 * 4
     o2, d2 = make_pair(68, 48, 320, 256, 128, 5e-3, nnz_base=b2)
@@ -168,8 +170,9 @@ def test_few_token_step_with_all_three_instantiations():
         assert np.linalg.norm(dv_gpu - dv_ref) <= 3e-2 * np.linalg.norm(dv_ref)
 
 
-def test_few_token_single_calls_with_loss():
-    szo.szo_set_tile_config(0)
+@pytest.mark.parametrize("cfg", [0, 4])
+def test_few_token_single_calls_with_loss(cfg):
+    szo.szo_set_tile_config(cfg)
     o, d = make_pair(70, 40, 256, 512, 128, 1e-2, fmt="lut")
     seed, eps = 5, 1e-3
     ws = szo.new_workspace()
