@@ -201,9 +201,10 @@ def main():
                     help="4-bit format of the frozen part: uniform codes with group scales (the workloads' format) or "
                          "the non-uniform one, a table of 16 fp16 centroids per output row")
     ap.add_argument("--unfused-loss", action="store_true", help="write y and run the separate loss kernel")
-    ap.add_argument("--tile-config", type=int, default=0, choices=[0, 1, 2],
-                    help="0: the library chooses (few-token path for M <= 64); 1 / 2: force the tiled kernel with "
-                         "128x128 / 256x256 workgroup tiles (for comparisons)")
+    ap.add_argument("--tile-config", type=int, default=0, choices=[0, 1, 2, 3, 4],
+                    help="0: the library chooses (few-token path for M <= 128); 1 / 2: force the tiled kernel with "
+                         "128x128 / 256x256 workgroup tiles; 3: as 2, and always one grouped launch per step; 4: as 0 "
+                         "with 32 token rows per pass of the few-token path wherever there are more than 16 (for comparisons)")
     ap.add_argument("--seed", type=int, default=2024)
     ap.add_argument("--data-seed", type=int, default=0)
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle baseline leg (0 = skip)")
@@ -250,7 +251,7 @@ def main():
     import torch
     from paper_2406_02913_amd import stack, synth, szo
 
-    few_default = (args.m or synth.WORKLOADS[args.workload]["M"]) <= 64
+    few_default = (args.m or synth.WORKLOADS[args.workload]["M"]) <= 128
     if args.steps is None:
         args.steps = 200 if few_default else 20
     if args.warmup is None:
@@ -305,7 +306,7 @@ def main():
     # ---- the dominant kernel alone: the library brackets every forward-kernel launch of a few more
     #      steps with events on the launch stream (szo_kernel_timing) ----
     fwd_flops = sum(2.0 * m.M * m.N * m.K for m in mats)
-    few = all(m.M <= 64 for m in mats) and dt == szo.TILE_F16 and args.tile_config == 0   # the library's few-token path
+    few = all(m.M <= 128 for m in mats) and dt == szo.TILE_F16 and args.tile_config in (0, 4)   # the library's few-token path
     reps = args.steps if args.kernel_reps is None else max(1, args.kernel_reps)
     szo.szo_kernel_timing(True)
     for s in range(reps):

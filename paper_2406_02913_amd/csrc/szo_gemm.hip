@@ -21,6 +21,7 @@
 // them 256 at a time (one Philox counter = four consecutive entries per lane) into a small
 // LDS window holding (tile position, value), and each K step only copies the few entries of
 // its tile from the window into the weight tile.
+#include <algorithm>
 #include <cstddef>
 #include <vector>
 #include "szo_internal.h"
@@ -929,13 +930,15 @@ static int run_forward(const szo_linear_desc* d, uint64_t seed, uint64_t step, i
 
 static double* partial_area(void* workspace) { return (double*)((char*)workspace + kWorkspaceHeader); }
 
-template <int DT, int FMT = SZO_FORMAT_UNIFORM>
+template <int DT, int FMT = SZO_FORMAT_UNIFORM, int TILE = 256>
 static int launch_table(const FwdParams* table_dev, int entries, int64_t blocks, hipStream_t stream) {
-  constexpr int BM = 256, BN = 256;
+  static_assert(TILE == 256 || TILE == 128, "two workgroup tiles exist");
+  constexpr int BM = TILE, BN = TILE;
+  constexpr int WAVES_N = TILE == 256 ? 4 : 2, WMB = TILE == 256 ? 4 : 2;      // 2x4 waves of 128x64, or 2x2 of 64x64
   constexpr size_t main_bytes = 2 * (size_t)(BM + BN) * BK * sizeof(uint16_t) + (size_t)(BN / 64) * (kWindow * 6 + 128);
   constexpr size_t target_bytes = (size_t)BM * (BN * 2 + 32);
   constexpr size_t lds_bytes = main_bytes > target_bytes ? main_bytes : target_bytes;
-  auto kern = linear_fwd_table_kernel<2, 4, 4, 2, DT, true, FMT>;
+  auto kern = linear_fwd_table_kernel<2, WAVES_N, WMB, 2, DT, true, FMT>;
   static bool attr_set = false;
   if (!attr_set) {
     SZO_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
@@ -943,12 +946,14 @@ static int launch_table(const FwdParams* table_dev, int entries, int64_t blocks,
   }
   int rc = timing_begin(stream);
   if (rc != SZO_OK) return rc;
-  kern<<<(unsigned)blocks, 512, lds_bytes, stream>>>(table_dev, entries);
+  kern<<<(unsigned)blocks, 128 * WAVES_N, lds_bytes, stream>>>(table_dev, entries);
   SZO_LAUNCH_CHECK();
   return timing_end(stream);
 }
 
-// Both forwards of every matrix of a step as ONE launch of 256x256 tiles with the loss fused.
+// Both forwards of every matrix of a step as ONE launch with the loss fused: 256x256 tiles, or 128x128
+// when the library chooses the tiles and no matrix has more than 128 tokens (a 256-row tile would then
+// be at least half padding).
 // Returns SZO_EUNSUPPORTED when the stack does not qualify (the caller then launches per matrix):
 // mixed tile types or formats, a table that does not fit the workspace, or too few tiles to fill the chip.
 // On success *partials_per_sign is the number of loss partials of one sign: the "+" partials are
@@ -956,13 +961,17 @@ static int launch_table(const FwdParams* table_dev, int entries, int64_t blocks,
 static int grouped_forwards(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t step, float eps,
                             void* table_dev, double* partials, int64_t* partials_per_sign, hipStream_t stream) {
   if (g_tile_config == 1) return SZO_EUNSUPPORTED;
+  int64_t max_m = 0;
+  for (int i = 0; i < n; ++i) max_m = std::max<int64_t>(max_m, descs[i].N > 0 ? descs[i].M : 0);
+  const bool auto_tiles = g_tile_config == 0 || g_tile_config == 4;
+  const int tile = (auto_tiles && n > 0 && descs[0].format == SZO_FORMAT_UNIFORM && max_m <= 128) ? 128 : 256;
   int64_t T = 0;
   int live = 0;
   for (int i = 0; i < n; ++i) {
     const szo_linear_desc* d = &descs[i];
     if (d->M == 0 || d->N == 0) continue;
     if (d->tile_dtype != descs[0].tile_dtype || d->format != descs[0].format) return SZO_EUNSUPPORTED;
-    T += (int64_t)((d->M + 255) / 256) * ((d->N + 255) / 256);
+    T += (int64_t)((d->M + tile - 1) / tile) * ((d->N + tile - 1) / tile);
     ++live;
   }
   if ((T < 192 && g_tile_config != 3) || T == 0 || 2 * T > kMaxLossPartials) return SZO_EUNSUPPORTED;
@@ -974,7 +983,7 @@ static int grouped_forwards(const szo_linear_desc* descs, int n, uint64_t seed, 
     const szo_linear_desc* d = &descs[i];
     if (d->M == 0 || d->N == 0) continue;
     const double scale = 1.0 / ((double)d->M * (double)d->N);
-    const int gm = (int)((d->M + 255) / 256), gn = (int)((d->N + 255) / 256);
+    const int gm = (int)((d->M + tile - 1) / tile), gn = (int)((d->N + tile - 1) / tile);
     for (int pass = 0; pass < 2; ++pass) {                  // "+" then "-": the pair shares x and the codes in L2
       FwdParams p;
       const int rc = fill_params(p, d, seed, step, pass == 0 ? +1 : -1, eps, partials + (pass == 0 ? 0 : T) + offset, scale);
@@ -993,6 +1002,11 @@ static int grouped_forwards(const szo_linear_desc* descs, int n, uint64_t seed, 
   *partials_per_sign = T;
   if (descs[0].format == SZO_FORMAT_LUT)
     return launch_table<SZO_TILE_F16, SZO_FORMAT_LUT>((const FwdParams*)table_dev, (int)table.size(), first_block, stream);
+  if (tile == 128) {
+    if (descs[0].tile_dtype == SZO_TILE_F16)
+      return launch_table<SZO_TILE_F16, SZO_FORMAT_UNIFORM, 128>((const FwdParams*)table_dev, (int)table.size(), first_block, stream);
+    return launch_table<SZO_TILE_BF16, SZO_FORMAT_UNIFORM, 128>((const FwdParams*)table_dev, (int)table.size(), first_block, stream);
+  }
   if (descs[0].tile_dtype == SZO_TILE_F16)
     return launch_table<SZO_TILE_F16>((const FwdParams*)table_dev, (int)table.size(), first_block, stream);
   return launch_table<SZO_TILE_BF16>((const FwdParams*)table_dev, (int)table.size(), first_block, stream);

@@ -120,7 +120,7 @@ def test_bf16_tile_is_available_and_less_accurate_on_g():
 
 
 def test_kernel_timing_counts_forward_launches_only():
-    _, d = make_pair(3, 128, 256, 256, 32, 1e-3)        # more than 64 tokens: the tiled path
+    _, d = make_pair(3, 160, 256, 256, 32, 1e-3)        # more than 128 tokens: the tiled path
     ws = szo.new_workspace()
     scal = torch.zeros(3, dtype=torch.float64, device="cuda")
     szo.szo_set_tile_config(0)
@@ -217,3 +217,45 @@ def test_more_matrices_than_one_descriptor_table_holds():
     assert abs(lp - r["loss_plus"]) <= 5e-3 * r["loss_plus"] and abs(lm - r["loss_minus"]) <= 5e-3 * r["loss_minus"]
     assert abs(g - r["g"]) <= 1e-2 * max(abs(r["g"]), sigma_g(mats[:1]) * np.sqrt(n))
     assert torch.equal(before, d.sp_val)
+
+
+def test_grouped_launch_with_128_row_tiles_for_steps_of_at_most_128_tokens():
+    """Up to 128 tokens where the few-token path does not apply (here: one K is not a multiple of 128): a
+    256-row tile would be mostly padding, so with the library choosing, a step that is large enough runs
+    as one grid of 128x128 tiles; it must equal the per-matrix launches of the same tiles (configuration 1)
+    bit for bit, and the oracle."""
+    shapes = [(71, 100, 8192, 128, 128, 2e-3), (72, 128, 8200, 192, 64, 1e-3), (73, 65, 8192, 256, 32, 0.0)]
+    results = []
+    for cfg in (1, 0):
+        szo.szo_set_tile_config(cfg)
+        os_, ds_, base = [], [], 0
+        for (sd, M, N, K, G, dens) in shapes:
+            o, d = make_pair(sd, M, N, K, G, dens, nnz_base=base)
+            base += (o.sp_idx.size + 3) // 4 * 4
+            os_.append(o)
+            ds_.append(d)
+        ws = szo.new_workspace()
+        scal = torch.zeros(3, dtype=torch.float64, device="cuda")
+        descs = szo.desc_array([d.desc(with_y=False) for d in ds_])
+        hist = []
+        szo.szo_kernel_timing(True)
+        for s in range(2):
+            szo.szo_zo_step(descs, 37, s, 1e-3, 1e-3, scal, ws, szo.STEP_FUSED_LOSS)
+            hist.append(scal.cpu().numpy().copy())
+        _, launches = szo.szo_kernel_timing_read()
+        szo.szo_kernel_timing(False)
+        assert launches == (2 if cfg == 0 else 2 * 2 * len(shapes))
+        results.append((hist, [d.sp_val.cpu().numpy().copy() for d in ds_]))
+        if cfg == 0:
+            ref = [clone(o) for o in os_]
+            sg = sigma_g(os_)
+            for s in range(2):
+                r = ozo.zo_step(ref, 37, s, 1e-3, 1e-3)
+                lp, lm, g = hist[s]
+                assert abs(lp - r["loss_plus"]) <= 1e-6 * r["loss_plus"]
+                assert abs(g - r["g"]) <= 1e-2 * max(abs(r["g"]), sg)
+    (h1, v1), (h0, v0) = results
+    for a, b in zip(h1, h0):
+        assert np.array_equal(a, b)
+    for a, b in zip(v1, v0):
+        assert np.array_equal(a, b)
