@@ -207,6 +207,15 @@ __global__ void __launch_bounds__(256, R == 1 ? SM_MIN_BLOCKS : 2) small_m_kerne
 #pragma unroll
     for (int i = 0; i < W; ++i) raw.w[i] = tab[lo * W + i];
     mt = __builtin_bit_cast(SmallMat, raw);
+  } else {
+    // a single matrix, descriptor in the kernel arguments: blockIdx.y is the slice of ROWS token rows
+    // (a table holds one entry per slice instead, and its launches have gridDim.y == 1)
+    const int slice = (int)blockIdx.y;
+    mt.x += (size_t)slice * ROWS * (size_t)mt.K;
+    if (mt.target) mt.target += (size_t)slice * ROWS * (size_t)mt.N;
+    if (mt.y) mt.y += (size_t)slice * ROWS * (size_t)mt.N;
+    mt.M = min(ROWS, mt.M - slice * ROWS);
+    mt.partial_base = slice * (int)gridDim.x;
   }
   // Pointers read out of a table are generic to the compiler; say that they are global memory, or
   // every access becomes a flat load with conservative waits on both memory counters.
@@ -602,7 +611,7 @@ static int small_m_class(const szo_linear_desc* d, int rblocks) {
 static int class_mode(int cls) { return cls / 2 == 0 ? SM_FAST : cls / 2 == 1 ? SM_LUT : SM_PLAIN; }
 static int class_rblocks(int cls) { return cls % 2 + 1; }
 
-static void small_m_launch(int mode, int r, int blocks, const SmallArgs& a, hipStream_t stream) {
+static void small_m_launch(int mode, int r, dim3 blocks, const SmallArgs& a, hipStream_t stream) {
   const size_t lds = small_lds_bytes(r);
   if (r == 1) {
     if (mode == SM_FAST) small_m_kernel<SM_FAST, 1><<<blocks, 256, lds, stream>>>(a);
@@ -673,36 +682,29 @@ static int set_small_attrs() {
 }
 
 // One matrix, descriptor passed in the kernel arguments (no device table needed).
-// Up to 64 token rows: one launch per slice of 16 rows (up to 16 tokens) or 32 rows (more).  In loss
-// mode slice i writes its partials at partial_*[i * small_m_blocks(d) ..], scaled by 1 / (M N) of the
-// whole matrix, so that their sum over all slices is the matrix's loss.
+// Up to 128 token rows: one launch whose second grid dimension counts the slices of 16 or 32 rows.  In
+// loss mode slice i writes its partials at partial_*[i * small_m_blocks(d) ..], scaled by 1 / (M N) of
+// the whole matrix, so that their sum over all slices is the matrix's loss.
 int small_m_launch_one(const szo_linear_desc* d, uint64_t seed, uint64_t step, float eps, int sign, bool loss_mode,
                        double* partial_plus, double* partial_minus, hipStream_t stream) {
   const int rc = set_small_attrs();
   if (rc != SZO_OK) return rc;
   const int blocks = small_m_blocks(d);
   const int rblocks = small_m_rblocks(d, small_m_wgs16(d));
-  const int rows = SM_ROWS * rblocks;
   const int slices = slices_of(d, rblocks);
-  for (int sl = 0; sl < slices; ++sl) {
-    SmallArgs a{};
-    fill_mat(a.one, d);                                     // loss_scale from the whole matrix
-    a.one.x += (size_t)sl * rows * (size_t)d->K;
-    if (a.one.target) a.one.target += (size_t)sl * rows * (size_t)d->N;
-    if (a.one.y) a.one.y += (size_t)sl * rows * (size_t)d->N;
-    a.one.M = (int)std::min<int64_t>(rows, d->M - (int64_t)sl * rows);
-    a.table = nullptr; a.n_mats = 1;
-    a.store_sign = sign; a.loss_mode = loss_mode ? 1 : 0;
-    a.seed = seed; a.step = step; a.eps = eps;
-    a.partial_plus = partial_plus ? partial_plus + (size_t)sl * blocks : nullptr;
-    a.partial_minus = partial_minus ? partial_minus + (size_t)sl * blocks : nullptr;
-    const int trc = timing_begin(stream);
-    if (trc != SZO_OK) return trc;
-    small_m_launch(small_m_mode(d), rblocks, blocks, a, stream);
-    SZO_LAUNCH_CHECK();
-    const int erc = timing_end(stream);
-    if (erc != SZO_OK) return erc;
-  }
+  SmallArgs a{};
+  fill_mat(a.one, d);                                       // whole matrix: the kernel offsets rows by slice
+  a.table = nullptr; a.n_mats = 1;
+  a.store_sign = sign; a.loss_mode = loss_mode ? 1 : 0;
+  a.seed = seed; a.step = step; a.eps = eps;
+  a.partial_plus = partial_plus;
+  a.partial_minus = partial_minus;
+  const int trc = timing_begin(stream);
+  if (trc != SZO_OK) return trc;
+  small_m_launch(small_m_mode(d), rblocks, dim3((unsigned)blocks, (unsigned)slices), a, stream);
+  SZO_LAUNCH_CHECK();
+  const int erc = timing_end(stream);
+  if (erc != SZO_OK) return erc;
   return SZO_OK;
 }
 
@@ -783,7 +785,7 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
     if (do_forward && class_blocks[cls] > 0) {
       a.table = tdev + first_entry; a.n_mats = class_entries[cls];
       if ((rc = timing_begin(stream)) != SZO_OK) return rc;
-      small_m_launch(class_mode(cls), class_rblocks(cls), class_blocks[cls], a, stream);
+      small_m_launch(class_mode(cls), class_rblocks(cls), dim3((unsigned)class_blocks[cls]), a, stream);
       SZO_LAUNCH_CHECK();
       if ((rc = timing_end(stream)) != SZO_OK) return rc;
     }
