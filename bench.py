@@ -39,6 +39,14 @@ def algorithmic_bytes_fwd(m, fused=True):
     return (m.N * m.K // 2 + side + 8 * m.nnz + 2 * m.M * m.K + (2 if fused else 4) * m.M * m.N)
 
 
+def few_token_path(M):
+    """The library's rule for the few-token path (slices of 16 / 32 token rows instead of 256-row tiles):
+    at most 15 slices of 32 rows, and fewer than 7.5 of them per row of tiles.  Only used to label the
+    kernel and to pick default step counts."""
+    slices, tile_rows = (M + 31) // 32, (M + 255) // 256
+    return slices <= 15 and 2 * slices < 15 * tile_rows
+
+
 def cpu_baseline(cfg, args, total_flops_per_step):
     """The oracle, as it stands, on a bounded sample of the same workload."""
     import numpy as np
@@ -202,7 +210,7 @@ def main():
                          "the non-uniform one, a table of 16 fp16 centroids per output row")
     ap.add_argument("--unfused-loss", action="store_true", help="write y and run the separate loss kernel")
     ap.add_argument("--tile-config", type=int, default=0, choices=[0, 1, 2, 3, 4],
-                    help="0: the library chooses (few-token path for M <= 128); 1 / 2: force the tiled kernel with "
+                    help="0: the library chooses (few-token path for small token counts); 1 / 2: force the tiled kernel with "
                          "128x128 / 256x256 workgroup tiles; 3: as 2, and always one grouped launch per step; 4: as 0 "
                          "with 32 token rows per pass of the few-token path wherever there are more than 16 (for comparisons)")
     ap.add_argument("--seed", type=int, default=2024)
@@ -251,7 +259,7 @@ def main():
     import torch
     from paper_2406_02913_amd import stack, synth, szo
 
-    few_default = (args.m or synth.WORKLOADS[args.workload]["M"]) <= 128
+    few_default = few_token_path(args.m or synth.WORKLOADS[args.workload]["M"])
     if args.steps is None:
         args.steps = 200 if few_default else 20
     if args.warmup is None:
@@ -306,7 +314,8 @@ def main():
     # ---- the dominant kernel alone: the library brackets every forward-kernel launch of a few more
     #      steps with events on the launch stream (szo_kernel_timing) ----
     fwd_flops = sum(2.0 * m.M * m.N * m.K for m in mats)
-    few = all(m.M <= 128 for m in mats) and dt == szo.TILE_F16 and args.tile_config in (0, 4)   # the library's few-token path
+    few = (all(few_token_path(m.M) and m.K % 128 == 0 for m in mats) and dt == szo.TILE_F16
+           and args.tile_config in (0, 4))                                                # the library's few-token path
     reps = args.steps if args.kernel_reps is None else max(1, args.kernel_reps)
     szo.szo_kernel_timing(True)
     for s in range(reps):

@@ -144,8 +144,9 @@ int szo_sparse_update(float* sp_val, const uint32_t* sp_idx, int64_t nnz, uint64
  * scalars: device double[3], overwritten with (L+, L-, g).  flags: bit 0 set = use the
  * loss-fusing forward and never write y (desc->y may then be NULL); large steps then run all
  * forwards (every layer, both signs) as one launch driven by a descriptor table that is staged in
- * the workspace, and steps with at most 128 tokens per layer stream the weights once per 16 or 32
- * token rows, each pass serving both signs.
+ * the workspace, and steps with few tokens per layer (up to 224, and 257 to 448: wherever slices of
+ * 32 token rows beat rows of 256-row tiles) stream the weights once per 16 or 32 token rows, each
+ * pass serving both signs.
  * descs: host array, read before the call returns.  Everything is enqueued on `stream`.  The
  * descriptor tables travel through a ring of four pinned host buffers (allocated on first use,
  * per host thread); a call waits on the host only if the copy of the call four steps earlier on
@@ -237,7 +238,7 @@ int szo_debug_zbar(uint64_t nnz_base, int64_t nnz, uint64_t seed, uint64_t step,
                    uint32_t* words_out, float* z_out, void* stream);
 
 /* Tuning/testing hook: which workgroup tile the forward uses.  0 = chosen from the shape
- * (default; also enables the few-token path for M <= 128), 1 = 128x128 outputs with 4 waves,
+ * (default; also enables the few-token path), 1 = 128x128 outputs with 4 waves,
  * 2 = 256x256 outputs with 8 waves, 3 = as 2 and szo_zo_step always launches all forwards of a
  * step as one grid (with 0 and 2 it does so only when the step has at least 192 tiles), 4 = as 0
  * and the few-token path takes 32 token rows per pass for every layer with more than 16 tokens

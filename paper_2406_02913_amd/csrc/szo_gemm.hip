@@ -1079,8 +1079,9 @@ int szo_zo_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t ste
   bool few = fuse && few_token_enabled() && n > 0 && n <= kMaxStepMatrices;
   for (int i = 0; few && i < n; ++i) few = small_m_step_eligible(&descs[i]);
   if (few) {
-    return small_m_step(descs, n, seed, step, eps, lr, (char*)workspace + kWorkspaceTableOffset,
-                        partial_area(workspace), scalars, true, true, s);
+    rc = small_m_step(descs, n, seed, step, eps, lr, (char*)workspace + kWorkspaceTableOffset,
+                      partial_area(workspace), scalars, true, true, s);
+    if (rc != SZO_EUNSUPPORTED) return rc;      // too many slices for the table: nothing was enqueued, take the tiled path
   }
   bool grouped = false;
   if (fuse) {

@@ -46,7 +46,7 @@ int reduce_step(const double* partials, int count, float eps, double* scalars, h
 
 // Few-token path (szo_smallm.hip): M <= 16, K % 128 == 0, fp16 tile.
 bool small_m_eligible(const szo_linear_desc* d);
-bool small_m_step_eligible(const szo_linear_desc* d);      // M <= 128: sliced into passes of 16 or 32 token rows
+bool small_m_step_eligible(const szo_linear_desc* d);      // few enough tokens: sliced into passes of 16 or 32 token rows
 int small_m_blocks(const szo_linear_desc* d);
 int small_m_slices(const szo_linear_desc* d);              // passes over the weights: 16 or 32 token rows each
 void small_m_force_wide(bool on);                          // testing hook: 32-row passes whatever the launch size

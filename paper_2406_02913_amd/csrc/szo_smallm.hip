@@ -624,12 +624,16 @@ static void small_m_launch(int mode, int r, dim3 blocks, const SmallArgs& a, hip
   }
 }
 
-// The step also takes matrices with up to 128 tokens: they run as slices of 16 or 32 token rows, each a
-// pass of its own over the weights.  On a 32-block 7B-shaped stack a 32-row pass takes 0.85-0.9 ms, so
-// four of them still beat the tiled kernel's 4.6 ms at 128 tokens (128x128 tiles, one grouped launch).
-constexpr int kSmallMaxTokens = 128;
+// The step also takes matrices with more tokens: they run as slices of 16 or 32 token rows, each a pass
+// of its own over the weights.  On a 32-block 7B-shaped stack a 32-row pass takes 0.8-0.9 ms and a row of
+// 256x256 tiles of the tiled kernel 6.4 ms, whatever part of its 256 rows is padding: slicing wins while
+// ceil(M/32) stays below 7.5 ceil(M/256), e.g. up to 224 tokens and from 257 to 448.  At most 15
+// slices, so that a 7B-shaped stack still fits the step's descriptor table.
+constexpr int kSmallMaxSlices = 15;
 bool small_m_step_eligible(const szo_linear_desc* d) {
-  if (d->M < 1 || d->M > kSmallMaxTokens) return false;
+  if (d->M < 1) return false;
+  const int64_t slices = (d->M + 31) / 32, tile_rows = (d->M + 255) / 256;
+  if (slices > kSmallMaxSlices || 2 * slices >= 15 * tile_rows) return false;
   szo_linear_desc one = *d;
   one.M = 1;
   return small_m_eligible(&one);

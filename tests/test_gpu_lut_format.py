@@ -82,7 +82,7 @@ def test_fused_loss_and_step_match_oracle():
     assert abs(acc.item() - LE) <= 5e-3 * LE
     sg = sigma_g([o1, o2])
     results = {}
-    for cfg in (0, 3):                            # per-matrix launches, then everything as one grouped launch
+    for cfg in (2, 3):                            # tiled kernel: per-matrix launches, then everything as one grouped launch
         szo.szo_set_tile_config(cfg)
         da, db = make_pair(48, 96, 320, 256, 128, 5e-3, nnz_base=0, fmt="lut")[1], make_pair(49, 200, 256, 512, 128, 2e-3, nnz_base=b2, fmt="lut")[1]
         scal = torch.zeros(3, dtype=torch.float64, device="cuda")
@@ -102,8 +102,8 @@ def test_fused_loss_and_step_match_oracle():
             assert np.linalg.norm(dv_gpu - dv_ref) <= 3e-2 * np.linalg.norm(dv_ref)
         results[cfg] = (got, da.sp_val.cpu().numpy(), db.sp_val.cpu().numpy())
     # same kernel body either way: bit-identical
-    assert results[0][0] == results[3][0]
-    assert np.array_equal(results[0][1], results[3][1]) and np.array_equal(results[0][2], results[3][2])
+    assert results[2][0] == results[3][0]
+    assert np.array_equal(results[2][1], results[3][1]) and np.array_equal(results[2][2], results[3][2])
 
 
 # (seed, M, N, K, density): the few-token kernel's table-format instantiation (M <= 64)

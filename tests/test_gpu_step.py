@@ -120,7 +120,7 @@ def test_bf16_tile_is_available_and_less_accurate_on_g():
 
 
 def test_kernel_timing_counts_forward_launches_only():
-    _, d = make_pair(3, 160, 256, 256, 32, 1e-3)        # more than 128 tokens: the tiled path
+    _, d = make_pair(3, 256, 256, 256, 32, 1e-3)        # a full row of 256-row tiles: the tiled path
     ws = szo.new_workspace()
     scal = torch.zeros(3, dtype=torch.float64, device="cuda")
     szo.szo_set_tile_config(0)
