@@ -209,7 +209,11 @@ def main():
                     help="4-bit format of the frozen part: uniform codes with group scales (the workloads' format) or "
                          "the non-uniform one, a table of 16 fp16 centroids per output row")
     ap.add_argument("--unfused-loss", action="store_true", help="write y and run the separate loss kernel")
-    ap.add_argument("--tile-config", type=int, default=0, choices=[0, 1, 2, 3, 4],
+    ap.add_argument("--one-dense-pass", action="store_true",
+                    help="SZO_STEP_ONE_DENSE_PASS: the slicing path of the few-token case at any token count (the dense "
+                         "product of a slice is computed once and serves both signs; valid because both forwards of a "
+                         "layer see the same x in this benchmark).  Not the default: see include/szo.h")
+    ap.add_argument("--tile-config", type=int, default=0, choices=[0, 1, 2, 3, 4, 5],
                     help="0: the library chooses (few-token path for small token counts); 1 / 2: force the tiled kernel with "
                          "128x128 / 256x256 workgroup tiles; 3: as 2, and always one grouped launch per step; 4: as 0 "
                          "with 32 token rows per pass of the few-token path wherever there are more than 16 (for comparisons)")
@@ -268,6 +272,8 @@ def main():
     torch.cuda.set_device(0)
     dt = szo.TILE_F16 if args.tile == "f16" else szo.TILE_BF16
     flags = 0 if args.unfused_loss else szo.STEP_FUSED_LOSS
+    if args.one_dense_pass and flags:
+        flags |= szo.STEP_ONE_DENSE_PASS
 
     t0 = time.perf_counter()
     count = [0]
@@ -314,8 +320,8 @@ def main():
     # ---- the dominant kernel alone: the library brackets every forward-kernel launch of a few more
     #      steps with events on the launch stream (szo_kernel_timing) ----
     fwd_flops = sum(2.0 * m.M * m.N * m.K for m in mats)
-    few = (all(few_token_path(m.M) and m.K % 128 == 0 for m in mats) and dt == szo.TILE_F16
-           and args.tile_config in (0, 4))                                                # the library's few-token path
+    few = (all((few_token_path(m.M) or args.one_dense_pass) and m.K % 128 == 0 for m in mats) and dt == szo.TILE_F16
+           and args.tile_config in (0, 4, 5) and bool(flags))                            # the library's few-token path
     reps = args.steps if args.kernel_reps is None else max(1, args.kernel_reps)
     szo.szo_kernel_timing(True)
     for s in range(reps):
@@ -376,6 +382,7 @@ def main():
                                + (f"int4 group {cfg['group']}, " if args.format == "uniform" else "4-bit table format, ") +
                                f"mask {cfg['density']:g} {cfg['mask']}, eps={eps}, lr={lr}",
                    "loss": "fused into the forward epilogue" if flags else "separate kernel",
+                   "dense_product": "once per slice of token rows, shared by both signs" if few else "once per sign",
                    "tile": args.tile, "format": args.format, "accumulate": "f32", "loss_accumulate": "f64"},
         "step_tflops": round(step_flops / (ms_per_step * 1e-3) / 1e12, 2),
         "step_frac_of_mfma_peak": round(step_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_MFMA_16BIT_TFLOPS, 4),

@@ -154,6 +154,13 @@ int szo_sparse_update(float* sp_val, const uint32_t* sp_idx, int64_t nnz, uint64
  * not meant to be captured into a HIP graph; the single-layer calls above are plain launches.
  * The workspace must not be shared with a call running concurrently on another stream. */
 #define SZO_STEP_FUSED_LOSS 1
+/* Bit 1 (with bit 0): take the slicing path of the few-token case at ANY token count.  Both forwards of
+ * a layer see the same x in this call, so y(+-) = x (dq + v)^T +- eps x z^T: the dense product is
+ * computed once per slice of up to 48 token rows and serves both signs, the sparse products are added.
+ * Same results as two forwards; half the dense work; the weights are streamed once per slice.  Not the
+ * default for many tokens because it does not carry over to a caller whose two forwards see different
+ * activations (every layer of a real model but the first), who calls szo_linear_fwd per sign instead. */
+#define SZO_STEP_ONE_DENSE_PASS 2
 int szo_zo_step(const szo_linear_desc* descs /* host */, int n, uint64_t seed, uint64_t step,
                 float eps, float lr, double* scalars, void* workspace, int flags, void* stream);
 
@@ -240,9 +247,10 @@ int szo_debug_zbar(uint64_t nnz_base, int64_t nnz, uint64_t seed, uint64_t step,
 /* Tuning/testing hook: which workgroup tile the forward uses.  0 = chosen from the shape
  * (default; also enables the few-token path), 1 = 128x128 outputs with 4 waves,
  * 2 = 256x256 outputs with 8 waves, 3 = as 2 and szo_zo_step always launches all forwards of a
- * step as one grid (with 0 and 2 it does so only when the step has at least 192 tiles), 4 = as 0
- * and the few-token path takes 32 token rows per pass for every layer with more than 16 tokens
- * (by default only in launches large enough to fill the chip more than twice over).
+ * step as one grid (with 0 and 2 it does so only when the step has at least 192 tiles), 4 / 5 = as 0
+ * and the few-token path takes 32 / 48 token rows per pass for every layer with more than 16 tokens
+ * (by default it chooses 16, 32 or 48, the larger ones only in launches that fill the chip more than
+ * twice over).
  * Process-wide, not thread-safe; results do not depend on it beyond fp32 summation order. */
 int szo_set_tile_config(int config);
 

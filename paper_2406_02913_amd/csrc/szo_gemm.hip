@@ -797,8 +797,8 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_table_kerne
 // ---- host side -----------------------------------------------------------------------------
 
 static int g_tile_config = 0;      // 0 = choose by shape, 1 = 128x128 (4 waves), 2 = 256x256 (8 waves), 3 = 2 + always group the step,
-                                   // 4 = as 0 with the few-token path's 32-row passes forced (see small_m_force_wide)
-static bool few_token_enabled() { return g_tile_config == 0 || g_tile_config == 4; }
+                                   // 4, 5 = as 0 with the few-token path's 32- / 48-row passes forced (see small_m_force_rblocks)
+static bool few_token_enabled() { return g_tile_config == 0 || g_tile_config >= 4; }
 
 static int ilog2_exact(int v) {
   int s = 0;
@@ -859,7 +859,7 @@ static int launch(FwdParams& p, hipStream_t stream) {
 
 // Which workgroup tile a shape runs with, and how many workgroups (= loss partials) that makes.
 static int plan_tiles(int M, int N, int format, int* blocks_out) {
-  int cfg = g_tile_config == 4 ? 0 : g_tile_config;
+  int cfg = g_tile_config >= 4 ? 0 : g_tile_config;
   if (format == SZO_FORMAT_LUT) cfg = 2;          // the table format exists for the 256x256 tile only
   if (cfg == 0) {
     const int64_t big_blocks = (int64_t)((M + 255) / 256) * ((N + 255) / 256);
@@ -963,7 +963,7 @@ static int grouped_forwards(const szo_linear_desc* descs, int n, uint64_t seed, 
   if (g_tile_config == 1) return SZO_EUNSUPPORTED;
   int64_t max_m = 0;
   for (int i = 0; i < n; ++i) max_m = std::max<int64_t>(max_m, descs[i].N > 0 ? descs[i].M : 0);
-  const bool auto_tiles = g_tile_config == 0 || g_tile_config == 4;
+  const bool auto_tiles = g_tile_config == 0 || g_tile_config >= 4;
   const int tile = (auto_tiles && n > 0 && descs[0].format == SZO_FORMAT_UNIFORM && max_m <= 128) ? 128 : 256;
   int64_t T = 0;
   int live = 0;
@@ -1019,9 +1019,9 @@ using namespace szo;
 extern "C" {
 
 int szo_set_tile_config(int config) {
-  if (config < 0 || config > 4) return SZO_EINVAL;
+  if (config < 0 || config > 5) return SZO_EINVAL;
   g_tile_config = config;
-  small_m_force_wide(config == 4);
+  small_m_force_rblocks(config == 4 ? 2 : config == 5 ? 3 : 0);
   return SZO_OK;
 }
 
@@ -1077,7 +1077,8 @@ int szo_zo_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t ste
   int rc;
   // Few-token stacks: one pass over the weights serves both forwards of the step.
   bool few = fuse && few_token_enabled() && n > 0 && n <= kMaxStepMatrices;
-  for (int i = 0; few && i < n; ++i) few = small_m_step_eligible(&descs[i]);
+  const bool one_pass = flags & SZO_STEP_ONE_DENSE_PASS;     // the caller asks for the slicing path at any token count
+  for (int i = 0; few && i < n; ++i) few = one_pass ? small_m_shape_eligible(&descs[i]) : small_m_step_eligible(&descs[i]);
   if (few) {
     rc = small_m_step(descs, n, seed, step, eps, lr, (char*)workspace + kWorkspaceTableOffset,
                       partial_area(workspace), scalars, true, true, s);

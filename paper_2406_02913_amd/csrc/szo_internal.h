@@ -49,7 +49,8 @@ bool small_m_eligible(const szo_linear_desc* d);
 bool small_m_step_eligible(const szo_linear_desc* d);      // few enough tokens: sliced into passes of 16 or 32 token rows
 int small_m_blocks(const szo_linear_desc* d);
 int small_m_slices(const szo_linear_desc* d);              // passes over the weights: 16 or 32 token rows each
-void small_m_force_wide(bool on);                          // testing hook: 32-row passes whatever the launch size
+bool small_m_shape_eligible(const szo_linear_desc* d);     // the same without looking at the token count
+void small_m_force_rblocks(int r);                         // testing hook: 0 = choose; 2, 3 = 32 / 48 token rows per pass wherever M > 16
 size_t small_m_table_bytes(int n);
 int small_m_launch_one(const szo_linear_desc* d, uint64_t seed, uint64_t step, float eps, int sign, bool loss_mode,
                        double* partial_plus, double* partial_minus, hipStream_t stream);

@@ -82,6 +82,7 @@ struct SmallArgs {
   const SmallMat* table;    // device table of n_mats matrices, or null: use `one`
   SmallMat one;
   int n_mats;
+  int slices;               // slices of token rows per strip in this launch (the longest matrix's count)
   int store_sign;           // store mode: which forward to write (-1, 0, +1); loss mode: unused
   int loss_mode;            // 1: write loss partials for both signs, 0: store y
   uint64_t seed, step;
@@ -165,12 +166,14 @@ __device__ __forceinline__ half8_t sm_lut_word(uint32_t q, const uint32_t (&T)[8
 // MODE 2 (table format): dq = lut[row][code]; a lane keeps the tables of its four rows in registers
 // (32 of them; it needs neither scales nor the constants of the un-centred codes, so it still fits
 // the register budget of three workgroups per CU).
-// R = 16-row blocks of tokens per pass (1 or 2).  With R = 2 every dequantised operand is multiplied with
-// two blocks of token rows, so that matrices with 17..128 tokens stream their weights half as often;
-// it costs 48 more registers (accumulators and activation operands), i.e. two workgroups per CU.
+// R = 16-row blocks of tokens per pass (1, 2 or 3).  With R > 1 every dequantised operand is multiplied
+// with R blocks of token rows, so that matrices with more than 16 tokens stream their weights less
+// often; each block costs 48 more registers (accumulators and activation operands): 196 and 253
+// registers, i.e. two workgroups per CU instead of three.
 constexpr int SM_PLAIN = 0, SM_FAST = 1, SM_LUT = 2;
 template <int MODE, int R>
 __global__ void __launch_bounds__(256, R == 1 ? SM_MIN_BLOCKS : 2) small_m_kernel(SmallArgs a) {
+  static_assert(R >= 1 && R <= 3, "one to three blocks of 16 token rows");
   constexpr bool FAST = MODE == SM_FAST, LUT = MODE == SM_LUT;
   constexpr int ROWS = SM_ROWS * R;                          // token rows of one pass
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
@@ -189,7 +192,11 @@ __global__ void __launch_bounds__(256, R == 1 ? SM_MIN_BLOCKS : 2) small_m_kerne
     const int xcd = bid & 7, i = bid >> 3;
     bid = (((i >> 3) << 3) + xcd) * 8 + (i & 7);
   }
-  // ---- which matrix, which 256-column strip ----
+  // ---- which slice of token rows, which matrix, which 256-column strip ----
+  // Consecutive (remapped) ids are the slices of one strip: they read the same weights, so they should
+  // run at the same time on the same XCD and share them through its L2.
+  const int slice = bid % a.slices;
+  bid /= a.slices;
   // The table entry is read through the constant address space (scalar loads: the table is written
   // before the launch and never during it), so that its fields live in scalar registers like the
   // kernel arguments do; read through a generic pointer they would occupy ~30 vector registers.
@@ -207,16 +214,14 @@ __global__ void __launch_bounds__(256, R == 1 ? SM_MIN_BLOCKS : 2) small_m_kerne
 #pragma unroll
     for (int i = 0; i < W; ++i) raw.w[i] = tab[lo * W + i];
     mt = __builtin_bit_cast(SmallMat, raw);
-  } else {
-    // a single matrix, descriptor in the kernel arguments: blockIdx.y is the slice of ROWS token rows
-    // (a table holds one entry per slice instead, and its launches have gridDim.y == 1)
-    const int slice = (int)blockIdx.y;
-    mt.x += (size_t)slice * ROWS * (size_t)mt.K;
-    if (mt.target) mt.target += (size_t)slice * ROWS * (size_t)mt.N;
-    if (mt.y) mt.y += (size_t)slice * ROWS * (size_t)mt.N;
-    mt.M = min(ROWS, mt.M - slice * ROWS);
-    mt.partial_base = slice * (int)gridDim.x;
   }
+  // a launch has as many slices of ROWS token rows per strip as its longest matrix needs
+  if (slice * ROWS >= mt.M) return;
+  mt.x += (size_t)slice * ROWS * (size_t)mt.K;
+  if (mt.target) mt.target += (size_t)slice * ROWS * (size_t)mt.N;
+  if (mt.y) mt.y += (size_t)slice * ROWS * (size_t)mt.N;
+  mt.M = min(ROWS, mt.M - slice * ROWS);
+  mt.partial_base += slice * ((mt.N + SM_BN - 1) / SM_BN);      // slice i of a matrix: partials [i * strips ..)
   // Pointers read out of a table are generic to the compiler; say that they are global memory, or
   // every access becomes a flat load with conservative waits on both memory counters.
 #define SZO_GLOBAL(T, p) ((const T __attribute__((address_space(1)))*)(p))
@@ -584,10 +589,17 @@ static size_t small_lds_bytes(int r) {
 // that fits the chip in one go (measured: a single decoder block) is faster as more, smaller passes side
 // by side.  `launch_wgs16` = workgroups the whole launch would have with 16 rows per pass.
 constexpr int64_t kSmallWideWorkgroups = 1536;              // two rounds of the 768 workgroups the chip holds
-static bool g_force_wide = false;
-void small_m_force_wide(bool on) { g_force_wide = on; }
+static int g_force_rblocks = 0;                             // testing hook: 2 or 3 = that many wherever M > 16
+void small_m_force_rblocks(int r) { g_force_rblocks = r; }
 static int small_m_rblocks(const szo_linear_desc* d, int64_t launch_wgs16) {
-  return (d->M > SM_ROWS && (g_force_wide || launch_wgs16 > kSmallWideWorkgroups)) ? 2 : 1;
+  if (d->M <= SM_ROWS) return 1;
+  if (g_force_rblocks) return g_force_rblocks;
+  if (launch_wgs16 <= kSmallWideWorkgroups) return 1;
+  // fewest passes weighted by what a pass costs (measured on a 32-block 7B stack: 0.62, 0.79, 1.0 ms)
+  const int64_t cost[3] = {62 * ((d->M + 15) / 16), 79 * ((d->M + 31) / 32), 100 * ((d->M + 47) / 48)};
+  int best = 0;
+  for (int r = 1; r < 3; ++r) if (cost[r] < cost[best]) best = r;
+  return best + 1;
 }
 
 bool small_m_eligible(const szo_linear_desc* d) {
@@ -603,13 +615,13 @@ static int small_m_mode(const szo_linear_desc* d) {
   return d->group == 128 ? SM_FAST : SM_PLAIN;
 }
 // position of an instantiation (mode, row blocks) in a step's table and launch order
-constexpr int kSmallClasses = 6;
+constexpr int kSmallClasses = 9;
 static int small_m_class(const szo_linear_desc* d, int rblocks) {
   const int m = small_m_mode(d);
-  return 2 * (m == SM_FAST ? 0 : m == SM_LUT ? 1 : 2) + (rblocks - 1);
+  return 3 * (m == SM_FAST ? 0 : m == SM_LUT ? 1 : 2) + (rblocks - 1);
 }
-static int class_mode(int cls) { return cls / 2 == 0 ? SM_FAST : cls / 2 == 1 ? SM_LUT : SM_PLAIN; }
-static int class_rblocks(int cls) { return cls % 2 + 1; }
+static int class_mode(int cls) { return cls / 3 == 0 ? SM_FAST : cls / 3 == 1 ? SM_LUT : SM_PLAIN; }
+static int class_rblocks(int cls) { return cls % 3 + 1; }
 
 static void small_m_launch(int mode, int r, dim3 blocks, const SmallArgs& a, hipStream_t stream) {
   const size_t lds = small_lds_bytes(r);
@@ -617,26 +629,33 @@ static void small_m_launch(int mode, int r, dim3 blocks, const SmallArgs& a, hip
     if (mode == SM_FAST) small_m_kernel<SM_FAST, 1><<<blocks, 256, lds, stream>>>(a);
     else if (mode == SM_LUT) small_m_kernel<SM_LUT, 1><<<blocks, 256, lds, stream>>>(a);
     else small_m_kernel<SM_PLAIN, 1><<<blocks, 256, lds, stream>>>(a);
-  } else {
+  } else if (r == 2) {
     if (mode == SM_FAST) small_m_kernel<SM_FAST, 2><<<blocks, 256, lds, stream>>>(a);
     else if (mode == SM_LUT) small_m_kernel<SM_LUT, 2><<<blocks, 256, lds, stream>>>(a);
     else small_m_kernel<SM_PLAIN, 2><<<blocks, 256, lds, stream>>>(a);
+  } else {
+    if (mode == SM_FAST) small_m_kernel<SM_FAST, 3><<<blocks, 256, lds, stream>>>(a);
+    else if (mode == SM_LUT) small_m_kernel<SM_LUT, 3><<<blocks, 256, lds, stream>>>(a);
+    else small_m_kernel<SM_PLAIN, 3><<<blocks, 256, lds, stream>>>(a);
   }
 }
 
 // The step also takes matrices with more tokens: they run as slices of 16 or 32 token rows, each a pass
 // of its own over the weights.  On a 32-block 7B-shaped stack a 32-row pass takes 0.8-0.9 ms and a row of
 // 256x256 tiles of the tiled kernel 6.4 ms, whatever part of its 256 rows is padding: slicing wins while
-// ceil(M/32) stays below 7.5 ceil(M/256), e.g. up to 224 tokens and from 257 to 448.  At most 15
-// slices, so that a 7B-shaped stack still fits the step's descriptor table.
+// ceil(M/32) stays below 7.5 ceil(M/256), e.g. up to 224 tokens and from 257 to 448; beyond 15 such
+// slices the tiled kernel is the default (SZO_STEP_ONE_DENSE_PASS overrides that).
 constexpr int kSmallMaxSlices = 15;
-bool small_m_step_eligible(const szo_linear_desc* d) {
+bool small_m_shape_eligible(const szo_linear_desc* d) {
   if (d->M < 1) return false;
-  const int64_t slices = (d->M + 31) / 32, tile_rows = (d->M + 255) / 256;
-  if (slices > kSmallMaxSlices || 2 * slices >= 15 * tile_rows) return false;
   szo_linear_desc one = *d;
   one.M = 1;
   return small_m_eligible(&one);
+}
+bool small_m_step_eligible(const szo_linear_desc* d) {
+  const int64_t slices = (d->M + 31) / 32, tile_rows = (d->M + 255) / 256;
+  if (slices > kSmallMaxSlices || 2 * slices >= 15 * tile_rows) return false;
+  return small_m_shape_eligible(d);
 }
 
 int small_m_blocks(const szo_linear_desc* d) { return (int)((d->N + SM_BN - 1) / SM_BN); }
@@ -680,15 +699,18 @@ static int set_small_attrs() {
     SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_FAST, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds_bytes(2)));
     SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_PLAIN, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds_bytes(2)));
     SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_LUT, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds_bytes(2)));
+    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_FAST, 3>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds_bytes(3)));
+    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_PLAIN, 3>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds_bytes(3)));
+    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_LUT, 3>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds_bytes(3)));
     attr_set = true;
   }
   return SZO_OK;
 }
 
 // One matrix, descriptor passed in the kernel arguments (no device table needed).
-// Up to 128 token rows: one launch whose second grid dimension counts the slices of 16 or 32 rows.  In
-// loss mode slice i writes its partials at partial_*[i * small_m_blocks(d) ..], scaled by 1 / (M N) of
-// the whole matrix, so that their sum over all slices is the matrix's loss.
+// One launch of strips x slices workgroups.  In loss mode slice i writes its partials at
+// partial_*[i * small_m_blocks(d) ..], scaled by 1 / (M N) of the whole matrix, so that their sum over
+// all slices is the matrix's loss.
 int small_m_launch_one(const szo_linear_desc* d, uint64_t seed, uint64_t step, float eps, int sign, bool loss_mode,
                        double* partial_plus, double* partial_minus, hipStream_t stream) {
   const int rc = set_small_attrs();
@@ -705,7 +727,8 @@ int small_m_launch_one(const szo_linear_desc* d, uint64_t seed, uint64_t step, f
   a.partial_minus = partial_minus;
   const int trc = timing_begin(stream);
   if (trc != SZO_OK) return trc;
-  small_m_launch(small_m_mode(d), rblocks, dim3((unsigned)blocks, (unsigned)slices), a, stream);
+  a.slices = slices;
+  small_m_launch(small_m_mode(d), rblocks, dim3((unsigned)(blocks * slices)), a, stream);
   SZO_LAUNCH_CHECK();
   const int erc = timing_end(stream);
   if (erc != SZO_OK) return erc;
@@ -726,13 +749,11 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
   int64_t wgs16 = 0;
   for (int i = 0; i < n; ++i) wgs16 += small_m_wgs16(&descs[i]);
   auto rblocks_of = [&](const szo_linear_desc* d) { return small_m_rblocks(d, wgs16); };
-  int max_entries = 0;
-  for (int i = 0; i < n; ++i) max_entries += do_forward ? slices_of(&descs[i], rblocks_of(&descs[i])) : 1;
-  if (small_m_table_bytes(max_entries) > kTableBytesPerMatrix * (size_t)kMaxStepMatrices) return SZO_EUNSUPPORTED;
+  if (small_m_table_bytes(n) > kTableBytesPerMatrix * (size_t)kMaxStepMatrices) return SZO_EUNSUPPORTED;
   static thread_local std::vector<SmallMat> host_table;
-  host_table.resize((size_t)max_entries);
+  host_table.resize((size_t)std::max(n, 1));
   SmallMat* const host = host_table.data();
-  // order: by instantiation (fast, table format, plain; 16 rows before 32), inside each by K descending
+  // order: by instantiation (fast, table format, plain; fewer rows per pass first), inside each by K descending
   int order[kMaxStepMatrices];
   for (int i = 0; i < n; ++i) order[i] = i;
   auto sort_key = [&](int o) {
@@ -749,54 +770,50 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
     }
     order[j + 1] = o;
   }
-  int class_entries[kSmallClasses] = {}, class_blocks[kSmallClasses] = {}, partials = 0, entries = 0;
-  int64_t quads = 0;
+  // One table entry per matrix; a launch has (strips of its matrices) x (slices of its longest matrix)
+  // workgroups (those past a matrix's last slice return at once), and slice i of a matrix writes its
+  // loss partials behind those of slice i - 1.
+  int class_entries[kSmallClasses] = {}, class_blocks[kSmallClasses] = {}, class_slices[kSmallClasses] = {}, entries = 0;
+  int64_t quads = 0, partials = 0;
   for (int r = 0; r < n; ++r) {
     const szo_linear_desc* d = &descs[order[r]];
     const int rblocks = rblocks_of(d);
     const int cls = small_m_class(d, rblocks);
-    // forward: one table entry per slice of 16 or 32 token rows; update only: one entry per matrix
-    const int rows = SM_ROWS * rblocks;
-    const int slices = do_forward ? slices_of(d, rblocks) : 1;
-    for (int sl = 0; sl < slices; ++sl) {
-      SmallMat& m = host[entries++];
-      fill_mat(m, d);
-      if (do_forward) {
-        m.x += (size_t)sl * rows * (size_t)d->K;
-        m.target += (size_t)sl * rows * (size_t)d->N;
-        m.M = (int)std::min<int64_t>(rows, d->M - (int64_t)sl * rows);
-      }
-      m.first_block = class_blocks[cls];
-      m.partial_base = partials;
-      m.first_quad = quads;          // every slice of a matrix: the update finds the last one, once
-      const int b = small_m_blocks(d);
-      class_blocks[cls] += b;
-      ++class_entries[cls];
-      partials += b;
-    }
+    const int slices = slices_of(d, rblocks), b = small_m_blocks(d);
+    SmallMat& m = host[entries++];
+    fill_mat(m, d);
+    m.first_block = class_blocks[cls];
+    m.partial_base = (int)partials;
+    m.first_quad = quads;
+    class_blocks[cls] += b;
+    class_slices[cls] = std::max(class_slices[cls], slices);
+    ++class_entries[cls];
+    partials += (int64_t)b * slices;
     quads += ((int64_t)d->nnz + 3) / 4;
+    if (do_forward && 2 * partials > kMaxLossPartials) return SZO_EUNSUPPORTED;
+    if ((int64_t)class_blocks[cls] * class_slices[cls] > 0x7FFFFFFF) return SZO_EUNSUPPORTED;
   }
-  if (do_forward && 2 * (int64_t)partials > kMaxLossPartials) return SZO_EUNSUPPORTED;
   rc = stage_table(host, sizeof(SmallMat) * (size_t)entries, table_dev, stream);
   if (rc != SZO_OK) return rc;
   SmallArgs a{};
   a.store_sign = 1; a.loss_mode = 1;
   a.seed = seed; a.step = step; a.eps = eps;
-  a.partial_plus = partial_plus; a.partial_minus = partial_plus + partials;
+  a.partial_plus = partial_plus; a.partial_minus = do_forward ? partial_plus + partials : nullptr;
   const SmallMat* tdev = (const SmallMat*)table_dev;
   int first_entry = 0;
   for (int cls = 0; cls < kSmallClasses; ++cls) {
     if (do_forward && class_blocks[cls] > 0) {
       a.table = tdev + first_entry; a.n_mats = class_entries[cls];
+      a.slices = class_slices[cls];
       if ((rc = timing_begin(stream)) != SZO_OK) return rc;
-      small_m_launch(class_mode(cls), class_rblocks(cls), dim3((unsigned)class_blocks[cls]), a, stream);
+      small_m_launch(class_mode(cls), class_rblocks(cls), dim3((unsigned)(class_blocks[cls] * class_slices[cls])), a, stream);
       SZO_LAUNCH_CHECK();
       if ((rc = timing_end(stream)) != SZO_OK) return rc;
     }
     first_entry += class_entries[cls];
   }
   if (do_forward) {
-    rc = reduce_step(partial_plus, partials, eps, scalars, stream);
+    rc = reduce_step(partial_plus, (int)partials, eps, scalars, stream);
     if (rc != SZO_OK) return rc;
   }
   if (do_update && quads > 0) {

@@ -17,6 +17,7 @@ OK, EINVAL, EUNSUPPORTED, ELAUNCH = 0, -1, -2, -3
 TILE_F16, TILE_BF16 = 0, 1
 TILE_ROWS, TILE_COLS = 64, 64
 STEP_FUSED_LOSS = 1
+STEP_ONE_DENSE_PASS = 2
 FORMAT_UNIFORM, FORMAT_LUT = 0, 1
 
 if not os.path.exists(LIB_PATH):

@@ -33,8 +33,8 @@ SHAPES = [
 ]
 
 
-# configuration 4: 32 token rows per pass wherever there are more than 16 (otherwise only in large launches)
-@pytest.mark.parametrize("shape,cfg", [(sh, 0) for sh in SHAPES] + [(sh, 4) for sh in SHAPES if sh[1] > 16])
+# configurations 4 and 5: 32 / 48 token rows per pass wherever there are more than 16 (otherwise only in large launches)
+@pytest.mark.parametrize("shape,cfg", [(sh, 0) for sh in SHAPES] + [(sh, c) for sh in SHAPES if sh[1] > 16 for c in (4, 5)])
 def test_few_token_forward_matches_oracle(shape, cfg):
     s, M, N, K, G, dens = shape
     szo.szo_set_tile_config(cfg)
@@ -171,11 +171,11 @@ def test_one_full_size_block_at_16_tokens_two_steps():
         assert np.linalg.norm(dv_gpu - dv_ref) <= 3e-2 * np.linalg.norm(dv_ref) + 1e-12
 
 
-@pytest.mark.parametrize("cfg", [0, 4])
+@pytest.mark.parametrize("cfg", [0, 4, 5])
 def test_step_with_up_to_64_tokens_runs_as_slices(cfg):
-    """17..64 tokens: the step streams the weights once per slice of 16 token rows, or of 32 in launches
-    that are large (configuration 4 forces that); matrices of different token counts may share a step,
-    and the sparse values are updated exactly once."""
+    """17..64 tokens: the step streams the weights once per slice of 16 token rows, or of 32 / 48 in
+    launches that are large (configurations 4 / 5 force that); matrices of different token counts may
+    share a step, and the sparse values are updated exactly once."""
     szo.szo_set_tile_config(cfg)
     o1, d1 = make_pair(51, 64, 320, 512, 128, 2e-3, nnz_base=0)
     b2 = (o1.sp_idx.size + 3) // 4 * 4

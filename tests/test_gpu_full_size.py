@@ -112,13 +112,13 @@ def test_mistral_up_projection_8192_tokens_sampled(density):
     assert rel_fro(y, _sampled_oracle(o, z, -1, eps, rows_n, rows_m, "D", K)) <= 2e-5
 
 
-@pytest.mark.parametrize("M,cfg", [(1, 0), (16, 0), (64, 0), (64, 4)])
+@pytest.mark.parametrize("M,cfg", [(1, 0), (16, 0), (64, 0), (64, 4), (64, 5)])
 def test_opt_ffn_projections_decode_token_counts(M, cfg):
     """OPT-6.7B's two FFN matrices (16384 x 4096 and 4096 x 16384) at 1 / 16 / 64 tokens: one fused step
     on the few-token path against the oracle (losses, g, updated values)."""
     from oracle import zo as ozo
     from helpers import clone, sigma_g
-    szo.szo_set_tile_config(cfg)                     # 4: the 64 tokens run as two passes of 32 rows, as in a full stack
+    szo.szo_set_tile_config(cfg)                     # 4 / 5: the 64 tokens run as two passes of 32 / 48 rows, as in a full stack
     o1, d1 = make_pair(9, M, 16384, 4096, 128, 1e-3, nnz_base=0)
     base = (o1.sp_idx.size + 3) // 4 * 4
     o2, d2 = make_pair(10, M, 4096, 16384, 128, 1e-3, nnz_base=base)

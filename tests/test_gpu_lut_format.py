@@ -117,8 +117,8 @@ FEW = [
 ]
 
 
-# configuration 4: 32 token rows per pass wherever there are more than 16 (otherwise only in large launches)
-@pytest.mark.parametrize("shape,cfg", [(sh, 0) for sh in FEW] + [(sh, 4) for sh in FEW if sh[1] > 16])
+# configurations 4 and 5: 32 / 48 token rows per pass wherever there are more than 16 (otherwise only in large launches)
+@pytest.mark.parametrize("shape,cfg", [(sh, 0) for sh in FEW] + [(sh, c) for sh in FEW if sh[1] > 16 for c in (4, 5)])
 def test_few_token_forward_matches_oracle(shape, cfg):
     s, M, N, K, dens = shape
     szo.szo_set_tile_config(cfg)
@@ -139,7 +139,7 @@ def test_few_token_forward_matches_oracle(shape, cfg):
         assert rel_fro(tiled[sign], y2) <= 2e-4 and not np.array_equal(tiled[sign], y2)
 
 
-@pytest.mark.parametrize("cfg", [0, 4])
+@pytest.mark.parametrize("cfg", [0, 4, 5])
 def test_few_token_step_with_all_three_instantiations(cfg):
     # one step over a table-format layer, a group-128 layer and a group-64 layer: three launches, one g
     szo.szo_set_tile_config(cfg)
@@ -170,7 +170,7 @@ def test_few_token_step_with_all_three_instantiations(cfg):
         assert np.linalg.norm(dv_gpu - dv_ref) <= 3e-2 * np.linalg.norm(dv_ref)
 
 
-@pytest.mark.parametrize("cfg", [0, 4])
+@pytest.mark.parametrize("cfg", [0, 4, 5])
 def test_few_token_single_calls_with_loss(cfg):
     szo.szo_set_tile_config(cfg)
     o, d = make_pair(70, 40, 256, 512, 128, 1e-2, fmt="lut")

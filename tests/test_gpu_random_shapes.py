@@ -24,7 +24,7 @@ def _cases(n, seed):
         N = int(rng.choice([1, 5, 63, 64, 65, 130, 255, 256, 257, 300, 511, 640]))
         dens = float(rng.choice([0.0, 1e-3, 1e-2, 5e-2]))
         kind = "heavy_tail" if (N >= 100 and dens <= 1e-2 and rng.random() < 0.5) else "uniform"   # hot rows hold k/2
-        cfg = int(rng.choice([0, 1, 2, 3, 4]))
+        cfg = int(rng.choice([0, 1, 2, 3, 4, 5]))
         dt = "bf16" if (fmt == "uniform" and rng.random() < 0.25) else "f16"
         out.append((1000 + i, M, N, K, group, dens, kind, fmt, cfg, dt))
     return out

@@ -259,3 +259,33 @@ def test_grouped_launch_with_128_row_tiles_for_steps_of_at_most_128_tokens():
         assert np.array_equal(a, b)
     for a, b in zip(v1, v0):
         assert np.array_equal(a, b)
+
+
+def test_one_dense_pass_flag_takes_the_slicing_path_at_any_token_count():
+    """512 tokens run on the tiled kernel by default (two full forwards per layer); with
+    SZO_STEP_ONE_DENSE_PASS the same step runs as slices whose dense product serves both signs.  Two
+    different kernels and associations, the same losses, g and update; both agree with the oracle."""
+    o1, d1 = make_pair(81, 512, 320, 512, 128, 2e-3, nnz_base=0)
+    b2 = (o1.sp_idx.size + 3) // 4 * 4
+    o2, d2 = make_pair(82, 300, 256, 256, 64, 5e-3, nnz_base=b2)
+    seed, eps, lr = 17, 1e-3, 1e-3
+    sg = sigma_g([o1, o2])
+    outs = {}
+    for flags in (szo.STEP_FUSED_LOSS, szo.STEP_FUSED_LOSS | szo.STEP_ONE_DENSE_PASS):
+        da, db = make_pair(81, 512, 320, 512, 128, 2e-3, nnz_base=0)[1], make_pair(82, 300, 256, 256, 64, 5e-3, nnz_base=b2)[1]
+        ws = szo.new_workspace()
+        scal = torch.zeros(3, dtype=torch.float64, device="cuda")
+        ref = [clone(o1), clone(o2)]
+        szo.szo_kernel_timing(True)
+        szo.szo_zo_step([da.desc(with_y=False), db.desc(with_y=False)], seed, 0, eps, lr, scal, ws, flags)
+        _, launches = szo.szo_kernel_timing_read()
+        szo.szo_kernel_timing(False)
+        lp, lm, g = scal.cpu().numpy()
+        r = ozo.zo_step(ref, seed, 0, eps, lr)
+        assert abs(lp - r["loss_plus"]) <= 1e-4 * r["loss_plus"] and abs(lm - r["loss_minus"]) <= 1e-4 * r["loss_minus"]
+        assert abs(g - r["g"]) <= 1e-2 * max(abs(r["g"]), sg)
+        outs[flags] = (launches, g, da.sp_val.cpu().numpy(), db.sp_val.cpu().numpy())
+    assert outs[szo.STEP_FUSED_LOSS][0] == 4                          # two matrices, two signs, tiled kernel
+    assert outs[szo.STEP_FUSED_LOSS | szo.STEP_ONE_DENSE_PASS][0] == 2  # one launch per instantiation (group 128, group 64)
+    ga, gb = outs[szo.STEP_FUSED_LOSS][1], outs[szo.STEP_FUSED_LOSS | szo.STEP_ONE_DENSE_PASS][1]
+    assert abs(ga - gb) <= 2e-2 * max(abs(ga), sg)
