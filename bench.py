@@ -39,11 +39,12 @@ def algorithmic_bytes_fwd(m, fused=True):
     return (m.N * m.K // 2 + side + 8 * m.nnz + 2 * m.M * m.K + (2 if fused else 4) * m.M * m.N)
 
 
-def few_token_path(M):
+def few_token_path(M, two_sets=False):
     """The library's rule for the few-token path (slices of 16 / 32 token rows instead of 256-row tiles):
-    at most 15 slices of 32 rows, and fewer than 7.5 of them per row of tiles.  Only used to label the
-    kernel and to pick default step counts."""
-    slices, tile_rows = (M + 31) // 32, (M + 255) // 256
+    at most 15 slices of 32 rows (16 with two activation sets), and fewer than 7.5 of them per row of
+    tiles.  Only used to label the kernel and to pick default step counts."""
+    rows = 16 if two_sets else 32
+    slices, tile_rows = (M + rows - 1) // rows, (M + 255) // 256
     return slices <= 15 and 2 * slices < 15 * tile_rows
 
 
@@ -209,6 +210,9 @@ def main():
                     help="4-bit format of the frozen part: uniform codes with group scales (the workloads' format) or "
                          "the non-uniform one, a table of 16 fp16 centroids per output row")
     ap.add_argument("--unfused-loss", action="store_true", help="write y and run the separate loss kernel")
+    ap.add_argument("--two-activation-sets", action="store_true",
+                    help="give every layer a second, different set of activations for its -eps forward (desc.x_minus), "
+                         "as inside a model; the few-token path then still reads the weights once for both signs")
     ap.add_argument("--one-dense-pass", action="store_true",
                     help="SZO_STEP_ONE_DENSE_PASS: the slicing path of the few-token case at any token count (the dense "
                          "product of a slice is computed once and serves both signs; valid because both forwards of a "
@@ -263,7 +267,7 @@ def main():
     import torch
     from paper_2406_02913_amd import stack, synth, szo
 
-    few_default = few_token_path(args.m or synth.WORKLOADS[args.workload]["M"])
+    few_default = few_token_path(args.m or synth.WORKLOADS[args.workload]["M"], args.two_activation_sets)
     if args.steps is None:
         args.steps = 200 if few_default else 20
     if args.warmup is None:
@@ -291,6 +295,10 @@ def main():
     log(f"[bench] {len(mats)} matrices resident after {time.perf_counter() - t0:.1f} s, "
         f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB")
 
+    if args.two_activation_sets:
+        gen = torch.Generator(device="cuda").manual_seed(args.data_seed + 7)
+        for m in mats:
+            m.x_minus = torch.randn(m.x.shape, device="cuda", generator=gen).to(torch.bfloat16)
     szo.szo_set_tile_config(args.tile_config)
     descs = szo.desc_array([m.desc(dt, with_y=bool(args.unfused_loss)) for m in mats])
     ws = szo.new_workspace()
@@ -320,7 +328,7 @@ def main():
     # ---- the dominant kernel alone: the library brackets every forward-kernel launch of a few more
     #      steps with events on the launch stream (szo_kernel_timing) ----
     fwd_flops = sum(2.0 * m.M * m.N * m.K for m in mats)
-    few = (all((few_token_path(m.M) or args.one_dense_pass) and m.K % 128 == 0 for m in mats) and dt == szo.TILE_F16
+    few = (all((few_token_path(m.M, args.two_activation_sets) or args.one_dense_pass) and m.K % 128 == 0 for m in mats) and dt == szo.TILE_F16
            and args.tile_config in (0, 4, 5) and bool(flags))                            # the library's few-token path
     reps = args.steps if args.kernel_reps is None else max(1, args.kernel_reps)
     szo.szo_kernel_timing(True)
@@ -382,7 +390,9 @@ def main():
                                + (f"int4 group {cfg['group']}, " if args.format == "uniform" else "4-bit table format, ") +
                                f"mask {cfg['density']:g} {cfg['mask']}, eps={eps}, lr={lr}",
                    "loss": "fused into the forward epilogue" if flags else "separate kernel",
-                   "dense_product": "once per slice of token rows, shared by both signs" if few else "once per sign",
+                   "dense_product": ("once per sign" if (not few or args.two_activation_sets)
+                                     else "once per slice of token rows, shared by both signs"),
+                   "activations": "x for +eps, x_minus for -eps" if args.two_activation_sets else "one x for both signs",
                    "tile": args.tile, "format": args.format, "accumulate": "f32", "loss_accumulate": "f64"},
         "step_tflops": round(step_flops / (ms_per_step * 1e-3) / 1e12, 2),
         "step_frac_of_mfma_peak": round(step_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_MFMA_16BIT_TFLOPS, 4),

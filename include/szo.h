@@ -76,6 +76,9 @@ typedef struct szo_linear_desc {
   const void*     lut;      /* device, fp16  [N,16] row-major, 16-byte aligned; SZO_FORMAT_LUT only */
   int32_t  format;          /* SZO_FORMAT_UNIFORM (0) or SZO_FORMAT_LUT                  */
   int32_t  reserved;        /* 0                                                         */
+  const void*     x_minus;  /* device, bf16 [M,K], 16-byte aligned, or NULL: what the -eps forward of
+                             * szo_zo_step reads instead of x (the two forwards of a layer inside a
+                             * model see different activations); ignored by the single-forward calls */
 } szo_linear_desc;
 
 /* Formats of the frozen 4-bit part (Section 3.5 allows any post-training quantiser; Appendix C.5,

@@ -29,6 +29,8 @@ class Matrix:
     target_bits: np.ndarray  # uint16 bf16 [M, N]
     nnz_base: int = 0
     lut: np.ndarray = None   # float16 [N, 16]: non-uniform format (scales, group unused)
+    x_minus_bits: np.ndarray = None   # uint16 bf16 [M, K]: activations seen by the -eps forward, if they
+                                      # differ (below the first layer of a model they do); None = x_bits
 
 
 def spsa_scalar(loss_plus, loss_minus, eps):
@@ -45,7 +47,8 @@ def model_loss(mats, seed, step, sign, eps, mode="E", tile_dtype="f16", zs=None,
     total = 0.0
     for i, m in enumerate(mats):
         z = zs[i] if zs is not None else zbar(seed, step, m.nnz_base, m.sp_idx.size)
-        y = linear_fwd(m.x_bits, m.codes, m.scales, m.group, m.sp_idx, m.sp_val,
+        x = m.x_minus_bits if (sign < 0 and m.x_minus_bits is not None) else m.x_bits
+        y = linear_fwd(x, m.codes, m.scales, m.group, m.sp_idx, m.sp_val,
                        z=z, sign=sign, eps=eps, mode=mode, tile_dtype=tile_dtype, lut=m.lut)
         total += loss_fn(y, m.target_bits)
     return total

@@ -827,7 +827,7 @@ static int validate_desc(const szo_linear_desc* d, int sign, bool need_y, bool n
   if (d->nnz > 0 && (!d->sp_idx || !d->sp_val)) return SZO_EINVAL;
   if (need_y && !d->y) return SZO_EINVAL;
   if (need_target && !d->target) return SZO_EINVAL;
-  if (((uintptr_t)d->x & 15) || ((uintptr_t)d->qweight & 15) || ((uintptr_t)d->scales & 1) ||
+  if (((uintptr_t)d->x & 15) || ((uintptr_t)d->x_minus & 15) || ((uintptr_t)d->qweight & 15) || ((uintptr_t)d->scales & 1) ||
       ((uintptr_t)d->tile_ptr & 3) || ((uintptr_t)d->sp_idx & 15) || ((uintptr_t)d->sp_val & 15) ||
       ((uintptr_t)d->y & 3) || ((uintptr_t)d->target & 1))
     return SZO_EINVAL;
@@ -913,13 +913,15 @@ static int fill_params(FwdParams& p, const szo_linear_desc* d, uint64_t seed, ui
   return SZO_OK;
 }
 
+// `step_minus`: this is the -eps forward of a whole step, which reads desc->x_minus where that is set.
 static int run_forward(const szo_linear_desc* d, uint64_t seed, uint64_t step, int sign, float eps,
-                       double* partials, double scale, hipStream_t stream) {
+                       double* partials, double scale, hipStream_t stream, bool step_minus = false) {
   const bool fuse = partials != nullptr;
   if (d->M == 0 || d->N == 0) return SZO_OK;
   FwdParams p;
   const int frc = fill_params(p, d, seed, step, sign, eps, partials, scale);
   if (frc != SZO_OK) return frc;
+  if (step_minus && d->x_minus) p.x = (const uint16_t*)d->x_minus;
   if (d->format == SZO_FORMAT_LUT)
     return fuse ? launch<2, 4, 4, 2, SZO_TILE_F16, true, SZO_FORMAT_LUT>(p, stream)
                 : launch<2, 4, 4, 2, SZO_TILE_F16, false, SZO_FORMAT_LUT>(p, stream);
@@ -988,6 +990,7 @@ static int grouped_forwards(const szo_linear_desc* descs, int n, uint64_t seed, 
       FwdParams p;
       const int rc = fill_params(p, d, seed, step, pass == 0 ? +1 : -1, eps, partials + (pass == 0 ? 0 : T) + offset, scale);
       if (rc != SZO_OK) return rc;
+      if (pass == 1 && d->x_minus) p.x = (const uint16_t*)d->x_minus;
       p.grid_m = gm; p.grid_n = gn;
       p.y = nullptr;                                        // the step's fused path never writes y
       p.first_block = (int)first_block;
@@ -1113,10 +1116,10 @@ int szo_zo_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t ste
         if (fuse) {
           int blocks;
           plan_tiles((int)d->M, (int)d->N, d->format, &blocks);
-          rc = run_forward(d, seed, step, sign, eps, part, scale, s);
+          rc = run_forward(d, seed, step, sign, eps, part, scale, s, pass == 1);
           part += blocks;
         } else {
-          rc = run_forward(d, seed, step, sign, eps, nullptr, 0.0, s);
+          rc = run_forward(d, seed, step, sign, eps, nullptr, 0.0, s, pass == 1);
           if (rc == SZO_OK) rc = szo_mse_loss(d->y, d->target, d->M * d->N, scale, scalars + pass, workspace, s);
         }
         if (rc != SZO_OK) return rc;

@@ -24,7 +24,7 @@ inline int hip_failed(hipError_t e) {
 constexpr int kMaxLossPartials = 1 << 20;
 constexpr size_t kWorkspaceHeader = 64;
 constexpr int kMaxStepMatrices = 4096;            // descriptor table of the few-token step
-constexpr size_t kTableBytesPerMatrix = 128;
+constexpr size_t kTableBytesPerMatrix = 144;
 constexpr size_t kWorkspaceTableOffset = kWorkspaceHeader + sizeof(double) * (size_t)kMaxLossPartials;
 constexpr size_t kWorkspaceBytes = kWorkspaceTableOffset + kTableBytesPerMatrix * (size_t)kMaxStepMatrices;
 

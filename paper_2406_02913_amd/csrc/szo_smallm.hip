@@ -56,6 +56,7 @@ constexpr int SM_CAP = 512;             // entries held per band (ring)
 
 struct SmallMat {
   const uint16_t* x;        // bf16 [M,K]
+  const uint16_t* x2;       // bf16 [M,K] or null: the -eps forward's activations where they differ (DUAL kernels)
   const uint8_t* qweight;   // [N,K/2]
   const uint16_t* scales;   // fp16 [N,K/group]
   const uint32_t* tile_ptr;
@@ -171,11 +172,16 @@ __device__ __forceinline__ half8_t sm_lut_word(uint32_t q, const uint32_t (&T)[8
 // often; each block costs 48 more registers (accumulators and activation operands): 196 and 253
 // registers, i.e. two workgroups per CU instead of three.
 constexpr int SM_PLAIN = 0, SM_FAST = 1, SM_LUT = 2;
-template <int MODE, int R>
+// DUAL (R = 2 only): the two forwards read different activations (x for +eps, x2 for -eps).  Block 0 then
+// holds 16 token rows of x and block 1 the same rows of x2: still one pass over the weights for both
+// signs, but nothing else is shared, and y(+) = acc[0] + eps accz[0], y(-) = acc[1] - eps accz[1].
+template <int MODE, int R, bool DUAL = false>
 __global__ void __launch_bounds__(256, R == 1 ? SM_MIN_BLOCKS : 2) small_m_kernel(SmallArgs a) {
   static_assert(R >= 1 && R <= 3, "one to three blocks of 16 token rows");
+  static_assert(!DUAL || R == 2, "two activation sets: one block of rows each");
   constexpr bool FAST = MODE == SM_FAST, LUT = MODE == SM_LUT;
-  constexpr int ROWS = SM_ROWS * R;                          // token rows of one pass
+  constexpr int ROWS = SM_ROWS * R;                          // rows of activations staged per pass
+  constexpr int TOK = DUAL ? SM_ROWS : ROWS;                 // token rows of one pass
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
   _Float16* const xs = reinterpret_cast<_Float16*>(smem);                        // [2][ROWS][SM_XSTRIDE]
   uint16_t* const winp = reinterpret_cast<uint16_t*>(xs + 2 * ROWS * SM_XSTRIDE);      // [4 bands][SM_CAP] packed position (see refill)
@@ -215,17 +221,19 @@ __global__ void __launch_bounds__(256, R == 1 ? SM_MIN_BLOCKS : 2) small_m_kerne
     for (int i = 0; i < W; ++i) raw.w[i] = tab[lo * W + i];
     mt = __builtin_bit_cast(SmallMat, raw);
   }
-  // a launch has as many slices of ROWS token rows per strip as its longest matrix needs
-  if (slice * ROWS >= mt.M) return;
-  mt.x += (size_t)slice * ROWS * (size_t)mt.K;
-  if (mt.target) mt.target += (size_t)slice * ROWS * (size_t)mt.N;
-  if (mt.y) mt.y += (size_t)slice * ROWS * (size_t)mt.N;
-  mt.M = min(ROWS, mt.M - slice * ROWS);
+  // a launch has as many slices of TOK token rows per strip as its longest matrix needs
+  if (slice * TOK >= mt.M) return;
+  mt.x += (size_t)slice * TOK * (size_t)mt.K;
+  if (DUAL) mt.x2 += (size_t)slice * TOK * (size_t)mt.K;
+  if (mt.target) mt.target += (size_t)slice * TOK * (size_t)mt.N;
+  if (mt.y) mt.y += (size_t)slice * TOK * (size_t)mt.N;
+  mt.M = min(TOK, mt.M - slice * TOK);
   mt.partial_base += slice * ((mt.N + SM_BN - 1) / SM_BN);      // slice i of a matrix: partials [i * strips ..)
   // Pointers read out of a table are generic to the compiler; say that they are global memory, or
   // every access becomes a flat load with conservative waits on both memory counters.
 #define SZO_GLOBAL(T, p) ((const T __attribute__((address_space(1)))*)(p))
   const auto g_x = SZO_GLOBAL(uint16_t, mt.x);
+  const auto g_x2 = SZO_GLOBAL(uint16_t, DUAL ? mt.x2 : mt.x);
   const auto g_q = SZO_GLOBAL(uint8_t, mt.qweight);
   const auto g_scales = SZO_GLOBAL(uint16_t, mt.scales);
   const auto g_tile_ptr = SZO_GLOBAL(uint32_t, mt.tile_ptr);
@@ -296,8 +304,9 @@ __global__ void __launch_bounds__(256, R == 1 ? SM_MIN_BLOCKS : 2) small_m_kerne
     const int col = min(c * SM_KC + 8 * (tid & 31), K - 8);
 #pragma unroll
     for (int i = 0; i < 2 * R; ++i) {
-      const int m = min((tid >> 5) + 8 * i, M - 1);
-      xr[i] = *reinterpret_cast<const u32x4 __attribute__((address_space(1)))*>(g_x + (size_t)m * K + col);
+      const int row = (tid >> 5) + 8 * i;                   // DUAL: staged rows 16.. are token rows 0.. of x2
+      const int m = min(DUAL ? (row & 15) : row, M - 1);
+      xr[i] = *reinterpret_cast<const u32x4 __attribute__((address_space(1)))*>(((DUAL && i >= 2) ? g_x2 : g_x) + (size_t)m * K + col);
     }
   };
   auto store_x = [&](int c) {
@@ -306,7 +315,7 @@ __global__ void __launch_bounds__(256, R == 1 ? SM_MIN_BLOCKS : 2) small_m_kerne
 #pragma unroll
     for (int i = 0; i < 2 * R; ++i) {
       const int m = (tid >> 5) + 8 * i;
-      const bool ok = col_ok && m < M;
+      const bool ok = col_ok && (DUAL ? (m & 15) : m) < M;
       u32x4 o;
 #pragma unroll
       for (int w = 0; w < 4; ++w) o[w] = ok ? sm_stage_x_word(xr[i], w) : 0u;
@@ -522,15 +531,15 @@ __global__ void __launch_bounds__(256, R == 1 ? SM_MIN_BLOCKS : 2) small_m_kerne
     const int nl = 16 * s + nn, n = n0 + wave * 64 + nl;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const int m = 16 * rb + 4 * jj + r;
+      const int m = (DUAL ? 0 : 16 * rb) + 4 * jj + r;     // token row
       if (m < M && n < N) {
         const float pz = a.eps * accz[rb][s][r];
         const float yp = acc[rb][s][r] + pz, ym = acc[rb][s][r] - pz;
         if (a.loss_mode) {
           const float t = __uint_as_float((uint32_t)g_target[(size_t)m * N + n] << 16);
           const float dp = yp - t, dm = ym - t;
-          lp += (double)(dp * dp);
-          lm += (double)(dm * dm);
+          if (!DUAL || rb == 0) lp += (double)(dp * dp);    // DUAL: block 0 is the +eps forward, block 1 the -eps one
+          if (!DUAL || rb == 1) lm += (double)(dm * dm);
         } else {
           g_y[(size_t)m * N + n] = a.store_sign > 0 ? yp : a.store_sign < 0 ? ym : acc[rb][s][r];
         }
@@ -615,17 +624,26 @@ static int small_m_mode(const szo_linear_desc* d) {
   return d->group == 128 ? SM_FAST : SM_PLAIN;
 }
 // position of an instantiation (mode, row blocks) in a step's table and launch order
-constexpr int kSmallClasses = 9;
-static int small_m_class(const szo_linear_desc* d, int rblocks) {
-  const int m = small_m_mode(d);
-  return 3 * (m == SM_FAST ? 0 : m == SM_LUT ? 1 : 2) + (rblocks - 1);
+// (classes 9..11: two activation sets, always two blocks of rows)
+constexpr int kSmallClasses = 12;
+static int small_m_class(const szo_linear_desc* d, int rblocks, bool dual) {
+  const int m = small_m_mode(d), mi = m == SM_FAST ? 0 : m == SM_LUT ? 1 : 2;
+  return dual ? 9 + mi : 3 * mi + (rblocks - 1);
 }
-static int class_mode(int cls) { return cls / 3 == 0 ? SM_FAST : cls / 3 == 1 ? SM_LUT : SM_PLAIN; }
-static int class_rblocks(int cls) { return cls % 3 + 1; }
+static bool class_dual(int cls) { return cls >= 9; }
+static int class_mode(int cls) {
+  const int mi = class_dual(cls) ? cls - 9 : cls / 3;
+  return mi == 0 ? SM_FAST : mi == 1 ? SM_LUT : SM_PLAIN;
+}
+static int class_rblocks(int cls) { return class_dual(cls) ? 2 : cls % 3 + 1; }
 
-static void small_m_launch(int mode, int r, dim3 blocks, const SmallArgs& a, hipStream_t stream) {
+static void small_m_launch(int mode, int r, bool dual, dim3 blocks, const SmallArgs& a, hipStream_t stream) {
   const size_t lds = small_lds_bytes(r);
-  if (r == 1) {
+  if (dual) {
+    if (mode == SM_FAST) small_m_kernel<SM_FAST, 2, true><<<blocks, 256, lds, stream>>>(a);
+    else if (mode == SM_LUT) small_m_kernel<SM_LUT, 2, true><<<blocks, 256, lds, stream>>>(a);
+    else small_m_kernel<SM_PLAIN, 2, true><<<blocks, 256, lds, stream>>>(a);
+  } else if (r == 1) {
     if (mode == SM_FAST) small_m_kernel<SM_FAST, 1><<<blocks, 256, lds, stream>>>(a);
     else if (mode == SM_LUT) small_m_kernel<SM_LUT, 1><<<blocks, 256, lds, stream>>>(a);
     else small_m_kernel<SM_PLAIN, 1><<<blocks, 256, lds, stream>>>(a);
@@ -653,7 +671,8 @@ bool small_m_shape_eligible(const szo_linear_desc* d) {
   return small_m_eligible(&one);
 }
 bool small_m_step_eligible(const szo_linear_desc* d) {
-  const int64_t slices = (d->M + 31) / 32, tile_rows = (d->M + 255) / 256;
+  // two activation sets: a pass holds 16 token rows of each, so it is worth less
+  const int64_t slices = (d->M + (d->x_minus ? 15 : 31)) / (d->x_minus ? 16 : 32), tile_rows = (d->M + 255) / 256;
   if (slices > kSmallMaxSlices || 2 * slices >= 15 * tile_rows) return false;
   return small_m_shape_eligible(d);
 }
@@ -663,8 +682,8 @@ int small_m_blocks(const szo_linear_desc* d) { return (int)((d->N + SM_BN - 1) /
 static int64_t small_m_wgs16(const szo_linear_desc* d) {
   return (int64_t)small_m_blocks(d) * ((d->M + SM_ROWS - 1) / SM_ROWS);
 }
-static int slices_of(const szo_linear_desc* d, int rblocks) {
-  const int rows = SM_ROWS * rblocks;
+static int slices_of(const szo_linear_desc* d, int rblocks, bool dual = false) {
+  const int rows = dual ? SM_ROWS : SM_ROWS * rblocks;
   return (int)((d->M + rows - 1) / rows);
 }
 // passes of a single-matrix call
@@ -673,7 +692,7 @@ int small_m_slices(const szo_linear_desc* d) { return slices_of(d, small_m_rbloc
 size_t small_m_table_bytes(int n) { return sizeof(SmallMat) * (size_t)n; }
 
 static void fill_mat(SmallMat& m, const szo_linear_desc* d) {
-  m.x = (const uint16_t*)d->x; m.qweight = d->qweight;
+  m.x = (const uint16_t*)d->x; m.x2 = (const uint16_t*)d->x_minus; m.qweight = d->qweight;
   m.scales = (const uint16_t*)(d->format == SZO_FORMAT_LUT ? d->lut : d->scales);
   m.tile_ptr = d->tile_ptr; m.sp_idx = d->sp_idx; m.sp_val = d->sp_val;
   m.target = (const uint16_t*)d->target; m.y = d->y;
@@ -702,6 +721,9 @@ static int set_small_attrs() {
     SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_FAST, 3>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds_bytes(3)));
     SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_PLAIN, 3>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds_bytes(3)));
     SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_LUT, 3>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds_bytes(3)));
+    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_FAST, 2, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds_bytes(2)));
+    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_PLAIN, 2, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds_bytes(2)));
+    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_LUT, 2, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds_bytes(2)));
     attr_set = true;
   }
   return SZO_OK;
@@ -728,7 +750,7 @@ int small_m_launch_one(const szo_linear_desc* d, uint64_t seed, uint64_t step, f
   const int trc = timing_begin(stream);
   if (trc != SZO_OK) return trc;
   a.slices = slices;
-  small_m_launch(small_m_mode(d), rblocks, dim3((unsigned)(blocks * slices)), a, stream);
+  small_m_launch(small_m_mode(d), rblocks, false, dim3((unsigned)(blocks * slices)), a, stream);
   SZO_LAUNCH_CHECK();
   const int erc = timing_end(stream);
   if (erc != SZO_OK) return erc;
@@ -748,7 +770,9 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
   if (n > kMaxStepMatrices) return SZO_EUNSUPPORTED;
   int64_t wgs16 = 0;
   for (int i = 0; i < n; ++i) wgs16 += small_m_wgs16(&descs[i]);
-  auto rblocks_of = [&](const szo_linear_desc* d) { return small_m_rblocks(d, wgs16); };
+  // two activation sets (forward launches only): one block of rows for each, whatever the token count
+  auto dual_of = [&](const szo_linear_desc* d) { return do_forward && d->x_minus != nullptr; };
+  auto rblocks_of = [&](const szo_linear_desc* d) { return dual_of(d) ? 2 : small_m_rblocks(d, wgs16); };
   if (small_m_table_bytes(n) > kTableBytesPerMatrix * (size_t)kMaxStepMatrices) return SZO_EUNSUPPORTED;
   static thread_local std::vector<SmallMat> host_table;
   host_table.resize((size_t)std::max(n, 1));
@@ -757,7 +781,7 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
   int order[kMaxStepMatrices];
   for (int i = 0; i < n; ++i) order[i] = i;
   auto sort_key = [&](int o) {
-    return ((int64_t)(kSmallClasses - 1 - small_m_class(&descs[o], rblocks_of(&descs[o]))) << 40) + descs[o].K;
+    return ((int64_t)(kSmallClasses - 1 - small_m_class(&descs[o], rblocks_of(&descs[o]), dual_of(&descs[o]))) << 40) + descs[o].K;
   };
   for (int i = 1; i < n; ++i) {                       // insertion sort: n is a few hundred
     const int o = order[i];
@@ -778,8 +802,8 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
   for (int r = 0; r < n; ++r) {
     const szo_linear_desc* d = &descs[order[r]];
     const int rblocks = rblocks_of(d);
-    const int cls = small_m_class(d, rblocks);
-    const int slices = slices_of(d, rblocks), b = small_m_blocks(d);
+    const int cls = small_m_class(d, rblocks, dual_of(d));
+    const int slices = slices_of(d, rblocks, dual_of(d)), b = small_m_blocks(d);
     SmallMat& m = host[entries++];
     fill_mat(m, d);
     m.first_block = class_blocks[cls];
@@ -806,7 +830,7 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
       a.table = tdev + first_entry; a.n_mats = class_entries[cls];
       a.slices = class_slices[cls];
       if ((rc = timing_begin(stream)) != SZO_OK) return rc;
-      small_m_launch(class_mode(cls), class_rblocks(cls), dim3((unsigned)(class_blocks[cls] * class_slices[cls])), a, stream);
+      small_m_launch(class_mode(cls), class_rblocks(cls), class_dual(cls), dim3((unsigned)(class_blocks[cls] * class_slices[cls])), a, stream);
       SZO_LAUNCH_CHECK();
       if ((rc = timing_end(stream)) != SZO_OK) return rc;
     }

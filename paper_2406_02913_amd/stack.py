@@ -32,12 +32,13 @@ class DeviceLinear:
     target: torch.Tensor
     y: torch.Tensor = None
     lut: torch.Tensor = None          # fp16 [N,16]: non-uniform format (scales is None then)
+    x_minus: torch.Tensor = None      # bf16 [M,K]: activations of the -eps forward, if they differ
     host: dict = field(default_factory=dict)
 
     def desc(self, tile_dtype=szo.TILE_F16, with_y=True):
         return szo.make_desc(self.M, self.N, self.K, self.group, self.nnz, self.nnz_base, self.x,
                              self.qweight, self.scales, self.tile_ptr, self.sp_idx, self.sp_val,
-                             self.y if with_y else None, self.target, tile_dtype, self.lut)
+                             self.y if with_y else None, self.target, tile_dtype, self.lut, self.x_minus)
 
 
 def _to_dev(a, device, dtype=None):

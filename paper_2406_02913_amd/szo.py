@@ -33,7 +33,8 @@ class LinearDesc(C.Structure):
                 ("x", C.c_void_p), ("qweight", C.c_void_p), ("scales", C.c_void_p),
                 ("tile_ptr", C.c_void_p), ("sp_idx", C.c_void_p), ("sp_val", C.c_void_p),
                 ("y", C.c_void_p), ("target", C.c_void_p),
-                ("lut", C.c_void_p), ("format", C.c_int32), ("reserved", C.c_int32)]
+                ("lut", C.c_void_p), ("format", C.c_int32), ("reserved", C.c_int32),
+                ("x_minus", C.c_void_p)]
 
 
 _P = C.POINTER
@@ -111,11 +112,12 @@ def _stream(stream):
 
 
 def make_desc(M, N, K, group, nnz, nnz_base, x, qweight, scales, tile_ptr, sp_idx, sp_val,
-              y=None, target=None, tile_dtype=TILE_F16, lut=None):
-    """With `lut` (device fp16 [N,16]) the layer is of the non-uniform format; scales may then be None."""
+              y=None, target=None, tile_dtype=TILE_F16, lut=None, x_minus=None):
+    """With `lut` (device fp16 [N,16]) the layer is of the non-uniform format; scales may then be None.
+    `x_minus` (device bf16 [M,K]): activations of the -eps forward of szo_zo_step, if they differ from x."""
     return LinearDesc(M, N, K, group, tile_dtype, nnz, nnz_base, _dev(x), _dev(qweight), _dev(scales),
                       _dev(tile_ptr), _dev(sp_idx), _dev(sp_val), _dev(y), _dev(target),
-                      _dev(lut), FORMAT_UNIFORM if lut is None else FORMAT_LUT, 0)
+                      _dev(lut), FORMAT_UNIFORM if lut is None else FORMAT_LUT, 0, _dev(x_minus))
 
 
 # ---- hot calls -------------------------------------------------------------------------------

@@ -30,7 +30,8 @@ def make_oracle_matrix(seed, M, N, K, group, density=1e-3, kind="uniform", nnz=N
 
 
 def clone(m):
-    c = Matrix(m.x_bits, m.codes, m.scales, m.group, m.sp_idx, m.sp_val.copy(), m.target_bits, m.nnz_base, m.lut)
+    c = Matrix(m.x_bits, m.codes, m.scales, m.group, m.sp_idx, m.sp_val.copy(), m.target_bits, m.nnz_base, m.lut,
+               m.x_minus_bits)
     for a in ("tile_ptr", "W", "flat_sorted"):
         if hasattr(m, a):
             setattr(c, a, getattr(m, a))

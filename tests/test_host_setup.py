@@ -21,15 +21,16 @@ def test_every_declared_symbol_is_exported():
     assert declared == set(szo.EXPORTS)
     for name in declared:
         assert getattr(szo.lib, name) is not None
-    assert szo.szo_version() == 2
+    assert szo.szo_version() == 3
     assert szo.szo_workspace_bytes() >= 64 + 8 * 1024
 
 
 def test_descriptor_layout_matches_header():
     # 3*8 + 2*4 + 8 + 8 + 8 pointers*8 + table pointer + format + reserved
-    assert ctypes.sizeof(szo.LinearDesc) == 24 + 8 + 16 + 64 + 8 + 4 + 4
+    assert ctypes.sizeof(szo.LinearDesc) == 24 + 8 + 16 + 64 + 8 + 4 + 4 + 8
     assert szo.LinearDesc.x.offset == 48 and szo.LinearDesc.target.offset == 104
     assert szo.LinearDesc.lut.offset == 112 and szo.LinearDesc.format.offset == 120
+    assert szo.LinearDesc.x_minus.offset == 128
 
 
 @pytest.mark.parametrize("N,K,dens,seed", [(130, 64, 0.02, 21), (256, 1024, 1e-2, 22), (64, 4096, 1e-3, 23)])
