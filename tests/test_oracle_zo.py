@@ -144,3 +144,21 @@ def test_resume_is_exact():
         zo.zo_step(c, 5, s, 1e-3, 1e-3)
     for x, y in zip(a, c):
         assert np.array_equal(x.sp_val, y.sp_val)
+
+
+def test_second_activation_set_is_what_the_minus_forward_reads():
+    from oracle import layer as olayer
+    from paper_2406_02913_amd import synth
+    a = make_oracle_matrix(seed=3, M=6, N=64, K=128, group=32, nnz=17, nnz_base=4)
+    b = make_oracle_matrix(seed=3, M=6, N=64, K=128, group=32, nnz=17, nnz_base=4)
+    b.x_minus_bits = b.x_bits.copy()                       # the same set twice: nothing changes
+    ra, rb = zo.zo_step([a], 9, 1, 1e-3, 0.0), zo.zo_step([b], 9, 1, 1e-3, 0.0)
+    assert ra["loss_plus"] == rb["loss_plus"] and ra["loss_minus"] == rb["loss_minus"] and ra["g"] == rb["g"]
+    c = make_oracle_matrix(seed=3, M=6, N=64, K=128, group=32, nnz=17, nnz_base=4)
+    c.x_minus_bits = synth.activations(99, 6, 128)
+    rc = zo.zo_step([c], 9, 1, 1e-3, 0.0)
+    assert rc["loss_plus"] == ra["loss_plus"]
+    z = rc["z"][0]
+    y = olayer.linear_fwd(c.x_minus_bits, c.codes, c.scales, c.group, c.sp_idx, c.sp_val, z, -1, 1e-3)
+    assert rc["loss_minus"] == olayer.mse_loss(y, c.target_bits)          # an independent -eps forward on the second set
+    assert rc["g"] == (rc["loss_plus"] - rc["loss_minus"]) / (2.0 * float(np.float32(1e-3)))
