@@ -1,4 +1,4 @@
-"""GPU parity of the few-token path (M <= 16): dense product once, sparse
+"""GPU parity of the few-token path (slices of 16, 32 or 48 token rows): dense product once, sparse
 product per sign (the SparseAddMM association of Appendix C.5)."""
 import numpy as np
 import pytest
