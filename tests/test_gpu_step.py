@@ -289,3 +289,42 @@ def test_one_dense_pass_flag_takes_the_slicing_path_at_any_token_count():
     assert outs[szo.STEP_FUSED_LOSS | szo.STEP_ONE_DENSE_PASS][0] == 2  # one launch per instantiation (group 128, group 64)
     ga, gb = outs[szo.STEP_FUSED_LOSS][1], outs[szo.STEP_FUSED_LOSS | szo.STEP_ONE_DENSE_PASS][1]
     assert abs(ga - gb) <= 2e-2 * max(abs(ga), sg)
+
+
+def test_two_host_threads_each_with_its_own_stream_and_workspace():
+    """The step's descriptor tables travel through per-thread pinned buffers: two host threads stepping
+    different layers on different streams with different workspaces must not disturb each other."""
+    import threading
+    szo.szo_set_tile_config(0)
+    cases = [(121, 300, 384, 512, 128, 2e-3), (122, 40, 512, 1152, 128, 2e-3)]      # tiled kernel | few-token kernel
+    want = []
+    for c in cases:                                    # reference: one after the other, default stream
+        _, d = make_pair(*c)
+        want.append((_gpu_steps([d], 6, 41, 1e-3, 1e-3, szo.STEP_FUSED_LOSS), d.sp_val.cpu().numpy().copy()))
+    devs = [make_pair(*c)[1] for c in cases]
+    wss = [szo.new_workspace() for _ in cases]
+    scals = [torch.zeros(3, dtype=torch.float64, device="cuda") for _ in cases]
+    streams = [torch.cuda.Stream() for _ in cases]
+    torch.cuda.synchronize()
+    got = [[], []]
+    errors = []
+
+    def worker(i):
+        try:
+            descs = szo.desc_array([devs[i].desc()])
+            for s in range(6):
+                szo.szo_zo_step(descs, 41, s, 1e-3, 1e-3, scals[i], wss[i], szo.STEP_FUSED_LOSS, streams[i].cuda_stream)
+                streams[i].synchronize()
+                got[i].append(scals[i].cpu().numpy().copy())
+        except Exception as e:                          # surfaced in the main thread below
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=100)
+    assert not errors and all(not t.is_alive() for t in threads)
+    for i in range(2):
+        assert all(np.array_equal(a, b) for a, b in zip(got[i], want[i][0]))
+        assert np.array_equal(devs[i].sp_val.cpu().numpy(), want[i][1])
