@@ -1070,7 +1070,8 @@ int szo_zo_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t ste
   for (int i = 0; i < n; ++i) {     // reject everything before anything is enqueued
     const int rc = validate_desc(&descs[i], 1, !fuse, true);
     if (rc != SZO_OK) return rc;
-    if (descs[i].nnz > 0 && ((uintptr_t)descs[i].sp_val & 15)) return SZO_EINVAL;
+    // the update touches every layer's values, also those of a layer without tokens
+    if (descs[i].nnz > 0 && (!descs[i].sp_val || ((uintptr_t)descs[i].sp_val & 15))) return SZO_EINVAL;
     if (descs[i].M == 0 || descs[i].N == 0) continue;
     int blocks;
     plan_tiles((int)descs[i].M, (int)descs[i].N, descs[i].format, &blocks);
@@ -1081,7 +1082,10 @@ int szo_zo_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t ste
   // Few-token stacks: one pass over the weights serves both forwards of the step.
   bool few = fuse && few_token_enabled() && n > 0 && n <= kMaxStepMatrices;
   const bool one_pass = flags & SZO_STEP_ONE_DENSE_PASS;     // the caller asks for the slicing path at any token count
-  for (int i = 0; few && i < n; ++i) few = one_pass ? small_m_shape_eligible(&descs[i]) : small_m_step_eligible(&descs[i]);
+  for (int i = 0; few && i < n; ++i) {
+    if (descs[i].M == 0 || descs[i].N == 0) continue;        // an empty layer contributes nothing on either path
+    few = one_pass ? small_m_shape_eligible(&descs[i]) : small_m_step_eligible(&descs[i]);
+  }
   if (few) {
     rc = small_m_step(descs, n, seed, step, eps, lr, (char*)workspace + kWorkspaceTableOffset,
                       partial_area(workspace), scalars, true, true, s);

@@ -328,3 +328,19 @@ def test_two_host_threads_each_with_its_own_stream_and_workspace():
     for i in range(2):
         assert all(np.array_equal(a, b) for a, b in zip(got[i], want[i][0]))
         assert np.array_equal(devs[i].sp_val.cpu().numpy(), want[i][1])
+
+
+@pytest.mark.parametrize("flags", [0, szo.STEP_FUSED_LOSS])
+def test_empty_steps_and_empty_layers(flags):
+    szo.szo_set_tile_config(0)
+    ws = szo.new_workspace()
+    scal = torch.full((3,), 7.0, dtype=torch.float64, device="cuda")
+    szo.szo_zo_step([], 1, 0, 1e-3, 1e-3, scal, ws, flags)            # no layers: losses and g are zero
+    assert scal.cpu().tolist() == [0.0, 0.0, 0.0]
+    o, d = make_pair(131, 40, 256, 256, 128, 1e-2)
+    empty = d.desc()
+    empty.M = 0                                                        # a layer without tokens contributes nothing
+    szo.szo_zo_step([d.desc(), empty], 1, 0, 1e-3, 0.0, scal, ws, flags)
+    a = scal.cpu().numpy().copy()
+    szo.szo_zo_step([d.desc()], 1, 0, 1e-3, 0.0, scal, ws, flags)
+    assert np.array_equal(a, scal.cpu().numpy()) and a[0] > 0

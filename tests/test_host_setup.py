@@ -188,6 +188,10 @@ def test_hot_calls_validate_before_touching_the_gpu():
     assert szo.lib.szo_sparse_update(None, None, 4, 2, 0, 0, None, 0.1, None) == szo.EINVAL
     assert szo.lib.szo_spsa_g(None, None, 0.1, None, None) == szo.EINVAL
     assert szo.lib.szo_zo_step(None, 1, 0, 0, 0.1, 0.1, None, None, 0, None) == szo.EINVAL
+    # a layer without tokens may leave its activation pointers empty, but its sparse values are updated
+    e = szo.LinearDesc(M=0, N=64, K=128, group=32, tile_dtype=0, nnz=8, nnz_base=0)
+    buf = ctypes.create_string_buffer(64)
+    assert szo.lib.szo_zo_step(ctypes.byref(e), 1, 0, 0, 0.1, 0.1, ctypes.addressof(buf), ctypes.addressof(buf), 0, None) == szo.EINVAL
     assert szo.lib.szo_debug_zbar(0, -1, 0, 0, None, None, None) == szo.EINVAL
 
 
