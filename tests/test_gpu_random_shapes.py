@@ -74,3 +74,32 @@ def test_random_case(case):
     dv_ref = om.sp_val.astype(np.float64) - o.sp_val
     tol = gtol * max(abs(r["g"]), sg) / max(abs(r["g"]), 1e-300) + 1e-2
     assert np.linalg.norm(dv_gpu - dv_ref) <= tol * np.linalg.norm(dv_ref) + 1e-12
+
+
+@pytest.mark.parametrize("M,cfg,fmt", [(16, 0, "uniform"), (48, 5, "uniform"), (16, 0, "lut"), (300, 2, "uniform"), (300, 3, "lut")])
+def test_every_weight_sensitive(M, cfg, fmt):
+    """Density 1: the whole matrix lives in the sparse part (4096 entries per 64 x 64 tile), the dense codes
+    are all the zero code (or, in the table format, whatever centroid is nearest to zero)."""
+    N, K = 128, 256
+    o, d = make_pair(2001, M, N, K, 128, 1.0, fmt=fmt)
+    assert o.sp_idx.size == N * K
+    szo.szo_set_tile_config(cfg)
+    seed, step, eps = 3, 2, 1e-3
+    z = ophilox.zbar(seed, step, 0, o.sp_idx.size)
+    for sign in (+1, -1):
+        szo.szo_linear_fwd(d.desc(), seed, step, sign, eps)
+        torch.cuda.synchronize()
+        yE = olayer.linear_fwd(o.x_bits, o.codes, None if fmt == "lut" else o.scales, 128, o.sp_idx, o.sp_val, z, sign, eps, "E", lut=o.lut)
+        assert rel_fro(d.y.cpu().numpy(), yE) <= 5e-3
+    ws = szo.new_workspace()
+    scal = torch.zeros(3, dtype=torch.float64, device="cuda")
+    om = clone(o)
+    szo.szo_zo_step([d.desc(with_y=False)], seed, step, eps, 1e-4, scal, ws, szo.STEP_FUSED_LOSS)
+    r = ozo.zo_step([om], seed, step, eps, 1e-4)
+    lp, lm, g = scal.cpu().numpy()
+    sg = sigma_g([o])
+    assert abs(lp - r["loss_plus"]) <= 5e-3 * r["loss_plus"] and abs(g - r["g"]) <= 1e-2 * max(abs(r["g"]), sg)
+    dv_gpu = d.sp_val.cpu().numpy().astype(np.float64) - o.sp_val
+    dv_ref = om.sp_val.astype(np.float64) - o.sp_val
+    tol = 1e-2 * max(abs(r["g"]), sg) / max(abs(r["g"]), 1e-300) + 1e-2
+    assert np.linalg.norm(dv_gpu - dv_ref) <= tol * np.linalg.norm(dv_ref) + 1e-12
