@@ -344,3 +344,20 @@ def test_empty_steps_and_empty_layers(flags):
     a = scal.cpu().numpy().copy()
     szo.szo_zo_step([d.desc()], 1, 0, 1e-3, 0.0, scal, ws, flags)
     assert np.array_equal(a, scal.cpu().numpy()) and a[0] > 0
+
+
+@pytest.mark.parametrize("cfg", [0, 3])
+def test_step_over_layers_of_both_tile_types(cfg):
+    # an fp16-tile layer and a bf16-tile layer in one step: no grouped launch, one g
+    szo.szo_set_tile_config(cfg)
+    o1, d1 = make_pair(141, 300, 256, 256, 128, 5e-3, nnz_base=0)
+    b2 = (o1.sp_idx.size + 3) // 4 * 4
+    o2, d2 = make_pair(142, 300, 320, 512, 64, 5e-3, nnz_base=b2)
+    ws = szo.new_workspace()
+    scal = torch.zeros(3, dtype=torch.float64, device="cuda")
+    descs = szo.desc_array([d1.desc(szo.TILE_F16, with_y=False), d2.desc(szo.TILE_BF16, with_y=False)])
+    szo.szo_zo_step(descs, 3, 0, 1e-3, 0.0, scal, ws, szo.STEP_FUSED_LOSS)
+    lp, lm, g = scal.cpu().numpy()
+    r = ozo.zo_step([clone(o1), clone(o2)], 3, 0, 1e-3, 0.0)
+    assert abs(lp - r["loss_plus"]) <= 5e-3 * r["loss_plus"] and abs(lm - r["loss_minus"]) <= 5e-3 * r["loss_minus"]
+    assert abs(g - r["g"]) <= 1e-1 * max(abs(r["g"]), sigma_g([o1, o2]))       # the bf16 layer's share of g is coarse
