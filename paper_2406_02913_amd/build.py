@@ -11,7 +11,6 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 HIP_SOURCES = ["szo_kernels.hip", "szo_gemm.hip", "szo_smallm.hip"]
 HOST_SOURCES = ["szo_host.cpp"]
-PROBES = ["mfma_ceiling", "hbm_read_ceiling"]
 
 COMMON = ["-O3", "-fPIC", "-std=c++17", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 # packed fp32 VALU forms are switched off (see the hardware notes this project follows)
@@ -25,8 +24,7 @@ def _run(cmd, verbose):
 
 
 def build(verbose=False, extra=()):
-    """Compiles every source (in parallel: the translation units are independent), links the library,
-    and builds the stand-alone measurement probes."""
+    """Compiles every source (in parallel: the translation units are independent) and links the library."""
     from concurrent.futures import ThreadPoolExecutor
     jobs, objs = [], []
     for src in HOST_SOURCES:
@@ -37,10 +35,6 @@ def build(verbose=False, extra=()):
         obj = os.path.join(CSRC, src + ".o")
         jobs.append([HIPCC, "-c"] + COMMON + DEVICE + list(extra) + [os.path.join(CSRC, src), "-o", obj])
         objs.append(obj)
-    # stand-alone measurement probes (ceilings quoted in the profile summaries); not linked into the library
-    for probe in PROBES:
-        jobs.append([HIPCC, "-O3", "-std=c++17"] + DEVICE + [os.path.join(CSRC, "probes", probe + ".hip"),
-                                                              "-o", os.path.join(HERE, "probe_" + probe)])
     with ThreadPoolExecutor(max_workers=min(8, len(jobs))) as pool:
         list(pool.map(lambda c: _run(c, verbose), jobs))
     _run([HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs + ["-lpthread"], verbose)

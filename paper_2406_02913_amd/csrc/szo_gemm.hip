@@ -25,7 +25,7 @@
 #include <cstddef>
 #include <vector>
 #include "szo_internal.h"
-#include "szo_rng.cuh"
+#include "szo_rng.h"
 #include <type_traits>
 
 namespace szo {

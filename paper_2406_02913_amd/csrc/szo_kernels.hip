@@ -3,7 +3,7 @@
 #include <cstring>
 #include <vector>
 #include "szo_internal.h"
-#include "szo_rng.cuh"
+#include "szo_rng.h"
 
 namespace szo {
 

@@ -32,7 +32,7 @@
 #include <cstddef>
 #include <vector>
 #include "szo_internal.h"
-#include "szo_rng.cuh"
+#include "szo_rng.h"
 
 namespace szo {
 
