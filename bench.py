@@ -8,7 +8,11 @@ of each, the SPSA scalar g, and the sparse update of every matrix.  Inputs are
 seeded, synthetic and already resident in HBM when the clock starts.
 
 Prints ONE JSON line: metric, value (ZO steps/s), ms_per_step, the roofline of the dominant kernel
-(achieved vs peak, from per-launch events recorded by the library) and the CPU oracle as a baseline.
+(achieved vs peak, from per-launch events recorded by the library around the launches of the timed
+steps themselves), the CPU oracle as a baseline with the parity of the GPU path on the same sample,
+and -- in the default invocation -- the other workloads of the configuration list as extra keys:
+`few_token` (the same stack at 16 tokens, HBM-bound), `c4` (a Mistral-7B block at 8192 tokens at three
+mask densities) and `c5` (a 32-block OPT-6.7B stack at 1 / 16 / 64 tokens).
 """
 import argparse
 import json
@@ -32,11 +36,11 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def algorithmic_bytes_fwd(m, fused=True):
+def algorithmic_bytes_fwd(m, M, fused=True):
     """Bytes one pass over a matrix must move: codes + scales + sparse (idx, val) + x, and either
     the bf16 target (loss fused into the kernel) or the fp32 y it writes."""
     side = 32 * m.N if m.lut is not None else 2 * m.N * (m.K // m.group)    # per-row table | group scales
-    return (m.N * m.K // 2 + side + 8 * m.nnz + 2 * m.M * m.K + (2 if fused else 4) * m.M * m.N)
+    return (m.N * m.K // 2 + side + 8 * m.nnz + 2 * M * m.K + (2 if fused else 4) * M * m.N)
 
 
 def few_token_path(M, two_sets=False):
@@ -48,40 +52,172 @@ def few_token_path(M, two_sets=False):
     return slices <= 15 and 2 * slices < 15 * tile_rows
 
 
-def cpu_baseline(cfg, args, total_flops_per_step):
-    """The oracle, as it stands, on a bounded sample of the same workload."""
+def time_steps(szo, torch, descs, seed, eps, lr, flags, steps, warmup, first_step=0):
+    """`warmup` untimed steps, then `steps` timed ones between two events on the launch stream; the same
+    timed steps have every forward-kernel and update-kernel launch bracketed by the library's own events."""
+    ws = szo.new_workspace()
+    scal = torch.zeros(3, dtype=torch.float64, device="cuda")
+    stream = torch.cuda.current_stream()
+    for s in range(first_step, first_step + warmup):
+        szo.szo_zo_step(descs, seed, s, eps, lr, scal, ws, flags, stream.cuda_stream)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    szo.szo_kernel_timing(True)
+    w0 = time.perf_counter()
+    ev0.record(stream)
+    for s in range(first_step + warmup, first_step + warmup + steps):
+        szo.szo_zo_step(descs, seed, s, eps, lr, scal, ws, flags, stream.cuda_stream)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - w0
+    (k_ms, k_n), (u_ms, u_n) = szo.szo_kernel_timing_read2()
+    szo.szo_kernel_timing(False)
+    lp, lm, g = scal.cpu().tolist()
+    return {"ms_per_step": ev0.elapsed_time(ev1) / steps, "wall_ms_per_step": 1e3 * wall / steps,
+            "fwd_ms": k_ms, "fwd_launches": k_n, "upd_ms": u_ms, "upd_launches": u_n,
+            "steps": steps, "warmup": warmup, "last": (lp, lm, g)}
+
+
+def rooflines(mats, M, t, few, fused, traffic=None):
+    """Roofline entry of the dominant (forward) kernel and the figures of the sparse update, per launch."""
+    steps = t["steps"]
+    fwd_flops = sum(2.0 * M * m.N * m.K for m in mats)
+    launches = t["fwd_launches"]
+    k_ms = t["fwd_ms"] / launches
+    one_pass = float(sum(algorithmic_bytes_fwd(m, M, fused) for m in mats))
+    if few:       # one launch streams every matrix once and serves both signs
+        kernel = "small_m_kernel"
+        launch_bytes = one_pass * steps / launches
+    else:         # large fused steps run every forward of the step in one table-driven launch
+        kernel = "linear_fwd_table_kernel" if launches == steps else "linear_fwd_kernel"
+        launch_bytes = one_pass * 2 * steps / launches
+    launch_flops = 2 * fwd_flops * steps / launches
+    tflops = launch_flops / (k_ms * 1e-3) / 1e12
+    gbs = launch_bytes / (k_ms * 1e-3) / 1e9
+    mfma_bound = (launch_flops / launch_bytes) > (PEAK_MFMA_16BIT_TFLOPS * 1e12) / (PEAK_HBM_GBS * 1e9)
+    if mfma_bound:
+        roof = {"bound": "mfma", "achieved": round(tflops, 2), "peak": PEAK_MFMA_16BIT_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(tflops / PEAK_MFMA_16BIT_TFLOPS, 4), "traffic": traffic}
+    else:
+        roof = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": traffic}
+    roof.update({"kernel": kernel, "avg_launch_us": round(1e3 * k_ms, 2), "launches_timed": launches,
+                 "flops_per_launch": launch_flops, "bytes_per_launch": launch_bytes,
+                 "algorithmic_tflops": round(tflops, 2), "algorithmic_gbs": round(gbs, 1)})
+    upd = None
+    if t["upd_launches"]:       # 8 bytes per sensitive entry (fp32 value read and written); z is regenerated
+        u_ms = t["upd_ms"] / t["upd_launches"]
+        u_bytes = 8.0 * sum(m.nnz for m in mats) * steps / t["upd_launches"]
+        upd = {"kernel": "sparse_update", "avg_launch_us": round(1e3 * u_ms, 2), "launches_timed": t["upd_launches"],
+               "bytes_per_launch": u_bytes, "achieved": round(u_bytes / (u_ms * 1e-3) / 1e9, 1), "unit": "GB/s",
+               "frac_of_hbm_peak": round(u_bytes / (u_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+    return roof, upd, 2 * fwd_flops
+
+
+def descs_for(szo, mats, M, dt, with_y):
+    """Descriptors of the stack at M tokens: the first M rows of every x and target (row-major, so a
+    prefix of the resident arrays)."""
+    out = []
+    for m in mats:
+        d = m.desc(dt, with_y=with_y)
+        d.M = M
+        out.append(d)
+    return szo.desc_array(out)
+
+
+def extra_workload(szo, torch, stack, name, seed, data_seed, dt, variants, steps=None, warmup=None, **build):
+    """Builds `name` once per entry of `variants` that changes the stack (density) or once for all (token
+    counts), times the fused step, and returns one summary per variant."""
+    rows = []
+    mats = cfg = None
+    for v in variants:
+        if mats is None or "density" in v:
+            del mats
+            torch.cuda.empty_cache()
+            mats, cfg = stack.build_stack(name, data_seed, "cuda", density=v.get("density"), **build)
+        M = v.get("M", mats[0].M)
+        few = few_token_path(M)
+        descs = descs_for(szo, mats, M, dt, with_y=False)
+        t = time_steps(szo, torch, descs, seed, cfg["eps"], cfg["lr"], szo.STEP_FUSED_LOSS,
+                       steps or (200 if few else 20), warmup if warmup is not None else (30 if few else 5))
+        roof, upd, step_flops = rooflines(mats, M, t, few, True)
+        row = {"M": M, "density": v.get("density", cfg["density"]), "matrices": len(mats),
+               "ms_per_step": round(t["ms_per_step"], 4), "steps": t["steps"], "warmup": t["warmup"],
+               "step_tflops": round(step_flops / (t["ms_per_step"] * 1e-3) / 1e12, 2),
+               "roofline": roof, "sparse_update": upd}
+        log(f"[bench] {name} {v}: {t['ms_per_step']:.3f} ms/step, {roof['kernel']} {roof['achieved']} {roof['unit']} "
+            f"({100 * roof['frac']:.1f} % of peak)")
+        rows.append(row)
+    del mats
+    torch.cuda.empty_cache()
+    return rows
+
+
+def cpu_baseline_and_parity(szo, torch, mats, pristine, cfg, args, total_flops_per_step, dt):
+    """The oracle, as it stands, on a bounded sample of the same workload (whole matrices in stack order,
+    one full ZO step each, until the time budget is used), and the GPU path on the same sample (the same
+    matrices with their initial sparse values, one single-matrix fused step each through the C ABI):
+    the per-matrix losses and SPSA scalars of both sides, and the outputs of the first matrix, compared."""
     import numpy as np
     sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from helpers import make_oracle_matrix
-    from oracle import zo as ozo
+    from helpers import make_oracle_matrix, rel_fro
+    from oracle import zo as ozo, layer as olayer, philox as ophilox
     from paper_2406_02913_amd import synth
     try:
         from threadpoolctl import threadpool_info
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = os.cpu_count()
-    M = args.m or cfg["M"]
-    done_flops, t_spent, used = 0.0, 0.0, []
-    layers = args.layers or cfg["layers"]
-    for layer in range(layers):                 # whole matrices, in stack order, until the time budget is used
-        for i, (name, N, K) in enumerate(cfg["block"]):
-            m = make_oracle_matrix(synth.matrix_seed(args.data_seed, layer, i), M, N, K, cfg["group"],
-                                   cfg["density"], cfg["mask"], fmt=args.format)
-            t0 = time.perf_counter()
-            ozo.zo_step([m], args.seed, 0, cfg["eps"], cfg["lr"])
-            t_spent += time.perf_counter() - t0
-            done_flops += 2 * 2.0 * M * N * K
-            used.append(f"L{layer}.{name}")
-            if t_spent >= args.cpu_seconds:
-                break
+    M = mats[0].M
+    done_flops, t_spent, used, ref = 0.0, 0.0, [], []
+    nb = len(cfg["block"])
+    y_rel = None
+    for idx, dm in enumerate(mats):
+        layer, i = divmod(idx, nb)
+        name, N, K = cfg["block"][i]
+        m = make_oracle_matrix(synth.matrix_seed(args.data_seed, layer, i), M, N, K, cfg["group"],
+                               cfg["density"], cfg["mask"], nnz_base=dm.nnz_base, fmt=args.format)
+        if idx == 0:          # outputs of one perturbed forward, element by element (not part of the timed baseline)
+            z = ophilox.zbar(args.seed, 0, m.nnz_base, m.sp_idx.size)
+            y_ref = olayer.linear_fwd(m.x_bits, m.codes, m.scales, m.group, m.sp_idx, m.sp_val, z, +1, cfg["eps"], lut=m.lut)
+            dm.sp_val.copy_(pristine[0])
+            y_buf = torch.empty((M, N), dtype=torch.float32, device="cuda")
+            d = dm.desc(dt, with_y=False)
+            d.y = y_buf.data_ptr()
+            szo.szo_linear_fwd(d, args.seed, 0, +1, cfg["eps"])
+            y_rel = rel_fro(y_buf.cpu().numpy(), y_ref)
+            del y_buf, y_ref
+        t0 = time.perf_counter()
+        r = ozo.zo_step([m], args.seed, 0, cfg["eps"], cfg["lr"])
+        t_spent += time.perf_counter() - t0
+        ref.append((r["loss_plus"], r["loss_minus"], r["g"]))
+        done_flops += 2 * 2.0 * M * N * K
+        used.append(f"L{layer}.{name}")
         if t_spent >= args.cpu_seconds:
             break
     frac = done_flops / total_flops_per_step
     est_step_s = t_spent / frac
-    return {"value": 1.0 / est_step_s, "unit": "ZO steps/s", "cores": int(threads), "kind": "oracle",
+    base = {"value": 1.0 / est_step_s, "unit": "ZO steps/s", "cores": int(threads), "kind": "oracle",
             "sample": f"full oracle ZO step (fp64) on the first {len(used)} matrices of the stack ({used[0]} .. {used[-1]}) "
                       f"at M={M}: {t_spent:.2f} s for {100 * frac:.3f}% of one step's FLOPs, extrapolated by FLOPs",
             "cpu": platform.processor() or platform.machine(), "os_cpu_count": os.cpu_count()}
+    # the GPU on the same sample
+    ws = szo.new_workspace()
+    scal = torch.zeros(3, dtype=torch.float64, device="cuda")
+    got = []
+    for idx in range(len(ref)):
+        mats[idx].sp_val.copy_(pristine[idx])
+        szo.szo_zo_step([mats[idx].desc(dt, with_y=False)], args.seed, 0, cfg["eps"], 0.0, scal, ws, szo.STEP_FUSED_LOSS)
+        got.append(scal.cpu().tolist())
+    ref, got = np.array(ref), np.array(got)
+    parity = {"y_rel": y_rel,
+              "loss_rel": float(np.max(np.abs(got[:, :2] - ref[:, :2]) / ref[:, :2])),
+              "g_rel": float(np.linalg.norm(got[:, 2] - ref[:, 2]) / max(np.linalg.norm(ref[:, 2]), 1e-300)),
+              "sample": f"the baseline's {len(ref)} matrices: y of one +eps forward of {used[0]} (relative Frobenius error), "
+                        "per-matrix L+ and L- (largest relative error), per-matrix SPSA scalars g_i = (L+ - L-) / (2 eps) "
+                        "(||g_gpu - g_oracle|| / ||g_oracle|| over the sample)",
+              "tolerance": {"y_rel": 5e-3, "g_rel": 1e-2}}
+    return base, parity
 
 
 def host_rebuild(args):
@@ -108,91 +244,6 @@ def host_rebuild(args):
         total += t4 - t0
     print(json.dumps({"host_rebuild_s_per_block": total, "blocks_per_s": 1.0 / total, "threads": os.cpu_count(),
                       "workload": args.workload, "per_matrix": rows}), flush=True)
-
-
-def vendor_gemm(args):
-    """Not part of the path: torch.matmul (hipBLASLt / rocBLAS) on x [M,K] times W^T with W [N,K] already
-    in 16 bits, i.e. the dense product of the SparseAdd-then-DenseMM form without dequantisation, sparse
-    add, loss or update."""
-    import torch
-    from paper_2406_02913_amd import synth
-    cfg = synth.WORKLOADS[args.workload]
-    M = args.m or cfg["M"]
-    dt = torch.float16 if args.tile == "f16" else torch.bfloat16
-    rows, total_us, total_flops = [], 0.0, 0.0
-    torch.manual_seed(0)
-    for name, N, K in cfg["block"]:
-        for data in ("random", "zeros"):
-            if data == "random":
-                x = torch.randn(M, K, device="cuda").to(dt)
-                w = (0.02 * torch.randn(N, K, device="cuda")).to(dt)
-            else:
-                x = torch.zeros(M, K, device="cuda", dtype=dt)
-                w = torch.zeros(N, K, device="cuda", dtype=dt)
-            for _ in range(30):
-                y = x @ w.t()
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(50):
-                y = x @ w.t()
-            e1.record()
-            torch.cuda.synchronize()
-            us = 1e3 * e0.elapsed_time(e1) / 50
-            rows.append({"matrix": name, "M": M, "N": N, "K": K, "operands": data, "us": round(us, 1),
-                         "tflops": round(2.0 * M * N * K / us / 1e6, 1)})
-            if data == "random":
-                total_us += us
-                total_flops += 2.0 * M * N * K
-            del x, w, y
-    print(json.dumps({"vendor_dense_gemm": rows, "dtype": args.tile, "workload": args.workload,
-                      "block_us_random": round(total_us, 1),
-                      "block_tflops_random": round(total_flops / total_us / 1e6, 1)}), flush=True)
-
-
-def operand_sensitivity(args):
-    """Not the benchmark: the same fused step on a few blocks of the workload, timed with the synthetic
-    operands and again after x and / or the codes have been overwritten with zeros.  Matrix cores draw
-    power by the bits that toggle, so the difference is what the clock management takes; the all-zero
-    figure is what the kernel's instruction schedule alone allows."""
-    import torch
-    from paper_2406_02913_amd import stack, synth, szo
-    torch.cuda.set_device(0)
-    szo.szo_set_tile_config(3 if args.tile_config == 0 else args.tile_config)
-    dt = szo.TILE_F16 if args.tile == "f16" else szo.TILE_BF16
-    mats, cfg = stack.build_stack(args.workload, args.data_seed, "cuda", M=args.m, layers=args.layers or 4,
-                                  density=args.density)
-    descs = szo.desc_array([m.desc(dt, with_y=False) for m in mats])
-    ws = szo.new_workspace()
-    scal = torch.zeros(3, dtype=torch.float64, device="cuda")
-    flops = sum(2 * 2.0 * m.M * m.N * m.K for m in mats)
-    rows = []
-
-    def timed(tag):
-        for s in range(5):
-            szo.szo_zo_step(descs, args.seed, s, cfg["eps"], 0.0, scal, ws, szo.STEP_FUSED_LOSS)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for s in range(20):
-            szo.szo_zo_step(descs, args.seed, s, cfg["eps"], 0.0, scal, ws, szo.STEP_FUSED_LOSS)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / 20
-        rows.append({"operands": tag, "ms_per_step": round(ms, 3), "tflops": round(flops / ms / 1e9, 1)})
-
-    timed("synthetic x, synthetic codes")
-    for m in mats:
-        m.x.zero_()
-    timed("zero x, synthetic codes")
-    for m in mats:
-        m.qweight.fill_(0x88)
-    timed("zero x, zero codes")
-    for m in mats:
-        m.x.normal_()
-    timed("random x, zero codes")
-    print(json.dumps({"operand_sensitivity": rows, "workload": args.workload, "blocks": args.layers or 4,
-                      "M": mats[0].M, "dtype": args.tile, "lr": 0.0}), flush=True)
 
 
 def main():
@@ -224,19 +275,11 @@ def main():
     ap.add_argument("--seed", type=int, default=2024)
     ap.add_argument("--data-seed", type=int, default=0)
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle baseline leg (0 = skip)")
-    ap.add_argument("--kernel-reps", type=int, default=None,
-                    help="extra steps run with per-launch kernel timing switched on (default: as many as --steps)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="default invocation only: skip the few-token, Mistral-block and OPT-stack legs (profiling runs)")
     ap.add_argument("--host-rebuild", action="store_true",
                     help="instead of the benchmark: time the host-side bookkeeping of a mask change (new mask -> tile "
                          "order -> re-split and re-quantise -> banded layout) for one block of the workload and exit")
-    ap.add_argument("--vendor-gemm", action="store_true",
-                    help="instead of the benchmark: time the vendor library's plain dense 16-bit GEMM (torch.matmul) on "
-                         "the workload's shapes with random and with all-zero operands and exit (context for the "
-                         "roofline: what a dense product on already materialised weights reaches on this machine)")
-    ap.add_argument("--operand-sensitivity", action="store_true",
-                    help="instead of the benchmark: time the fused step on --layers (default 4) blocks with the synthetic "
-                         "operands and with x and / or the codes zeroed, and exit (how much of the step time is the "
-                         "data-dependent power draw of the matrix cores, how much the kernel's own schedule)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark: copy a buffer of this many MiB five times with a plain copy kernel "
                          "and exit (known traffic, to scale the FETCH_SIZE / WRITE_SIZE counters of a profiler run)")
@@ -254,12 +297,6 @@ def main():
     if args.host_rebuild:
         host_rebuild(args)
         return
-    if args.vendor_gemm:
-        vendor_gemm(args)
-        return
-    if args.operand_sensitivity:
-        operand_sensitivity(args)
-        return
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
         sys.exit(2)
@@ -267,6 +304,10 @@ def main():
     import torch
     from paper_2406_02913_amd import stack, synth, szo
 
+    # the default invocation (the headline workload, untouched) also reports the other workloads
+    default_run = (args.workload == "c3" and args.layers is None and args.m is None and args.density is None
+                   and not args.unfused_loss and not args.two_activation_sets and not args.one_dense_pass
+                   and args.tile == "f16" and args.tile_config == 0 and args.format == "uniform")
     few_default = few_token_path(args.m or synth.WORKLOADS[args.workload]["M"], args.two_activation_sets)
     if args.steps is None:
         args.steps = 200 if few_default else 20
@@ -294,98 +335,68 @@ def main():
     torch.cuda.synchronize()
     log(f"[bench] {len(mats)} matrices resident after {time.perf_counter() - t0:.1f} s, "
         f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB")
+    pristine = [m.sp_val.clone() for m in mats]          # the parity leg starts from the initial sparse values
 
     if args.two_activation_sets:
         gen = torch.Generator(device="cuda").manual_seed(args.data_seed + 7)
         for m in mats:
             m.x_minus = torch.randn(m.x.shape, device="cuda", generator=gen).to(torch.bfloat16)
     szo.szo_set_tile_config(args.tile_config)
-    descs = szo.desc_array([m.desc(dt, with_y=bool(args.unfused_loss)) for m in mats])
-    ws = szo.new_workspace()
-    scal = torch.zeros(3, dtype=torch.float64, device="cuda")
-    eps, lr = cfg["eps"], cfg["lr"]
-    stream = torch.cuda.current_stream()
-
-    def one_step(s):
-        szo.szo_zo_step(descs, args.seed, s, eps, lr, scal, ws, flags, stream.cuda_stream)
-
-    for s in range(args.warmup):
-        one_step(s)
-    torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    w0 = time.perf_counter()
-    ev0.record(stream)
-    for s in range(args.warmup, args.warmup + args.steps):
-        one_step(s)
-    ev1.record(stream)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - w0
-    ms_per_step = ev0.elapsed_time(ev1) / args.steps
-    lp, lm, g = scal.cpu().tolist()
-    log(f"[bench] {ms_per_step:.3f} ms/step (events), {1e3 * wall / args.steps:.3f} ms/step (wall); "
-        f"last step L+={lp:.6f} L-={lm:.6f} g={g:.4e}")
-
-    # ---- the dominant kernel alone: the library brackets every forward-kernel launch of a few more
-    #      steps with events on the launch stream (szo_kernel_timing) ----
-    fwd_flops = sum(2.0 * m.M * m.N * m.K for m in mats)
-    few = (all((few_token_path(m.M, args.two_activation_sets) or args.one_dense_pass) and m.K % 128 == 0 for m in mats) and dt == szo.TILE_F16
-           and args.tile_config in (0, 4, 5) and bool(flags))                            # the library's few-token path
-    reps = args.steps if args.kernel_reps is None else max(1, args.kernel_reps)
-    szo.szo_kernel_timing(True)
-    for s in range(reps):
-        one_step(args.warmup + args.steps + s)
-    (k_total_ms, launches), (u_total_ms, u_launches) = szo.szo_kernel_timing_read2()
-    szo.szo_kernel_timing(False)
-    k_ms = k_total_ms / launches
-    if few:
-        # one launch streams every matrix once and serves both signs
-        kernel = "small_m_kernel"
-        launch_bytes = float(sum(algorithmic_bytes_fwd(m, fused=bool(flags)) for m in mats)) * reps / launches
-        launch_flops = 2 * fwd_flops * reps / launches
-    else:
-        # large fused steps run every forward of the step in one table-driven launch
-        kernel = "linear_fwd_table_kernel" if launches == reps else "linear_fwd_kernel"
-        launch_bytes = float(sum(algorithmic_bytes_fwd(m, fused=bool(flags)) for m in mats)) * 2 * reps / launches
-        launch_flops = 2 * fwd_flops * reps / launches
-    tflops = launch_flops / (k_ms * 1e-3) / 1e12
-    gbs = launch_bytes / (k_ms * 1e-3) / 1e9
-    mfma_bound = (launch_flops / launch_bytes) > (PEAK_MFMA_16BIT_TFLOPS * 1e12) / (PEAK_HBM_GBS * 1e9)
-    if mfma_bound:
-        roof = {"bound": "mfma", "achieved": round(tflops, 2), "peak": PEAK_MFMA_16BIT_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(tflops / PEAK_MFMA_16BIT_TFLOPS, 4), "traffic": None}
-    else:
-        roof = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None}
-    if (args.layers is None and args.m is None and args.density is None and flags and dt == szo.TILE_F16
-            and args.tile_config == 0 and args.format == "uniform"):
-        roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(args.workload)
-    roof.update({"kernel": kernel, "avg_launch_us": round(1e3 * k_ms, 2), "launches_timed": launches,
-                 "flops_per_launch": launch_flops, "bytes_per_launch": launch_bytes})
-    # the sparse update: 8 bytes per sensitive entry (fp32 value read and written); z is regenerated
-    upd = None
-    if u_launches:
-        u_ms = u_total_ms / u_launches
-        u_bytes = 8.0 * sum(m.nnz for m in mats) * reps / u_launches
-        upd = {"kernel": "sparse_update", "avg_launch_us": round(1e3 * u_ms, 2), "launches_timed": u_launches,
-               "bytes_per_launch": u_bytes, "achieved": round(u_bytes / (u_ms * 1e-3) / 1e9, 1), "unit": "GB/s",
-               "frac_of_hbm_peak": round(u_bytes / (u_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
-    step_flops = 2 * fwd_flops
-    log(f"[bench] {kernel}: {1e3 * k_ms:.1f} us/launch avg over {launches} launches, {tflops:.1f} TFLOP/s, "
-        f"{gbs:.1f} GB/s algorithmic")
-
-    base = None
-    if args.cpu_seconds > 0:
-        base = cpu_baseline(cfg, args, step_flops)
-        log(f"[bench] oracle baseline: {base['value']:.3e} steps/s on {base['cores']} threads")
-
     M = mats[0].M
+    descs = szo.desc_array([m.desc(dt, with_y=bool(args.unfused_loss)) for m in mats])
+    eps, lr = cfg["eps"], cfg["lr"]
+
+    t = time_steps(szo, torch, descs, args.seed, eps, lr, flags, args.steps, args.warmup)
+    ms_per_step = t["ms_per_step"]
+    lp, lm, g = t["last"]
+    log(f"[bench] {ms_per_step:.3f} ms/step (events), {t['wall_ms_per_step']:.3f} ms/step (wall); "
+        f"last step L+={lp:.6f} L-={lm:.6f} g={g:.4e}")
+    few = (all((few_token_path(m.M, args.two_activation_sets) or args.one_dense_pass) and m.K % 128 == 0 for m in mats)
+           and dt == szo.TILE_F16 and args.tile_config in (0, 4, 5) and bool(flags))        # the library's few-token path
+    traffic = MEASURED_TRAFFIC_BYTES.get(args.workload) if (
+        args.layers is None and args.m is None and args.density is None and flags and dt == szo.TILE_F16
+        and args.tile_config == 0 and args.format == "uniform" and not args.two_activation_sets
+        and not args.one_dense_pass) else None
+    roof, upd, step_flops = rooflines(mats, M, t, few, bool(flags), traffic)
+    log(f"[bench] {roof['kernel']}: {roof['avg_launch_us']:.1f} us/launch avg over {roof['launches_timed']} launches of the "
+        f"timed steps, {roof['achieved']} {roof['unit']}")
+
+    extras = {}
+    if default_run and not args.no_extras:
+        # the second target: the same resident stack at 16 tokens (first 16 rows of every x and target)
+        d16 = descs_for(szo, mats, 16, dt, with_y=False)
+        t16 = time_steps(szo, torch, d16, args.seed, eps, lr, flags, 200, 30, first_step=1000)
+        r16, u16, _ = rooflines(mats, 16, t16, True, True, MEASURED_TRAFFIC_BYTES.get("c3m16"))
+        extras["few_token"] = {"workload": f"the same {len(mats)} matrices at M=16 tokens (the first 16 rows of every x and target)",
+                               "ms_per_step": round(t16["ms_per_step"], 4), "value": round(1e3 / t16["ms_per_step"], 2),
+                               "unit": "ZO steps/s", "steps": 200, "warmup": 30, "roofline": r16, "sparse_update": u16}
+        log(f"[bench] few_token: {t16['ms_per_step']:.4f} ms/step, small_m_kernel {r16['achieved']} GB/s "
+            f"({100 * r16['frac']:.1f} % of the HBM peak)")
+
+    base = parity = None
+    if args.cpu_seconds > 0:
+        base, parity = cpu_baseline_and_parity(szo, torch, mats, pristine, cfg, args, step_flops, dt)
+        log(f"[bench] oracle baseline: {base['value']:.3e} steps/s on {base['cores']} threads; parity {parity['y_rel']:.2e} (y), "
+            f"{parity['loss_rel']:.2e} (losses), {parity['g_rel']:.2e} (g)")
+
+    n_mats, n_blocks = len(mats), len(mats) // len(cfg["block"])
+    if default_run and not args.no_extras:
+        del mats, descs, pristine, d16
+        torch.cuda.empty_cache()
+        extras["c4"] = {"workload": "one Mistral-7B block (q, k, v, o, gate, up, down), M=8192 tokens, int4 group 128, uniform mask",
+                        "runs": extra_workload(szo, torch, stack, "c4", args.seed, args.data_seed, dt,
+                                               [{"density": 1e-4}, {"density": 1e-3}, {"density": 1e-2}])}
+        extras["c5"] = {"workload": "32 OPT-6.7B blocks (q, k, v, o, fc1, fc2), int4 group 128, uniform mask 0.001",
+                        "runs": extra_workload(szo, torch, stack, "c5", args.seed, args.data_seed, dt,
+                                               [{"M": 1}, {"M": 16}, {"M": 64}], layers=32, M=64)}
+
     out = {
         "metric": "ZO steps/sec + % bf16 MFMA peak, int4+0.1%-sparse linears, Llama-2-7B shapes",
         "value": round(1e3 / ms_per_step, 4), "unit": "ZO steps/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None,
         "dtype": "f16" if dt == szo.TILE_F16 else "bf16", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {len(mats)} matrices ({len(mats) // len(cfg['block'])} block(s) of "
+        "config": {"workload": f"{args.workload}: {n_mats} matrices ({n_blocks} block(s) of "
                                f"{[b[0] for b in cfg['block']]}), M={M} tokens, "
                                + (f"int4 group {cfg['group']}, " if args.format == "uniform" else "4-bit table format, ") +
                                f"mask {cfg['density']:g} {cfg['mask']}, eps={eps}, lr={lr}",
@@ -399,7 +410,9 @@ def main():
         "roofline": roof,
         "sparse_update": upd,
         "cpu_baseline": base,
+        "parity": parity,
     }
+    out.update(extras)
     print(json.dumps(out), flush=True)
 
 

@@ -54,8 +54,16 @@ extern "C" {
 #define SZO_TILE_COLS   64
 
 /* 16-bit type the dequantised weight tile and the activations are staged in
- * before the matrix-core product. */
-#define SZO_TILE_F16   0   /* default: keeps eps*z within the estimator's error budget */
+ * before the matrix-core product.
+ *   SZO_TILE_F16 (default) keeps w_sparse +- eps*z within the estimator's error budget (11-bit
+ *   significand), but NARROWS THE ACTIVATION DOMAIN: the bf16 activations are converted to fp16 with
+ *   truncation, which is exact only for 2^-14 <= |x| <= 65504.  Larger magnitudes saturate at
+ *   +-65504 (infinities stay infinite), smaller ones lose low bits and vanish below 2^-24; no error
+ *   is raised.  A caller whose activations may leave that range (outlier channels of a real model)
+ *   measures them with szo_activation_absmax() and takes what szo_choose_tile_dtype() returns.
+ *   SZO_TILE_BF16 stages the activations unchanged (full bf16 range); the sensitive values are then
+ *   rounded to 8 significant bits, which costs about 1-2 % of sigma_g on the SPSA scalar. */
+#define SZO_TILE_F16   0
 #define SZO_TILE_BF16  1
 
 /* One linear layer.  Plain data; filled by the caller for every call. */
@@ -65,7 +73,7 @@ typedef struct szo_linear_desc {
   int32_t  tile_dtype;     /* SZO_TILE_F16 or SZO_TILE_BF16                             */
   int64_t  nnz;            /* number of sensitive entries of this matrix (may be 0)     */
   uint64_t nnz_base;       /* global index of entry 0; multiple of 4                    */
-  const void*     x;        /* device, bf16  [M,K]                                      */
+  const void*     x;        /* device, bf16  [M,K]; with SZO_TILE_F16: |x| <= 65504 (see above) */
   const uint8_t*  qweight;  /* device, u4x2, banded layout (below), szo_qweight_bytes(N,K) */
   const void*     scales;   /* device, fp16, banded layout (below), szo_scales_count()     */
   const uint32_t* tile_ptr; /* device, u32   [szo_num_tiles(N,K) + 1]                   */
@@ -151,11 +159,14 @@ int szo_sparse_update(float* sp_val, const uint32_t* sp_idx, int64_t nnz, uint64
  * 32 token rows beat rows of 256-row tiles) stream the weights once per 16 or 32 token rows, each
  * pass serving both signs.
  * descs: host array, read before the call returns.  Everything is enqueued on `stream`.  The
- * descriptor tables travel through a ring of four pinned host buffers (allocated on first use,
- * per host thread); a call waits on the host only if the copy of the call four steps earlier on
- * this thread has not executed yet.  Because of those buffers and that wait, a fused-loss step is
- * not meant to be captured into a HIP graph; the single-layer calls above are plain launches.
- * The workspace must not be shared with a call running concurrently on another stream. */
+ * descriptor tables of the grouped launches (forwards of a fused step; the update of every step)
+ * travel through a ring of eight pinned host buffers per host thread (allocated on first use,
+ * released when the thread ends); a call waits on the host only if a copy issued eight tables
+ * earlier on this thread (four tiled steps) has not executed yet.  Because of those buffers NO
+ * variant of this call can be captured into a HIP graph: it returns SZO_EUNSUPPORTED, with nothing
+ * enqueued, while `stream` is capturing.  The single-layer calls above are plain launches and can
+ * be captured.  The workspace must not be shared with a call running concurrently on another
+ * stream. */
 #define SZO_STEP_FUSED_LOSS 1
 /* Bit 1 (with bit 0): take the slicing path of the few-token case at ANY token count.  Both forwards of
  * a layer see the same x in this call, so y(+-) = x (dq + v)^T +- eps x z^T: the dense product is
@@ -224,6 +235,15 @@ int szo_layout_weights(const uint8_t* q, const uint16_t* scales, int64_t N, int6
                        uint8_t* q_banded, uint16_t* scales_banded);
 
 /* ---- inspection ----------------------------------------------------------------------- */
+
+/* Largest |x| of `count` bf16 values (device), written as fp32 to *absmax_out (device, 4-byte aligned);
+ * NaN if any value is NaN, +inf if any is infinite, 0 for count == 0.  Enqueued on `stream`. */
+int szo_activation_absmax(const void* x /* device bf16 */, int64_t count, float* absmax_out /* device */,
+                          void* stream);
+
+/* Host rule for the tile type: SZO_TILE_F16 if every activation converts to fp16 without saturating
+ * (x_absmax <= 65504), else SZO_TILE_BF16; SZO_EINVAL for a negative or NaN argument. */
+int szo_choose_tile_dtype(float x_absmax);
 
 /* Timing of the forward kernels (the tiled kernel and the few-token kernel) for benchmarks.
  * szo_kernel_timing(1) makes every later forward-kernel launch record a pair of events around

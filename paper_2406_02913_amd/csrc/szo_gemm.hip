@@ -845,12 +845,10 @@ static int launch(FwdParams& p, hipStream_t stream) {
   constexpr size_t target_bytes = FUSE ? (size_t)BM * (BN * 2 + 32) : 0;      // staged target tile of the fused loss
   constexpr size_t lds_bytes = main_bytes > target_bytes ? main_bytes : target_bytes;
   auto kern = linear_fwd_kernel<WAVES_M, WAVES_N, WMB, WNB, DT, FUSE, FMT>;
-  static bool attr_set = false;     // per instantiation
-  if (!attr_set) {
-    SZO_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
-    attr_set = true;
-  }
-  int rc = timing_begin(stream);
+  static std::atomic<uint64_t> lds_limit_set{0};     // per instantiation
+  int rc = set_lds_limit_once(lds_limit_set, (const void*)kern, lds_bytes);
+  if (rc != SZO_OK) return rc;
+  rc = timing_begin(stream);
   if (rc != SZO_OK) return rc;
   kern<<<(unsigned)blocks, 64 * WAVES_M * WAVES_N, lds_bytes, stream>>>(p);
   SZO_LAUNCH_CHECK();
@@ -941,12 +939,10 @@ static int launch_table(const FwdParams* table_dev, int entries, int64_t blocks,
   constexpr size_t target_bytes = (size_t)BM * (BN * 2 + 32);
   constexpr size_t lds_bytes = main_bytes > target_bytes ? main_bytes : target_bytes;
   auto kern = linear_fwd_table_kernel<2, WAVES_N, WMB, 2, DT, true, FMT>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    SZO_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
-    attr_set = true;
-  }
-  int rc = timing_begin(stream);
+  static std::atomic<uint64_t> lds_limit_set{0};
+  int rc = set_lds_limit_once(lds_limit_set, (const void*)kern, lds_bytes);
+  if (rc != SZO_OK) return rc;
+  rc = timing_begin(stream);
   if (rc != SZO_OK) return rc;
   kern<<<(unsigned)blocks, 128 * WAVES_N, lds_bytes, stream>>>(table_dev, entries);
   SZO_LAUNCH_CHECK();
@@ -1065,6 +1061,9 @@ int szo_zo_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t ste
                 double* scalars, void* workspace, int flags, void* stream) {
   if (n < 0 || (n > 0 && !descs) || !scalars || !workspace || ((uintptr_t)workspace & 7)) return SZO_EINVAL;
   hipStream_t s = (hipStream_t)stream;
+  // The step's descriptor tables travel through pinned host buffers that later calls reuse: a captured
+  // step would replay stale tables.
+  if (stream_is_capturing(s)) return SZO_EUNSUPPORTED;
   const bool fuse = flags & SZO_STEP_FUSED_LOSS;
   int64_t total = 0;                // workgroups = loss partials of one pass
   for (int i = 0; i < n; ++i) {     // reject everything before anything is enqueued
@@ -1107,7 +1106,7 @@ int szo_zo_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t ste
   if (!grouped) {
     if (fuse && 2 * total > kMaxLossPartials) return SZO_EUNSUPPORTED;
     if (!fuse) {
-      rc = zero_words(scalars, 6, s);      // a fill kernel, not a memset node: safe under graph capture
+      rc = zero_words(scalars, 6, s);
       if (rc != SZO_OK) return rc;
     }
     for (int pass = 0; pass < 2; ++pass) {

@@ -5,6 +5,7 @@
 #include "szo.h"
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstring>
 #include <numeric>
@@ -221,7 +222,7 @@ int szo_quantize_pack(const float* W, int64_t N, int64_t K, int group, const uin
     for (int64_t j = 0; j < nnz; ++j) cols[fill[mask_flat[j] / (uint64_t)K]++] = (uint32_t)(mask_flat[j] % (uint64_t)K);
   }
   const int64_t groups = K / group;
-  int bad = 0;
+  std::atomic<int> bad{0};          // set by any worker thread
   parallel_rows(N, K, [&](int64_t lo, int64_t hi) {
     std::vector<float> row((size_t)K);
     for (int64_t n = lo; n < hi; ++n) {
@@ -232,7 +233,7 @@ int szo_quantize_pack(const float* W, int64_t N, int64_t K, int group, const uin
         float mx = 0.0f;
         for (int i = 0; i < group; ++i) mx = std::max(mx, std::fabs(w[i]));
         const uint16_t sb = f32_to_f16_bits(mx / 7.0f);
-        if ((sb & 0x7C00u) == 0x7C00u) bad = 1;              // inf / nan scale
+        if ((sb & 0x7C00u) == 0x7C00u) bad.store(1, std::memory_order_relaxed);              // inf / nan scale
         scales_out[n * groups + g] = sb;
         const float s = f16_bits_to_f32(sb);
         uint8_t* q = q_out + (n * K + g * group) / 2;
@@ -248,7 +249,7 @@ int szo_quantize_pack(const float* W, int64_t N, int64_t K, int group, const uin
       }
     }
   });
-  return bad ? SZO_EINVAL : SZO_OK;
+  return bad.load() ? SZO_EINVAL : SZO_OK;
 }
 
 int szo_quantize_pack_lut(const float* W, int64_t N, int64_t K, const uint32_t* mask_flat, int64_t nnz,
@@ -270,7 +271,7 @@ int szo_quantize_pack_lut(const float* W, int64_t N, int64_t K, const uint32_t* 
     std::vector<uint32_t> fill(row_start.begin(), row_start.end() - 1);
     for (int64_t j = 0; j < nnz; ++j) cols[fill[mask_flat[j] / (uint64_t)K]++] = (uint32_t)(mask_flat[j] % (uint64_t)K);
   }
-  int bad = 0;
+  std::atomic<int> bad{0};          // set by any worker thread
   parallel_rows(N, 8 * K, [&](int64_t lo, int64_t hi) {
     std::vector<float> row((size_t)K), sorted((size_t)K);
     for (int64_t n = lo; n < hi; ++n) {
@@ -281,7 +282,7 @@ int szo_quantize_pack_lut(const float* W, int64_t N, int64_t K, const uint32_t* 
       double centroid[16];
       for (int c = 0; c < 16; ++c) {
         const uint16_t b = f32_to_f16_bits(sorted[(size_t)((2 * c + 1) * (K / 32))]);
-        if ((b & 0x7C00u) == 0x7C00u) bad = 1;
+        if ((b & 0x7C00u) == 0x7C00u) bad.store(1, std::memory_order_relaxed);
         lut_out[n * 16 + c] = b;
         centroid[c] = (double)f16_bits_to_f32(b);
       }
@@ -302,7 +303,12 @@ int szo_quantize_pack_lut(const float* W, int64_t N, int64_t K, const uint32_t* 
       }
     }
   });
-  return bad ? SZO_EINVAL : SZO_OK;
+  return bad.load() ? SZO_EINVAL : SZO_OK;
+}
+
+int szo_choose_tile_dtype(float x_absmax) {
+  if (!(x_absmax >= 0.0f)) return SZO_EINVAL;                   // negative or NaN
+  return x_absmax <= 65504.0f ? SZO_TILE_F16 : SZO_TILE_BF16;   // largest finite fp16
 }
 
 size_t szo_qweight_bytes(int64_t N, int64_t K) {

@@ -3,6 +3,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <atomic>
 #include "szo.h"
 
 namespace szo {
@@ -17,6 +18,18 @@ inline int hip_failed(hipError_t e) {
 
 #define SZO_HIP(expr) do { if (::szo::hip_failed((expr))) return SZO_ELAUNCH; } while (0)
 #define SZO_LAUNCH_CHECK() SZO_HIP(hipGetLastError())
+
+// Raises a kernel's dynamic LDS limit once per device (`done` holds one bit per device id); safe to
+// call from several host threads.
+inline int set_lds_limit_once(std::atomic<uint64_t>& done, const void* fn, size_t bytes) {
+  int dev = 0;
+  SZO_HIP(hipGetDevice(&dev));
+  const uint64_t bit = 1ull << (dev & 63);
+  if (done.load(std::memory_order_acquire) & bit) return SZO_OK;
+  SZO_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+  done.fetch_or(bit, std::memory_order_release);
+  return SZO_OK;
+}
 
 // Loss workspace: a ticket counter (first 64 bytes) followed by one fp64 partial per
 // workgroup.  The last workgroup to finish adds the partials in index order, which makes
@@ -65,11 +78,15 @@ int timing_begin(hipStream_t stream, int kind = 0);
 int timing_end(hipStream_t stream);
 
 // Copies `bytes` (a multiple of 4) of host data into device memory `dst`, in stream order, without
-// blocking the host: the data goes through a ring of four pinned, device-mapped host buffers (grown
-// on demand with hipHostMalloc) and a small copy kernel reads it from there.  A kernel rather than a
+// blocking the host: the data goes through a ring of eight pinned, device-mapped host buffers per host
+// thread (grown on demand with hipHostMalloc, released when the thread ends) and a small copy kernel
+// reads it from there.  SZO_EUNSUPPORTED while `stream` is being captured into a graph.  A kernel rather than a
 // DMA copy because handing over from the copy engine to the compute queue costs more than reading a
 // few tens of KB over the host link.  Defined in szo_kernels.hip.
 int stage_table(const void* src, size_t bytes, void* dst, hipStream_t stream);
+
+// True while `stream` is being captured into a HIP graph.
+bool stream_is_capturing(hipStream_t stream);
 
 // Sets n 32-bit words to zero with a small kernel (defined in szo_kernels.hip).
 int zero_words(void* p, int n, hipStream_t stream);

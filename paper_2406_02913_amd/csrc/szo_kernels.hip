@@ -1,5 +1,6 @@
 // Small kernels of the step: the Gaussian inspection kernel, the stand-in MSE loss, the SPSA
 // scalar (Definition 1) and the sparse ZO-SGD update (Section 3.4, fixed-parameter update rule).
+#include <algorithm>
 #include <cstring>
 #include <vector>
 #include "szo_internal.h"
@@ -124,6 +125,18 @@ __global__ void __launch_bounds__(1024) reduce_step_kernel(const double* __restr
   }
 }
 
+// max |x| over bf16 values: the magnitude bits of non-negative floats order like unsigned integers, so
+// an integer atomic max of (bits & 0x7FFF) << 16 is the float maximum (NaN patterns compare above infinity
+// and come out as NaN).
+__global__ void __launch_bounds__(256) absmax_bf16_kernel(const uint16_t* __restrict__ x, int64_t count, uint32_t* out_bits) {
+  uint32_t m = 0u;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256)
+    m = max(m, (uint32_t)(x[i] & 0x7FFFu));
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, off, 64));
+  if ((threadIdx.x & 63) == 0 && m) atomicMax(out_bits, m << 16);
+}
+
 __global__ void zero_words_kernel(uint32_t* p, int n) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = 0u;
@@ -146,15 +159,35 @@ __global__ void __launch_bounds__(256) stage_copy_kernel(const uint32_t* __restr
   if (i < words) dst[i] = src[i];
 }
 
+// Pinned staging buffers of one host thread.  Eight slots: a tiled fused step stages two tables (its
+// forwards and its update), so the host may run four steps ahead of the GPU; a slot is reused only
+// after the copy kernel that read it has executed.  Released when the thread ends.
+namespace {
+struct StageSlot { void* host; const uint32_t* host_dev; size_t cap; hipEvent_t copied; bool used; };
+struct StageRing {
+  StageSlot slot[8] = {};
+  unsigned turn = 0;
+  ~StageRing() {
+    for (StageSlot& s : slot) {               // errors are ignored: the runtime may already be shutting down
+      if (s.used && s.copied) (void)hipEventSynchronize(s.copied);
+      if (s.copied) (void)hipEventDestroy(s.copied);
+      if (s.host) (void)hipHostFree(s.host);
+    }
+  }
+};
+}  // namespace
+
 int stage_table(const void* src, size_t bytes, void* dst, hipStream_t stream) {
   if (bytes == 0) return SZO_OK;
   if (bytes & 3) return SZO_EINVAL;
-  // A ring of four, so that the host may run a few steps ahead of the GPU; a slot is reused only
-  // after the copy kernel that read it has executed.
-  struct Slot { void* host; const uint32_t* host_dev; size_t cap; hipEvent_t copied; bool used; };
-  static thread_local Slot ring[4] = {};
-  static thread_local unsigned turn = 0;
-  Slot& slot = ring[turn++ & 3];
+  {
+    // A captured launch would replay the copy from a slot that later calls overwrite.
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    SZO_HIP(hipStreamIsCapturing(stream, &cap));
+    if (cap != hipStreamCaptureStatusNone) return SZO_EUNSUPPORTED;
+  }
+  static thread_local StageRing ring;
+  StageSlot& slot = ring.slot[ring.turn++ & 7];
   if (slot.used) SZO_HIP(hipEventSynchronize(slot.copied));
   if (!slot.copied) SZO_HIP(hipEventCreateWithFlags(&slot.copied, hipEventDisableTiming));
   if (bytes > slot.cap) {
@@ -172,6 +205,12 @@ int stage_table(const void* src, size_t bytes, void* dst, hipStream_t stream) {
   SZO_HIP(hipEventRecord(slot.copied, stream));
   slot.used = true;
   return SZO_OK;
+}
+
+bool stream_is_capturing(hipStream_t stream) {
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(stream, &cap) != hipSuccess) return false;
+  return cap != hipStreamCaptureStatusNone;
 }
 
 int zero_words(void* p, int n, hipStream_t stream) {
@@ -266,7 +305,7 @@ int szo_kernel_timing_read(double* total_ms, int64_t* launches) {
 }
 
 int szo_last_hip_error(void) { return g_last_hip_error; }
-int szo_version(void) { return 3; }
+int szo_version(void) { return 4; }
 size_t szo_workspace_bytes(void) { return kWorkspaceBytes; }
 
 int szo_workspace_init(void* workspace, void* stream) {
@@ -311,6 +350,17 @@ int szo_mse_loss(const float* y, const void* target, int64_t count, double scale
   blocks = blocks < 1 ? 1 : (blocks > kMseBlocks ? kMseBlocks : blocks);
   mse_kernel<<<(unsigned)blocks, kMseThreads, 0, (hipStream_t)stream>>>(
       y, (const uint16_t*)target, count, make_sink(workspace, loss_acc, scale), vec_ok);
+  SZO_LAUNCH_CHECK();
+  return SZO_OK;
+}
+
+int szo_activation_absmax(const void* x, int64_t count, float* absmax_out, void* stream) {
+  if (count < 0 || !absmax_out || ((uintptr_t)absmax_out & 3)) return SZO_EINVAL;
+  int rc = zero_words(absmax_out, 1, (hipStream_t)stream);
+  if (rc != SZO_OK || count == 0) return rc;
+  if (!x || ((uintptr_t)x & 1)) return SZO_EINVAL;
+  const int64_t blocks = std::min<int64_t>((count + 255) / 256, 2048);
+  absmax_bf16_kernel<<<(unsigned)blocks, 256, 0, (hipStream_t)stream>>>((const uint16_t*)x, count, (uint32_t*)absmax_out);
   SZO_LAUNCH_CHECK();
   return SZO_OK;
 }

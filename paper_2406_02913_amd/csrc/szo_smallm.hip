@@ -710,21 +710,17 @@ static void fill_mat(SmallMat& m, const szo_linear_desc* d) {
 }
 
 static int set_small_attrs() {
-  static bool attr_set = false;
-  if (!attr_set) {
-    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_FAST, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds_bytes(1)));
-    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_PLAIN, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds_bytes(1)));
-    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_LUT, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds_bytes(1)));
-    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_FAST, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds_bytes(2)));
-    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_PLAIN, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds_bytes(2)));
-    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_LUT, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds_bytes(2)));
-    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_FAST, 3>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds_bytes(3)));
-    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_PLAIN, 3>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds_bytes(3)));
-    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_LUT, 3>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds_bytes(3)));
-    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_FAST, 2, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds_bytes(2)));
-    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_PLAIN, 2, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds_bytes(2)));
-    SZO_HIP(hipFuncSetAttribute((const void*)small_m_kernel<SM_LUT, 2, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds_bytes(2)));
-    attr_set = true;
+  static std::atomic<uint64_t> done[12];
+  const void* const fn[12] = {
+      (const void*)small_m_kernel<SM_FAST, 1>, (const void*)small_m_kernel<SM_PLAIN, 1>, (const void*)small_m_kernel<SM_LUT, 1>,
+      (const void*)small_m_kernel<SM_FAST, 2>, (const void*)small_m_kernel<SM_PLAIN, 2>, (const void*)small_m_kernel<SM_LUT, 2>,
+      (const void*)small_m_kernel<SM_FAST, 3>, (const void*)small_m_kernel<SM_PLAIN, 3>, (const void*)small_m_kernel<SM_LUT, 3>,
+      (const void*)small_m_kernel<SM_FAST, 2, true>, (const void*)small_m_kernel<SM_PLAIN, 2, true>,
+      (const void*)small_m_kernel<SM_LUT, 2, true>};
+  const int rows[12] = {1, 1, 1, 2, 2, 2, 3, 3, 3, 2, 2, 2};
+  for (int i = 0; i < 12; ++i) {
+    const int rc = set_lds_limit_once(done[i], fn[i], small_lds_bytes(rows[i]));
+    if (rc != SZO_OK) return rc;
   }
   return SZO_OK;
 }
@@ -803,7 +799,9 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
     const szo_linear_desc* d = &descs[order[r]];
     const int rblocks = rblocks_of(d);
     const int cls = small_m_class(d, rblocks, dual_of(d));
-    const int slices = slices_of(d, rblocks, dual_of(d)), b = small_m_blocks(d);
+    // a layer without tokens or outputs has no workgroups; it keeps its table entry for the update
+    const bool live = d->M > 0 && d->N > 0;
+    const int slices = live ? slices_of(d, rblocks, dual_of(d)) : 0, b = live ? small_m_blocks(d) : 0;
     SmallMat& m = host[entries++];
     fill_mat(m, d);
     m.first_block = class_blocks[cls];
@@ -826,7 +824,7 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
   const SmallMat* tdev = (const SmallMat*)table_dev;
   int first_entry = 0;
   for (int cls = 0; cls < kSmallClasses; ++cls) {
-    if (do_forward && class_blocks[cls] > 0) {
+    if (do_forward && class_blocks[cls] > 0 && class_slices[cls] > 0) {
       a.table = tdev + first_entry; a.n_mats = class_entries[cls];
       a.slices = class_slices[cls];
       if ((rc = timing_begin(stream)) != SZO_OK) return rc;

@@ -62,6 +62,8 @@ _SIGS = {
     "szo_layout_weights": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_void_p, C.c_void_p]),
     "szo_philox4x32_10": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "szo_debug_zbar": (C.c_int, [C.c_uint64, C.c_int64, C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "szo_activation_absmax": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]),
+    "szo_choose_tile_dtype": (C.c_int, [C.c_float]),
     "szo_set_tile_config": (C.c_int, [C.c_int]),
     "szo_kernel_timing": (C.c_int, [C.c_int]),
     "szo_kernel_timing_read": (C.c_int, [C.c_void_p, C.c_void_p]),
@@ -254,6 +256,17 @@ def szo_philox4x32_10(ctr, key):
 def szo_debug_zbar(nnz_base, nnz, seed, step, words_out=None, z_out=None, stream=None):
     _check("szo_debug_zbar", lib.szo_debug_zbar(nnz_base, nnz, seed, step, _dev(words_out), _dev(z_out),
                                                 _stream(stream)))
+
+
+def szo_activation_absmax(x, count, absmax_out, stream=None):
+    _check("szo_activation_absmax", lib.szo_activation_absmax(_dev(x), count, _dev(absmax_out), _stream(stream)))
+
+
+def szo_choose_tile_dtype(x_absmax):
+    rc = lib.szo_choose_tile_dtype(x_absmax)
+    if rc < 0:
+        raise SzoError("szo_choose_tile_dtype", rc)
+    return rc
 
 
 def szo_set_tile_config(config):

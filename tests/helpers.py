@@ -88,10 +88,48 @@ def rel_fro(a, b):
 
 
 def sigma_g(mats):
-    """sqrt(sum |grad L on the mask|^2): the natural scale of g = z . grad L."""
+    """sqrt(sum |grad L on the mask|^2): the natural scale of g = z . grad L.  Small masks go through the
+    oracle's mse_grad_on_mask; for large ones (its gather would take M x nnz doubles) the same formula
+    dL/dW = (2 / (M N)) (y - t)^T x is evaluated as one dense product and read at the mask positions."""
     from oracle import layer
+    from oracle.quant import bf16_bits_to_f64
     tot = 0.0
     for m in mats:
         y0 = layer.linear_fwd(m.x_bits, m.codes, m.scales, m.group, m.sp_idx, m.sp_val, lut=m.lut)
-        tot += float(np.sum(layer.mse_grad_on_mask(m.x_bits, y0, m.target_bits, m.sp_idx, m.codes.shape[1]) ** 2))
+        M, K = m.x_bits.shape
+        if M * m.sp_idx.size <= (1 << 27):
+            grad = layer.mse_grad_on_mask(m.x_bits, y0, m.target_bits, m.sp_idx, K)
+        else:
+            r = (y0 - bf16_bits_to_f64(m.target_bits)) * (2.0 / y0.size)
+            grad = (r.T @ bf16_bits_to_f64(m.x_bits)).reshape(-1)[m.sp_idx.astype(np.int64)]
+        tot += float(np.sum(grad ** 2))
     return float(np.sqrt(tot))
+
+class UpdateBound:
+    """How far the sparse values may end up from the oracle's after some steps.  One step moves them by
+    -lr g z (Section 3.4, fixed-parameter update rule), so an error dg on the SPSA scalar moves matrix i
+    by lr |dg| ||z_i||, and the bar on g is |dg| <= 1e-2 max(|g|, sigma_g): for one step that is a
+    relative error of 1e-2 max(|g|, sigma_g) / |g| on the update.  Both sides store fp32 values, so one
+    ulp of the value per step comes on top."""
+
+    def __init__(self, sg, lr):
+        self.sg, self.lr, self.tol, self.steps = float(sg), float(np.float32(lr)), None, 0
+
+    def add(self, r, extra_dg=0.0):
+        """r: what the oracle's zo_step returned for this step (g and the per-matrix z); extra_dg: what
+        the test allows on g beyond the bar (two activation sets: the losses' own error over 2 eps)."""
+        dg = 1e-2 * max(abs(r["g"]), self.sg) + extra_dg
+        if self.tol is None:
+            self.tol = [0.0] * len(r["z"])
+        for i, z in enumerate(r["z"]):
+            self.tol[i] += self.lr * dg * float(np.linalg.norm(z))
+        self.steps += 1
+
+    def check(self, i, v_gpu, v_ref, v0):
+        v_gpu, v_ref = np.asarray(v_gpu, dtype=np.float64), np.asarray(v_ref, dtype=np.float64)
+        err = float(np.linalg.norm(v_gpu - v_ref))
+        allowed = self.tol[i] + self.steps * float(np.linalg.norm(np.spacing(np.abs(v_ref).astype(np.float32))))
+        moved = float(np.linalg.norm(v_ref - np.asarray(v0, dtype=np.float64)))
+        assert err <= allowed, (i, err, allowed, moved)
+        if self.lr > 0 and moved > 4 * allowed:       # the update is visible: the GPU's values moved too
+            assert float(np.linalg.norm(v_gpu - np.asarray(v0, dtype=np.float64))) >= 0.5 * moved

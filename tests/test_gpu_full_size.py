@@ -117,7 +117,7 @@ def test_opt_ffn_projections_decode_token_counts(M, cfg):
     """OPT-6.7B's two FFN matrices (16384 x 4096 and 4096 x 16384) at 1 / 16 / 64 tokens: one fused step
     on the few-token path against the oracle (losses, g, updated values)."""
     from oracle import zo as ozo
-    from helpers import clone, sigma_g
+    from helpers import clone, sigma_g, UpdateBound
     szo.szo_set_tile_config(cfg)                     # 4 / 5: the 64 tokens run as two passes of 32 / 48 rows, as in a full stack
     o1, d1 = make_pair(9, M, 16384, 4096, 128, 1e-3, nnz_base=0)
     base = (o1.sp_idx.size + 3) // 4 * 4
@@ -129,13 +129,13 @@ def test_opt_ffn_projections_decode_token_counts(M, cfg):
     szo.szo_zo_step([d1.desc(with_y=False), d2.desc(with_y=False)], 3, 0, 1e-3, 1e-4, scal, ws, szo.STEP_FUSED_LOSS)
     lp, lm, g = scal.cpu().numpy()
     r = ozo.zo_step(ref, 3, 0, 1e-3, 1e-4)
+    bound = UpdateBound(sg, 1e-4)
+    bound.add(r)
     assert abs(lp - r["loss_plus"]) <= 1e-4 * r["loss_plus"]
     assert abs(lm - r["loss_minus"]) <= 1e-4 * r["loss_minus"]
     assert abs(g - r["g"]) <= 1e-2 * max(abs(r["g"]), sg), (g, r["g"], sg)
-    for om, dd, o in zip(ref, (d1, d2), (o1, o2)):
-        dv_gpu = dd.sp_val.cpu().numpy().astype(np.float64) - o.sp_val
-        dv_ref = om.sp_val.astype(np.float64) - o.sp_val
-        assert np.linalg.norm(dv_gpu - dv_ref) <= 3e-2 * np.linalg.norm(dv_ref) + 1e-12
+    for i, (om, dd, o) in enumerate(zip(ref, (d1, d2), (o1, o2))):
+        bound.check(i, dd.sp_val.cpu().numpy(), om.sp_val, o.sp_val)
 
 
 def test_llama_block_step_in_the_benchmarks_launch_configuration():

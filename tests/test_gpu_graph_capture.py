@@ -11,6 +11,36 @@ from helpers import make_pair
 pytestmark = pytest.mark.gpu
 
 
+@pytest.mark.parametrize("flags", [0, szo.STEP_FUSED_LOSS])
+def test_whole_step_call_refuses_a_capturing_stream(flags):
+    """szo_zo_step stages descriptor tables through pinned host buffers that later calls reuse, so a
+    captured step would replay stale tables: while the stream is capturing it must return
+    SZO_EUNSUPPORTED with nothing enqueued (the captured graph stays empty and the values untouched)."""
+    szo.szo_set_tile_config(0)
+    _, d = make_pair(112, 16, 256, 256, 128, 5e-3)
+    ws = szo.new_workspace()
+    scal = torch.full((3,), 5.0, dtype=torch.float64, device="cuda")
+    v0 = d.sp_val.clone()
+    descs = szo.desc_array([d.desc()])
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        with pytest.raises(szo.SzoError) as err:
+            szo.szo_zo_step(descs, 1, 0, 1e-3, 1e-3, scal, ws, flags)
+        scal.add_(1.0)                                                # something to replay
+        graph.capture_end()
+    assert err.value.code == szo.EUNSUPPORTED
+    torch.cuda.synchronize()
+    graph.replay()
+    torch.cuda.synchronize()
+    assert scal.cpu().tolist() == [6.0, 6.0, 6.0] and torch.equal(v0, d.sp_val)
+    szo.szo_zo_step(descs, 1, 0, 1e-3, 1e-3, scal, ws, flags)         # and the eager call still works
+    torch.cuda.synchronize()
+    assert scal[0].item() > 0 and not torch.equal(v0, d.sp_val)
+
+
 @pytest.mark.parametrize("M", [16, 300])            # few-token kernel, tiled kernel
 def test_forward_loss_g_update_replay_from_a_graph(M):
     szo.szo_set_tile_config(0)

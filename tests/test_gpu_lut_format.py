@@ -8,7 +8,7 @@ import torch
 
 from oracle import layer as olayer, philox as ophilox, zo as ozo
 from paper_2406_02913_amd import szo
-from helpers import make_pair, clone, rel_fro, sigma_g
+from helpers import make_pair, clone, rel_fro, sigma_g, UpdateBound
 
 pytestmark = pytest.mark.gpu
 
@@ -89,17 +89,17 @@ def test_fused_loss_and_step_match_oracle():
         a, b = clone(o1), clone(o2)
         descs = szo.desc_array([da.desc(with_y=False), db.desc(with_y=False)])
         got = []
+        bound = UpdateBound(sg, lr)
         for s in range(3):
             szo.szo_zo_step(descs, seed, s, eps, lr, scal, ws, szo.STEP_FUSED_LOSS)
             lp, lm, g = scal.cpu().numpy()
             r = ozo.zo_step([a, b], seed, s, eps, lr)
+            bound.add(r)
             assert abs(lp - r["loss_plus"]) <= 5e-3 * r["loss_plus"]
             assert abs(g - r["g"]) <= 1e-2 * max(abs(r["g"]), sg), (cfg, s, g, r["g"])
             got.append((lp, lm, g))
-        for om, dd, oo in ((a, da, o1), (b, db, o2)):
-            dv_gpu = dd.sp_val.cpu().numpy().astype(np.float64) - oo.sp_val
-            dv_ref = om.sp_val.astype(np.float64) - oo.sp_val
-            assert np.linalg.norm(dv_gpu - dv_ref) <= 3e-2 * np.linalg.norm(dv_ref)
+        for i, (om, dd, oo) in enumerate(((a, da, o1), (b, db, o2))):
+            bound.check(i, dd.sp_val.cpu().numpy(), om.sp_val, oo.sp_val)
         results[cfg] = (got, da.sp_val.cpu().numpy(), db.sp_val.cpu().numpy())
     # same kernel body either way: bit-identical
     assert results[2][0] == results[3][0]
@@ -155,19 +155,19 @@ def test_few_token_step_with_all_three_instantiations(cfg):
     sg = sigma_g([o1, o2, o3])
     descs = szo.desc_array([d3.desc(with_y=False), d1.desc(with_y=False), d2.desc(with_y=False)])   # any order
     szo.szo_kernel_timing(True)
+    bound = UpdateBound(sg, lr)
     for s in range(3):
         szo.szo_zo_step(descs, seed, s, eps, lr, scal, ws, szo.STEP_FUSED_LOSS)
         lp, lm, g = scal.cpu().numpy()
         r = ozo.zo_step([c, a, b], seed, s, eps, lr)
+        bound.add(r)
         assert abs(lp - r["loss_plus"]) <= 5e-3 * r["loss_plus"]
         assert abs(g - r["g"]) <= 1e-2 * max(abs(r["g"]), sg), (s, g, r["g"])
     _, launches = szo.szo_kernel_timing_read()
     szo.szo_kernel_timing(False)
     assert launches == 9                          # few-token path: one launch per instantiation and step
-    for om, dd, oo in ((a, d1, o1), (b, d2, o2), (c, d3, o3)):
-        dv_gpu = dd.sp_val.cpu().numpy().astype(np.float64) - oo.sp_val
-        dv_ref = om.sp_val.astype(np.float64) - oo.sp_val
-        assert np.linalg.norm(dv_gpu - dv_ref) <= 3e-2 * np.linalg.norm(dv_ref)
+    for i, (om, dd, oo) in enumerate(((c, d3, o3), (a, d1, o1), (b, d2, o2))):      # the oracle's order of matrices
+        bound.check(i, dd.sp_val.cpu().numpy(), om.sp_val, oo.sp_val)
 
 
 @pytest.mark.parametrize("cfg", [0, 4, 5])

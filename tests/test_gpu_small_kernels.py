@@ -100,3 +100,45 @@ def test_update_and_forward_share_the_gaussian():
     z = torch.empty(nnz, dtype=torch.float32, device=DEV)
     szo.szo_debug_zbar(base, nnz, 5, 9, None, z)
     assert torch.equal(v, z)
+
+
+def test_activation_absmax_and_the_fp16_tiles_saturation():
+    """The fp16 tile truncates bf16 activations to fp16: beyond the largest finite fp16 they saturate at
+    +-65504 (documented in the header).  szo_activation_absmax measures the range on the device and
+    szo_choose_tile_dtype turns it into the tile type; the bf16 tile takes the same activations as they are."""
+    from oracle import layer as olayer
+    from oracle.quant import f32_to_bf16_bits
+    from helpers import make_pair, rel_fro
+    o, d = make_pair(151, 32, 256, 256, 128, 2e-3)
+    out = torch.zeros(1, dtype=torch.float32, device="cuda")
+    szo.szo_activation_absmax(d.x, d.M * d.K, out)
+    xf = (o.x_bits.astype(np.uint32) << 16).view(np.float32)
+    assert out.item() == float(np.abs(xf).max())
+    assert szo.szo_choose_tile_dtype(out.item()) == szo.TILE_F16
+    szo.szo_activation_absmax(d.x, 0, out)
+    assert out.item() == 0.0
+    # plant two outliers: 1e5 and -3e38 (both finite in bf16, both beyond fp16)
+    xb = o.x_bits.copy()
+    big = f32_to_bf16_bits(np.array([1.0e5, -3.0e38], dtype=np.float32))
+    xb[3, 17], xb[20, 200] = big[0], big[1]
+    d.x = torch.from_numpy(xb.view(np.int16)).view(torch.bfloat16).cuda()
+    szo.szo_activation_absmax(d.x, d.M * d.K, out)
+    assert out.item() == float(np.abs((big.astype(np.uint32) << 16).view(np.float32)).max())
+    assert szo.szo_choose_tile_dtype(out.item()) == szo.TILE_BF16
+    szo.szo_set_tile_config(2)                                     # the tiled kernel, both tile types
+    # fp16 tile: the result is that of activations clamped to +-65504
+    clamped = np.clip((xb.astype(np.uint32) << 16).view(np.float32), -65504.0, 65504.0)
+    y_ref16 = clamped.astype(np.float64) @ olayer.effective_weight(o.codes, o.scales, o.group, o.sp_idx, o.sp_val).T
+    szo.szo_linear_fwd(d.desc(szo.TILE_F16), 1, 0, 0, 0.0)
+    y16 = d.y.cpu().numpy()
+    assert np.isfinite(y16).all() and rel_fro(y16, y_ref16) <= 5e-3
+    # bf16 tile: the activations as they are
+    y_ref = olayer.linear_fwd(xb, o.codes, o.scales, o.group, o.sp_idx, o.sp_val)
+    szo.szo_linear_fwd(d.desc(szo.TILE_BF16), 1, 0, 0, 0.0)
+    ybf = d.y.cpu().numpy()
+    assert np.isfinite(ybf).all() and rel_fro(ybf, y_ref) <= 1e-2
+    szo.szo_set_tile_config(0)
+    # NaN in, NaN out of the range scan
+    xb[0, 0] = 0x7FC0
+    szo.szo_activation_absmax(torch.from_numpy(xb.view(np.int16)).view(torch.bfloat16).cuda(), d.M * d.K, out)
+    assert np.isnan(out.item())

@@ -21,8 +21,20 @@ def test_every_declared_symbol_is_exported():
     assert declared == set(szo.EXPORTS)
     for name in declared:
         assert getattr(szo.lib, name) is not None
-    assert szo.szo_version() == 3
+    assert szo.szo_version() == 4
     assert szo.szo_workspace_bytes() >= 64 + 8 * 1024
+
+
+def test_tile_type_rule_for_the_activation_range():
+    # the fp16 tile converts bf16 activations exactly only up to the largest finite fp16
+    assert szo.szo_choose_tile_dtype(0.0) == szo.TILE_F16
+    assert szo.szo_choose_tile_dtype(65504.0) == szo.TILE_F16
+    assert szo.szo_choose_tile_dtype(float(np.nextafter(np.float32(65504.0), np.float32(1e9)))) == szo.TILE_BF16
+    assert szo.szo_choose_tile_dtype(float("inf")) == szo.TILE_BF16
+    for bad in (-1.0, float("nan")):
+        with pytest.raises(szo.SzoError) as e:
+            szo.szo_choose_tile_dtype(bad)
+        assert e.value.code == szo.EINVAL
 
 
 def test_descriptor_layout_matches_header():
