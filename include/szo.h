@@ -178,6 +178,26 @@ int szo_sparse_update(float* sp_val, const uint32_t* sp_idx, int64_t nnz, uint64
 int szo_zo_step(const szo_linear_desc* descs /* host */, int n, uint64_t seed, uint64_t step,
                 float eps, float lr, double* scalars, void* workspace, int flags, void* stream);
 
+/* The same step for callers that cannot allocate: code running under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same inputs, same outputs as szo_zo_step with
+ * SZO_STEP_FUSED_LOSS (scalars = (L+, L-, g); every layer's sp_val updated; desc->y is not written),
+ * up to the order in which the fp64 loss partials are added.  It takes no workspace: the loss partials
+ * live in a fixed array inside the library (1 MiB per GPU, kept until the process ends), and it
+ * stages no descriptor table: every layer is one plain launch of the few-token kernel (when every
+ * layer of the step qualifies for it and none has x_minus), else one tiled launch per sign; then one
+ * reduction, and one update launch per layer.  It calls no
+ * allocating routine (no hipMalloc / hipHostMalloc, no event creation unless szo_kernel_timing is
+ * on) and can be captured into a HIP graph.
+ * Limit: at most 65 536 workgroups per sign over the whole step (one per 256 x 256 output tile, or
+ * per 128 x 128 tile for small layers, or per 256-column strip and slice of token rows of a few-token
+ * layer): beyond that SZO_EUNSUPPORTED, with nothing enqueued.  A Llama-2-7B decoder block at 4096
+ * tokens has 3 088 per sign.
+ * All calls on one GPU share that array: calls that overlap in time on one GPU (different streams
+ * or host threads) race on it.  Nothing in it needs clearing between calls (every partial that is
+ * read has been written by the same call). */
+int szo_zo_step_noalloc(const szo_linear_desc* descs /* host */, int n, uint64_t seed, uint64_t step,
+                        float eps, float lr, double* scalars /* device double[3] */, void* stream);
+
 /* Bytes of device workspace the loss-accumulating calls need (a constant). */
 size_t szo_workspace_bytes(void);
 

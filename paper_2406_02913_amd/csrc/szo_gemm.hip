@@ -26,7 +26,15 @@
 #include <vector>
 #include "szo_internal.h"
 #include "szo_rng.h"
+#include <mutex>
 #include <type_traits>
+
+// Loss partials of szo_zo_step_noalloc: one fp64 value per workgroup and sign, written by the forward
+// kernels and summed by reduce_step_kernel.  Lives in the code object, one copy per GPU, for callers
+// that cannot allocate a workspace.  Host code never uses this name as an address: it asks the runtime
+// for the array's device address once per device (noalloc_partials below).
+constexpr int kNoAllocMaxPartials = 1 << 17;                 // 1 MiB per GPU
+static __device__ __align__(256) double scratch[kNoAllocMaxPartials];
 
 namespace szo {
 
@@ -752,14 +760,14 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bi
   if (FUSE_LOSS) {
     // One scaled partial per workgroup, plain store: a later kernel on the same stream adds them
     // up in index order, so the kernel boundary is the only synchronisation needed.
-    __shared__ double scratch[NWAVES];
+    __shared__ double wave_part[NWAVES];
     const double w = wave_sum(loss);
-    if (lane == 0) scratch[wave] = w;
+    if (lane == 0) wave_part[wave] = w;
     __syncthreads();
     if (tid == 0) {
       double b = 0.0;
 #pragma unroll
-      for (int i = 0; i < NWAVES; ++i) b += scratch[i];
+      for (int i = 0; i < NWAVES; ++i) b += wave_part[i];
       p.partials[bid] = b * p.loss_scale;
     }
   }
@@ -1011,11 +1019,87 @@ static int grouped_forwards(const szo_linear_desc* descs, int n, uint64_t seed, 
   return launch_table<SZO_TILE_BF16>((const FwdParams*)table_dev, (int)table.size(), first_block, stream);
 }
 
+// Device address of `scratch` on the current device, looked up once per device.
+static int noalloc_partials(double** out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static double* ptr[kMaxDevices] = {};
+  int dev = 0;
+  SZO_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return SZO_EUNSUPPORTED;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    SZO_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return SZO_ELAUNCH;
+    ptr[dev] = (double*)p;
+  }
+  *out = ptr[dev];
+  return SZO_OK;
+}
+
 }  // namespace szo
 
 using namespace szo;
 
 extern "C" {
+
+int szo_zo_step_noalloc(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t step, float eps, float lr,
+                        double* scalars, void* stream) {
+  if (n < 0 || (n > 0 && !descs) || !scalars) return SZO_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  // Kernel choice as in szo_zo_step: the few-token kernel (one launch per layer, both signs) when every
+  // layer qualifies for it -- here also: no layer with a second activation set, which needs the grouped
+  // launch's dual kernel -- else the tiled kernel, one launch per layer and sign.
+  bool few_all = few_token_enabled() && n > 0;
+  for (int i = 0; few_all && i < n; ++i) {
+    if (descs[i].M <= 0 || descs[i].N <= 0) continue;
+    few_all = !descs[i].x_minus && small_m_step_eligible(&descs[i]);
+  }
+  auto few_one = [few_all](const szo_linear_desc*) { return few_all; };
+  int64_t T = 0;
+  for (int i = 0; i < n; ++i) {     // reject everything before anything is enqueued
+    const szo_linear_desc* d = &descs[i];
+    const int rc = validate_desc(d, 1, false, true);
+    if (rc != SZO_OK) return rc;
+    if (d->nnz > 0 && (!d->sp_val || ((uintptr_t)d->sp_val & 15))) return SZO_EINVAL;
+    if (d->M == 0 || d->N == 0) continue;
+    int blocks;
+    if (few_one(d)) blocks = small_m_blocks(d) * small_m_slices(d);
+    else plan_tiles((int)d->M, (int)d->N, d->format, &blocks);
+    if (blocks < 0) return SZO_EUNSUPPORTED;
+    T += blocks;
+  }
+  if (2 * T > kNoAllocMaxPartials) return SZO_EUNSUPPORTED;
+  double* part = nullptr;
+  int rc = noalloc_partials(&part);
+  if (rc != SZO_OK) return rc;
+  int64_t off = 0;
+  for (int i = 0; i < n; ++i) {
+    const szo_linear_desc* d = &descs[i];
+    if (d->M == 0 || d->N == 0) continue;
+    if (few_one(d)) {
+      rc = small_m_launch_one(d, seed, step, eps, 1, true, part + off, part + T + off, s);
+      off += small_m_blocks(d) * small_m_slices(d);
+    } else {
+      const double scale = 1.0 / ((double)d->M * (double)d->N);
+      int blocks;
+      plan_tiles((int)d->M, (int)d->N, d->format, &blocks);
+      rc = run_forward(d, seed, step, +1, eps, part + off, scale, s, false);
+      if (rc == SZO_OK) rc = run_forward(d, seed, step, -1, eps, part + T + off, scale, s, true);
+      off += blocks;
+    }
+    if (rc != SZO_OK) return rc;
+  }
+  rc = reduce_step(part, (int)T, eps, scalars, s);
+  if (rc != SZO_OK) return rc;
+  for (int i = 0; i < n; ++i) {
+    rc = szo_sparse_update(descs[i].sp_val, descs[i].sp_idx, descs[i].nnz, descs[i].nnz_base, seed, step,
+                           scalars + 2, lr, s);
+    if (rc != SZO_OK) return rc;
+  }
+  return SZO_OK;
+}
 
 int szo_set_tile_config(int config) {
   if (config < 0 || config > 5) return SZO_EINVAL;

@@ -305,7 +305,7 @@ int szo_kernel_timing_read(double* total_ms, int64_t* launches) {
 }
 
 int szo_last_hip_error(void) { return g_last_hip_error; }
-int szo_version(void) { return 4; }
+int szo_version(void) { return 5; }
 size_t szo_workspace_bytes(void) { return kWorkspaceBytes; }
 
 int szo_workspace_init(void* workspace, void* stream) {

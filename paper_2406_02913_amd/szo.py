@@ -48,6 +48,8 @@ _SIGS = {
                                      C.c_void_p, C.c_float, C.c_void_p]),
     "szo_zo_step": (C.c_int, [_P(LinearDesc), C.c_int, C.c_uint64, C.c_uint64, C.c_float, C.c_float,
                                C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]),
+    "szo_zo_step_noalloc": (C.c_int, [_P(LinearDesc), C.c_int, C.c_uint64, C.c_uint64, C.c_float, C.c_float,
+                                       C.c_void_p, C.c_void_p]),
     "szo_workspace_bytes": (C.c_size_t, []),
     "szo_workspace_init": (C.c_int, [C.c_void_p, C.c_void_p]),
     "szo_num_tiles": (C.c_int64, [C.c_int64, C.c_int64]),
@@ -157,6 +159,14 @@ def szo_zo_step(descs, seed, step, eps, lr, scalars, workspace, flags=0, stream=
         descs = desc_array(descs)
     _check("szo_zo_step", lib.szo_zo_step(descs, len(descs), seed, step, eps, lr, _dev(scalars),
                                           _dev(workspace), flags, _stream(stream)))
+
+
+def szo_zo_step_noalloc(descs, seed, step, eps, lr, scalars, stream=None):
+    """The fused-loss step without a workspace and without any allocation inside the library."""
+    if isinstance(descs, (list, tuple)):
+        descs = desc_array(descs)
+    _check("szo_zo_step_noalloc", lib.szo_zo_step_noalloc(descs, len(descs), seed, step, eps, lr, _dev(scalars),
+                                                          _stream(stream)))
 
 
 def szo_workspace_bytes():

@@ -21,7 +21,7 @@ def test_every_declared_symbol_is_exported():
     assert declared == set(szo.EXPORTS)
     for name in declared:
         assert getattr(szo.lib, name) is not None
-    assert szo.szo_version() == 4
+    assert szo.szo_version() == 5
     assert szo.szo_workspace_bytes() >= 64 + 8 * 1024
 
 
