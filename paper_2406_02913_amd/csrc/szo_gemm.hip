@@ -72,6 +72,9 @@ struct FwdParams {
   int first_block;          // grouped launch: id of this entry's first workgroup (a multiple of 8)
   int pad_;
   const uint16_t* lut;      // fp16 [N,16], table format only
+  // grouped launch: one entry runs BOTH forwards of its matrix; the fields above describe the +eps one
+  const uint16_t* x_minus;  // activations of the -eps forward (= x unless the layer has a second set)
+  double* partials_minus;   // loss partials of the -eps forward
 };
 
 // floor(v / d) for 32-bit v with a precomputed multiplier (Granlund-Montgomery, round-up form).
@@ -183,11 +186,27 @@ template <> struct Frag<SZO_TILE_BF16> {
 // the compiler from regrouping the slots.  Global loads are in place: as soon as a unit's
 // registers have been consumed they are reloaded with the same unit of the tile after next,
 // which gives every load one full K step (about a microsecond) to arrive.
-// `bid` is the workgroup's id inside this forward (0 .. grid_m*grid_n - 1); its residue mod 8 is the
-// XCD the workgroup runs on, both in a launch of its own and in a grouped launch (entries start at
-// multiples of 8).
+// Workgroup id -> output tile.  Workgroup ids go round-robin over the 8 XCDs, each with its own L2, so
+// ids with equal (id % 8) are first made consecutive ("logical" id): the workgroups resident on one XCD
+// at a time (32 with the 256x256 tile) are then a run of consecutive logical ids, and logical ids walk
+// the tile grid in strips of `strip` row blocks, so that run covers strip x (32 / strip) tiles which
+// share `strip` activation strips and 32 / strip weight strips through that L2.  `count` ids in all;
+// `bid`'s residue mod 8 is its XCD both in a launch of its own and in a grouped launch (entries start
+// at multiples of 8).
+__device__ __forceinline__ int logical_block(int bid, int count) {
+  const int q = count >> 3, r = count & 7;
+  const int xcd = bid & 7, idx = bid >> 3;
+  return xcd * q + min(xcd, r) + idx;
+}
+__device__ __forceinline__ void tile_of_logical(int L, int grid_m, int grid_n, int strip, int& bm, int& bn) {
+  const int width = strip * grid_n, g = L / width, first_m = strip * g;
+  const int gsize = min(grid_m - first_m, strip), rem = L - g * width;
+  bm = first_m + rem % gsize;
+  bn = rem / gsize;
+}
+
 template <int WAVES_M, int WAVES_N, int WMB, int WNB, int DT, bool FUSE_LOSS, int FMT>
-__device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bid) {
+__device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm, const int bn) {
   constexpr int NWAVES = WAVES_M * WAVES_N;
   constexpr int BM = 32 * WMB * WAVES_M, BN = 32 * WNB * WAVES_N;
   constexpr int W_WAVES = BN / 64;                 // one per 64-row band of the weight tile
@@ -218,20 +237,6 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bi
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-  // Workgroup -> output tile.  Workgroup ids go round-robin over the 8 XCDs, each with its own
-  // L2, so ids with equal (id % 8) are first made consecutive ("logical" id), and logical ids
-  // walk the tile grid in strips of 4 row blocks: the 32 workgroups resident on one XCD then
-  // cover 4 x 8 tiles and share 4 activation strips and 8 weight strips through that L2.
-  int bm, bn;
-  {
-    const int G = p.grid_m * p.grid_n, q = G >> 3, r = G & 7;
-    const int xcd = bid & 7, idx = bid >> 3;
-    const int L = xcd * q + min(xcd, r) + idx;
-    const int width = 4 * p.grid_n, g = L / width, first_m = 4 * g;
-    const int gsize = min(p.grid_m - first_m, 4), rem = L - g * width;
-    bm = first_m + rem % gsize;
-    bn = rem / gsize;
-  }
   const int m0 = bm * BM, n0 = bn * BN;
   const int nk = p.ktiles;
 
@@ -768,21 +773,27 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bi
       double b = 0.0;
 #pragma unroll
       for (int i = 0; i < NWAVES; ++i) b += wave_part[i];
-      p.partials[bid] = b * p.loss_scale;
+      p.partials[bm * p.grid_n + bn] = b * p.loss_scale;       // indexed by tile: the sum does not depend on the launch order
     }
   }
 }
 
 template <int WAVES_M, int WAVES_N, int WMB, int WNB, int DT, bool FUSE_LOSS, int FMT>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdParams p) {
-  linear_fwd_body<WAVES_M, WAVES_N, WMB, WNB, DT, FUSE_LOSS, FMT>(p, (int)blockIdx.x);
+  int bm, bn;
+  tile_of_logical(logical_block((int)blockIdx.x, p.grid_m * p.grid_n), p.grid_m, p.grid_n, 4, bm, bn);
+  linear_fwd_body<WAVES_M, WAVES_N, WMB, WNB, DT, FUSE_LOSS, FMT>(p, bm, bn);
 }
 
 // Grouped launch: every forward of a step (all matrices, both signs) in one grid, so that the only
 // partly filled round of workgroups is the last one of the step, not the last one of every matrix.
-// `table` holds one FwdParams per forward, ordered by first_block; a workgroup finds its entry by
+// `table` holds one FwdParams per MATRIX, ordered by first_block; a workgroup finds its entry by
 // binary search and reads it through the constant address space (scalar loads into scalar registers).
-// Workgroups between an entry's last tile and the next multiple of 8 have nothing to do.
+// An entry has 2 * grid_m * grid_n workgroups: neighbouring logical ids are the +eps and the -eps
+// forward of the same tile, and pairs walk the grid in strips of 2 row blocks, so the 32 workgroups
+// resident on an XCD are 2 x 8 tiles x 2 signs: both forwards of a tile read the same activations and
+// the same codes while those are in that XCD's L2, instead of the second forward fetching everything
+// again later.  Workgroups between an entry's last tile and the next multiple of 8 have nothing to do.
 template <int WAVES_M, int WAVES_N, int WMB, int WNB, int DT, bool FUSE_LOSS, int FMT>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_table_kernel(const FwdParams* table, int n_entries) {
   constexpr int W = (int)(sizeof(FwdParams) / 4), FB = (int)(offsetof(FwdParams, first_block) / 4);
@@ -796,10 +807,18 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_table_kerne
   struct Words { uint32_t w[W]; } raw;
 #pragma unroll
   for (int i = 0; i < W; ++i) raw.w[i] = tab[lo * W + i];
-  const FwdParams p = __builtin_bit_cast(FwdParams, raw);
-  const int bid = (int)blockIdx.x - p.first_block;
-  if (bid >= p.grid_m * p.grid_n) return;
-  linear_fwd_body<WAVES_M, WAVES_N, WMB, WNB, DT, FUSE_LOSS, FMT>(p, bid);
+  FwdParams p = __builtin_bit_cast(FwdParams, raw);
+  const int bid = (int)blockIdx.x - p.first_block, count = 2 * p.grid_m * p.grid_n;
+  if (bid >= count) return;
+  const int L = logical_block(bid, count);
+  int bm, bn;
+  tile_of_logical(L >> 1, p.grid_m, p.grid_n, 2, bm, bn);
+  if (L & 1) {                                              // the -eps forward of the tile
+    p.x = p.x_minus;
+    p.partials = p.partials_minus;
+    p.signed_eps = -p.signed_eps;
+  }
+  linear_fwd_body<WAVES_M, WAVES_N, WMB, WNB, DT, FUSE_LOSS, FMT>(p, bm, bn);
 }
 
 // ---- host side -----------------------------------------------------------------------------
@@ -981,7 +1000,7 @@ static int grouped_forwards(const szo_linear_desc* descs, int n, uint64_t seed, 
     ++live;
   }
   if ((T < 192 && g_tile_config != 3) || T == 0 || 2 * T > kMaxLossPartials) return SZO_EUNSUPPORTED;
-  if (sizeof(FwdParams) * (size_t)(2 * live) > kTableBytesPerMatrix * (size_t)kMaxStepMatrices) return SZO_EUNSUPPORTED;
+  if (sizeof(FwdParams) * (size_t)live > kTableBytesPerMatrix * (size_t)kMaxStepMatrices) return SZO_EUNSUPPORTED;
   static thread_local std::vector<FwdParams> table;
   table.clear();
   int64_t first_block = 0, offset = 0;
@@ -990,18 +1009,17 @@ static int grouped_forwards(const szo_linear_desc* descs, int n, uint64_t seed, 
     if (d->M == 0 || d->N == 0) continue;
     const double scale = 1.0 / ((double)d->M * (double)d->N);
     const int gm = (int)((d->M + tile - 1) / tile), gn = (int)((d->N + tile - 1) / tile);
-    for (int pass = 0; pass < 2; ++pass) {                  // "+" then "-": the pair shares x and the codes in L2
-      FwdParams p;
-      const int rc = fill_params(p, d, seed, step, pass == 0 ? +1 : -1, eps, partials + (pass == 0 ? 0 : T) + offset, scale);
-      if (rc != SZO_OK) return rc;
-      if (pass == 1 && d->x_minus) p.x = (const uint16_t*)d->x_minus;
-      p.grid_m = gm; p.grid_n = gn;
-      p.y = nullptr;                                        // the step's fused path never writes y
-      p.first_block = (int)first_block;
-      table.push_back(p);
-      first_block += ((int64_t)gm * gn + 7) & ~(int64_t)7;
-      if (first_block > 0x7FFFFFFF) return SZO_EUNSUPPORTED;
-    }
+    FwdParams p;
+    const int rc = fill_params(p, d, seed, step, +1, eps, partials + offset, scale);
+    if (rc != SZO_OK) return rc;
+    p.x_minus = d->x_minus ? (const uint16_t*)d->x_minus : p.x;
+    p.partials_minus = partials + T + offset;
+    p.grid_m = gm; p.grid_n = gn;
+    p.y = nullptr;                                          // the step's fused path never writes y
+    p.first_block = (int)first_block;
+    table.push_back(p);
+    first_block += (2 * (int64_t)gm * gn + 7) & ~(int64_t)7;
+    if (first_block > 0x7FFFFFFF) return SZO_EUNSUPPORTED;
     offset += (int64_t)gm * gn;
   }
   int rc = stage_table(table.data(), sizeof(FwdParams) * table.size(), table_dev, stream);

@@ -74,7 +74,8 @@ struct SmallMat {
   int div_shift;
   int first_block;          // workgroups of earlier matrices in this launch
   int partial_base;         // index of this matrix's first loss partial
-  int64_t first_quad;       // Philox counters (groups of 4 entries) of earlier matrices: grouped update
+  int64_t first_quad;       // threads of earlier matrices in the grouped update (one per Philox counter = 4 entries,
+                            // rounded up to whole waves of 64 per matrix)
 };
 
 static_assert(sizeof(SmallMat) <= kTableBytesPerMatrix, "table entries must fit the workspace's table area");
@@ -561,28 +562,41 @@ __global__ void __launch_bounds__(256, R == 1 ? SM_MIN_BLOCKS : 2) small_m_kerne
 }
 
 // Sparse ZO-SGD update of every matrix of a table in one launch (Section 3.4, fixed-parameter
-// update rule): thread = one Philox counter = four consecutive entries of one matrix.
+// update rule): thread = one Philox counter = four consecutive entries of one matrix.  A matrix's
+// counters start at a multiple of 64 threads, so a wave serves one matrix: it finds the table entry by
+// a binary search on scalar loads (through the constant address space) and keeps the entry's fields in
+// scalar registers.  (Searching per lane with vector loads made every wave wait for eight dependent
+// memory round trips before it could touch its entries; the launch then took 27 us for 52 MB.)
 __global__ void __launch_bounds__(256) sparse_update_table_kernel(const SmallMat* __restrict__ table, int n_mats,
                                                                   int64_t total_quads, uint64_t seed, uint64_t step,
                                                                   const double* __restrict__ g, float lr) {
-  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (t >= total_quads) return;
-  int lo = 0, hi = n_mats - 1;
+  constexpr int W = (int)(sizeof(SmallMat) / 4), FQ = (int)(offsetof(SmallMat, first_quad) / 4);
+  static_assert(offsetof(SmallMat, first_quad) % 8 == 0, "first_quad is read as two words");
+  const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+  const int64_t tw = (int64_t)blockIdx.x * 256 + 64 * wave;           // the wave's first thread
+  if (tw >= total_quads) return;
+  const auto* tab = (const uint32_t __attribute__((address_space(4)))*)table;
+  int lo = 0, hi = n_mats - 1;                                        // last matrix whose first_quad <= tw
   while (lo < hi) {
     const int mid = (lo + hi + 1) >> 1;
-    if (table[mid].first_quad <= t) lo = mid; else hi = mid - 1;
+    const int64_t fq = (int64_t)(((uint64_t)tab[mid * W + FQ + 1] << 32) | tab[mid * W + FQ]);
+    if (fq <= tw) lo = mid; else hi = mid - 1;
   }
-  const SmallMat& mt = table[lo];
-  const int64_t tq = t - mt.first_quad, j0 = 4 * tq;
+  struct Words { uint32_t w[W]; } raw;
+#pragma unroll
+  for (int i = 0; i < W; ++i) raw.w[i] = tab[lo * W + i];
+  const SmallMat mt = __builtin_bit_cast(SmallMat, raw);
+  const int64_t tq = tw + (int64_t)(threadIdx.x & 63) - mt.first_quad, j0 = 4 * tq;
   if (j0 >= (int64_t)mt.nnz) return;
   const float c = (float)((double)lr * *g);
   float z[4];
   zbar_quad((mt.nnz_base >> 2) + (uint64_t)tq, seed, step, z);
-  float* v = mt.sp_val + j0;
+  float __attribute__((address_space(1)))* const v = (float __attribute__((address_space(1)))*)mt.sp_val + j0;
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
   if (j0 + 4 <= (int64_t)mt.nnz) {
-    float4 w = *reinterpret_cast<float4*>(v);
-    w.x = fmaf(-c, z[0], w.x); w.y = fmaf(-c, z[1], w.y); w.z = fmaf(-c, z[2], w.z); w.w = fmaf(-c, z[3], w.w);
-    *reinterpret_cast<float4*>(v) = w;
+    f32x4 w = *reinterpret_cast<f32x4 __attribute__((address_space(1)))*>(v);
+    w[0] = fmaf(-c, z[0], w[0]); w[1] = fmaf(-c, z[1], w[1]); w[2] = fmaf(-c, z[2], w[2]); w[3] = fmaf(-c, z[3], w[3]);
+    *reinterpret_cast<f32x4 __attribute__((address_space(1)))*>(v) = w;
   } else {
     for (int i = 0; j0 + i < (int64_t)mt.nnz; ++i) v[i] = fmaf(-c, z[i], v[i]);
   }
@@ -811,7 +825,7 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
     class_slices[cls] = std::max(class_slices[cls], slices);
     ++class_entries[cls];
     partials += (int64_t)b * slices;
-    quads += ((int64_t)d->nnz + 3) / 4;
+    quads += (((int64_t)d->nnz + 3) / 4 + 63) & ~(int64_t)63;      // a wave of the update serves one matrix
     if (do_forward && 2 * partials > kMaxLossPartials) return SZO_EUNSUPPORTED;
     if ((int64_t)class_blocks[cls] * class_slices[cls] > 0x7FFFFFFF) return SZO_EUNSUPPORTED;
   }

@@ -11,7 +11,8 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libszo.so")
+# SZO_LIBRARY names another build of the same library (comparisons between builds); default: the in-tree one
+LIB_PATH = os.environ.get("SZO_LIBRARY") or os.path.join(_HERE, "libszo.so")
 
 OK, EINVAL, EUNSUPPORTED, ELAUNCH = 0, -1, -2, -3
 TILE_F16, TILE_BF16 = 0, 1
