@@ -278,7 +278,11 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm
 
   if (wave < W_WAVES) {
     // =============================== weight wave ===============================================
-    const int wr = wave * 64 + (lane >> 1), wh = lane & 1;       // tile row (plus 32*i), half of the row
+    // Lane l stages row l of the band: all 64 columns of a tile, as two halves i = 0, 1 of 32 columns
+    // (16 bytes of codes, one scale each).  A wave-wide write of one chunk then touches 64 consecutive rows
+    // at the same logical chunk -- the access pattern of the operand reads, which the swizzle makes
+    // conflict-free (with two lanes per row the writes measured two-way bank conflicts).
+    const int wr = wave * 64 + lane;                             // tile row
     const int band = n0 / 64 + wave;                             // band of the sparse layout
     const bool band_ok = band < p.bands;
     const uint32_t tp_base = (uint32_t)band * (uint32_t)nk;
@@ -297,8 +301,8 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm
     float* const wv = winVal + wave * kWindow;
     uint16_t* const wp = winPos + wave * kWindow;
 
-    // Banded layout: the 64 rows of this wave's band, one 64-column tile, are 2 KB in a row, so a
-    // load instruction of the wave (32 rows x 32 bytes) is contiguous.  Bands past N re-read the
+    // Banded layout: the 64 rows of this wave's band, one 64-column tile, are 2 KB in a row, so the two
+    // load instructions of the wave (64 rows x 16 bytes each) cover it without gaps.  Bands past N re-read the
     // last band (their outputs are never stored) and column tiles past the end re-read the last
     // tile (never consumed): the loads stay unconditional and in order.
     const uint8_t* qrow[2];
@@ -307,8 +311,8 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm
       const size_t bsafe = (size_t)min(band, p.bands - 1);
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
-        const int r = (lane >> 1) + 32 * i;                        // row inside the band
-        qrow[i] = p.qweight + (bsafe * (size_t)nk * 64 + (size_t)r) * 32 + 16 * wh;
+        const int r = lane;                                        // row inside the band
+        qrow[i] = p.qweight + (bsafe * (size_t)nk * 64 + (size_t)r) * 32 + 16 * i;
         srow[i] = p.scales + bsafe * (size_t)(p.K >> p.group_shift) * 64 + (size_t)((r & 15) * 4 + (r >> 4));
       }
     }
@@ -321,7 +325,7 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm
       qreg[i] = *reinterpret_cast<const u32x4*>(qrow[i] + (size_t)min(kt, nk - 1) * (64 * BK / 2));
     };
     auto load_s = [&](int kt, int i) {
-      sreg[i] = srow[i][(size_t)((min(kt, nk - 1) * BK + 32 * wh) >> p.group_shift) * 64];
+      sreg[i] = srow[i][(size_t)((min(kt, nk - 1) * BK + 32 * i) >> p.group_shift) * 64];
     };
     auto load_w = [&](int kt, int i) { load_q(kt, i); load_s(kt, i); };
 
@@ -547,7 +551,7 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm
               const _Float16 sh = __builtin_bit_cast(_Float16, sreg[i]);
               outw[w] = dequant_out<DT>(qreg[i][c], w, (float)sh, half2_t{sh, sh}, dqk);
               if (w == 3) {
-                *reinterpret_cast<u32x4*>(ldsB + dst * BN * BK + chunk_off(wr + 32 * i, 4 * wh + c)) = outw;
+                *reinterpret_cast<u32x4*>(ldsB + dst * BN * BK + chunk_off(wr, 4 * i + c)) = outw;
                 if (c == 3) load_w(load_kt, i);
               }
             }
@@ -576,7 +580,7 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm
               outw[w] = dequant_out<DT>(qreg[i][c], w, (float)sh, half2_t{sh, sh}, dqk);
             }
             if (w == 3) {
-              *reinterpret_cast<u32x4*>(ldsB + dst * BN * BK + chunk_off(wr + 32 * i, 4 * wh + c)) = outw;
+              *reinterpret_cast<u32x4*>(ldsB + dst * BN * BK + chunk_off(wr, 4 * i + c)) = outw;
               if (c == 3) {
                 if (DT != SZO_TILE_F16) load_q(load_kt, i);
                 load_s(load_kt, i);
