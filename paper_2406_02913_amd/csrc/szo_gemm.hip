@@ -205,10 +205,18 @@ __device__ __forceinline__ void tile_of_logical(int L, int grid_m, int grid_n, i
   bn = rem / gsize;
 }
 
-template <int WAVES_M, int WAVES_N, int WMB, int WNB, int DT, bool FUSE_LOSS, int FMT>
+// DUAL (grouped launch of a step, loss fused, both forwards read the same activations): the workgroup
+// computes BOTH forwards of a tile of BM x BN/2 outputs.  Rows [0, BN/2) of the weight tile in LDS hold
+// W + eps z, rows [BN/2, BN) the same rows of W with W - eps z: the codes are loaded and dequantised once
+// and written twice, the two copies differ only at the sensitive entries.  Waves of the first half of a
+// wave row compute the +eps forward, the others the -eps forward; every MFMA of both forwards is
+// executed, only the staging of the weights is shared.  The MFMA loop is the same as without DUAL.
+template <int WAVES_M, int WAVES_N, int WMB, int WNB, int DT, bool FUSE_LOSS, int FMT, bool DUAL = false>
 __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm, const int bn) {
   constexpr int NWAVES = WAVES_M * WAVES_N;
   constexpr int BM = 32 * WMB * WAVES_M, BN = 32 * WNB * WAVES_N;
+  constexpr int TN = DUAL ? BN / 2 : BN;           // output columns of the tile
+  static_assert(!DUAL || (FUSE_LOSS && FMT == SZO_FORMAT_UNIFORM && BN == 256), "dual-sign tiles: fused loss, uniform format, 256 rows");
   constexpr int W_WAVES = BN / 64;                 // one per 64-row band of the weight tile
   constexpr int X_WAVES = NWAVES - W_WAVES;
   static_assert(BN % 64 == 0 && X_WAVES > 0, "need whole bands and at least one activation wave");
@@ -237,7 +245,7 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-  const int m0 = bm * BM, n0 = bn * BN;
+  const int m0 = bm * BM, n0 = bn * TN;
   const int nk = p.ktiles;
 
   float16_t acc[WMB][WNB];
@@ -276,7 +284,18 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm
     }
   };
 
-  if (wave < W_WAVES) {
+  if (DUAL && wave >= W_WAVES / 2 && wave < W_WAVES) {
+    // ============ DUAL: the bands of these waves are the -eps copies, written by waves 0 .. W_WAVES/2-1 ====
+    auto nothing = [](int) {};
+    for (int kt = 0; kt < nk; kt += 2) {
+      __syncthreads();
+      run_tile(0, nothing);
+      if (kt + 1 < nk) {
+        __syncthreads();
+        run_tile(1, nothing);
+      }
+    }
+  } else if (wave < W_WAVES) {
     // =============================== weight wave ===============================================
     // Lane l stages row l of the band: all 64 columns of a tile, as two halves i = 0, 1 of 32 columns
     // (16 bytes of codes, one scale each).  A wave-wide write of one chunk then touches 64 consecutive rows
@@ -299,7 +318,10 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm
     }
     uint32_t win_lo = 0, win_hi = 0;                             // entries [win_lo, win_hi) are in the window
     float* const wv = winVal + wave * kWindow;
+    float* const wv_minus = winVal + (wave + W_WAVES / 2) * kWindow;   // DUAL: value for the -eps copy (the idle waves' space)
     uint16_t* const wp = winPos + wave * kWindow;
+    constexpr int kMinusCopy = (BN / 2) * BK;                    // DUAL: offset of the -eps copy of a tile position (128 rows:
+                                                                 // the swizzle, a function of row / 2 mod 8, is the same there)
 
     // Banded layout: the 64 rows of this wave's band, one 64-column tile, are 2 KB in a row, so the two
     // load instructions of the wave (64 rows x 16 bytes each) cover it without gaps.  Bands past N re-read the
@@ -351,11 +373,15 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm
             val[c] = ok ? p.sp_val[j + c] : 0.0f;
           }
         }
+        float val_minus[4] = {val[0], val[1], val[2], val[3]};
         if (p.signed_eps != 0.0f) {
           float z[4];
           zbar_quad((p.nnz_base + j) >> 2, p.seed, p.step, z);
 #pragma unroll
-          for (int c = 0; c < 4; ++c) val[c] = fmaf(p.signed_eps, z[c], val[c]);
+          for (int c = 0; c < 4; ++c) {
+            if (DUAL) val_minus[c] = fmaf(-p.signed_eps, z[c], val[c]);
+            val[c] = fmaf(p.signed_eps, z[c], val[c]);
+          }
         }
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
@@ -364,6 +390,7 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm
           const uint32_t kk = (idx[c] - n * (uint32_t)p.K) & 63u;
           wp[4 * lane + c] = (r < 64u) ? (uint16_t)lds_pos<DT>(wave * 64 + (int)r, (int)kk) : (uint16_t)0xFFFFu;
           wv[4 * lane + c] = val[c];
+          if (DUAL) wv_minus[4 * lane + c] = val_minus[c];
         }
       }
       win_lo = s;
@@ -384,6 +411,7 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm
           if (pos != 0xFFFFu) {
             uint16_t* w = B + pos;
             Frag<DT>::store(w, Frag<DT>::load(w) + wv[e]);
+            if (DUAL) Frag<DT>::store(w + kMinusCopy, Frag<DT>::load(w + kMinusCopy) + wv_minus[e]);
           }
         }
         cur = hi;
@@ -526,8 +554,9 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm
     u32x4 outw;
     uint32_t st_a[3][2], st_b[3][2];
     uint32_t sc_pos = 0xFFFFu;
-    float sc_val = 0.0f, sc_old = 0.0f;
+    float sc_val = 0.0f, sc_old = 0.0f, sc_val_minus = 0.0f, sc_old_minus = 0.0f;
     uint16_t* sc_addr = nullptr;
+    uint16_t* sc_addr_minus = nullptr;
     auto make_slice = [&](int dst, int load_kt) {
       return [&, dst, load_kt](int s) {
         // the k-th (0 or 1) output word staged from slot `slot`: unit u, word w; false if none
@@ -552,6 +581,7 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm
               outw[w] = dequant_out<DT>(qreg[i][c], w, (float)sh, half2_t{sh, sh}, dqk);
               if (w == 3) {
                 *reinterpret_cast<u32x4*>(ldsB + dst * BN * BK + chunk_off(wr, 4 * i + c)) = outw;
+                if (DUAL) *reinterpret_cast<u32x4*>(ldsB + dst * BN * BK + kMinusCopy + chunk_off(wr, 4 * i + c)) = outw;
                 if (c == 3) load_w(load_kt, i);
               }
             }
@@ -581,6 +611,7 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm
             }
             if (w == 3) {
               *reinterpret_cast<u32x4*>(ldsB + dst * BN * BK + chunk_off(wr, 4 * i + c)) = outw;
+              if (DUAL) *reinterpret_cast<u32x4*>(ldsB + dst * BN * BK + kMinusCopy + chunk_off(wr, 4 * i + c)) = outw;
               if (c == 3) {
                 if (DT != SZO_TILE_F16) load_q(load_kt, i);
                 load_s(load_kt, i);
@@ -594,13 +625,20 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm
             const uint32_t e = active ? sc_e0 + lane : 0u;
             sc_pos = wp[e];
             sc_val = wv[e];
+            if (DUAL) sc_val_minus = wv_minus[e];
           } else if (s == 27) {                         // every dense word of the tile is written by slot 25
             const bool ok = active && sc_pos != 0xFFFFu;
             sc_addr = ok ? ldsB + dst * BN * BK + sc_pos : sink16 + wave * 64 + lane;
             sc_val = ok ? sc_val : 0.0f;
             sc_old = Frag<DT>::load(sc_addr);
+            if (DUAL) {                                 // the same position in the -eps copy
+              sc_addr_minus = ok ? ldsB + dst * BN * BK + kMinusCopy + sc_pos : sink16 + (wave + W_WAVES / 2) * 64 + lane;
+              sc_val_minus = ok ? sc_val_minus : 0.0f;
+              sc_old_minus = Frag<DT>::load(sc_addr_minus);
+            }
           } else if (s == 30) {
             Frag<DT>::store(sc_addr, sc_old + sc_val);
+            if (DUAL) Frag<DT>::store(sc_addr_minus, sc_old_minus + sc_val_minus);
           }
         }
       };
@@ -685,12 +723,12 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm
   // squares are formed in fp32, summed over the 16 registers of one MFMA block in fp32, and
   // every such partial is added in fp64 (the loss difference of the two passes is ~1e-6 of the
   // loss, far below fp32 resolution of a long sum).
-  constexpr int TROW = BN * 2 + 32;               // LDS row stride of the target tile in bytes
+  constexpr int TROW = TN * 2 + 32;               // LDS row stride of the target tile in bytes
   bool staged = false;
   if (FUSE_LOSS) {
     staged = ((p.N & 7) == 0) && ((reinterpret_cast<uintptr_t>(p.target) & 15) == 0);
     if (staged) {
-      constexpr int CPR = BN / 8;                 // 16-byte chunks per tile row
+      constexpr int CPR = TN / 8;                 // 16-byte chunks per tile row
       constexpr int ROWS_PER_PASS = 64 * NWAVES / CPR;
       uint8_t* const T = reinterpret_cast<uint8_t*>(lds);
       const int c = tid % CPR, r0 = tid / CPR;
@@ -720,7 +758,9 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm
   }
   double loss = 0.0;
   // Element (i, j, r) of this lane: tile row ml0 + 32 i + 8 (r/4) + r%4, tile column nl0 + 32 j.
-  const int ml0 = wm * 32 * WMB + 4 * (lane >> 5), nl0 = wn * 32 * WNB + (lane & 31);
+  // DUAL: the waves of the second half of a wave row hold the -eps forward of the same columns.
+  const int wn_col = DUAL ? wn % (WAVES_N / 2) : wn;
+  const int ml0 = wm * 32 * WMB + 4 * (lane >> 5), nl0 = wn_col * 32 * WNB + (lane & 31);
   const uint8_t* const trow = reinterpret_cast<const uint8_t*>(lds) + ml0 * TROW + nl0 * 2;
   // FULL: whole tile inside the matrix (no bounds checks).  STAGED: targets come from LDS.
   // STORE: y is written.  The three are compile-time so that the common cases are straight code.
@@ -756,7 +796,7 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm
   {
     using T = std::true_type;
     using F = std::false_type;
-    const bool full = m0 + BM <= p.M && n0 + BN <= p.N;
+    const bool full = m0 + BM <= p.M && n0 + TN <= p.N;
     if (FUSE_LOSS) {
       if (full && staged && !p.y) finish(T{}, T{}, F{});            // the step's path
       else if (staged) { if (p.y) finish(F{}, T{}, T{}); else finish(F{}, T{}, F{}); }
@@ -774,10 +814,14 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm
     if (lane == 0) wave_part[wave] = w;
     __syncthreads();
     if (tid == 0) {
-      double b = 0.0;
+      double b = 0.0, b_minus = 0.0;
 #pragma unroll
-      for (int i = 0; i < NWAVES; ++i) b += wave_part[i];
+      for (int i = 0; i < NWAVES; ++i) {
+        if (DUAL && (i % WAVES_N) >= WAVES_N / 2) b_minus += wave_part[i];
+        else b += wave_part[i];
+      }
       p.partials[bm * p.grid_n + bn] = b * p.loss_scale;       // indexed by tile: the sum does not depend on the launch order
+      if (DUAL) p.partials_minus[bm * p.grid_n + bn] = b_minus * p.loss_scale;
     }
   }
 }
@@ -798,7 +842,9 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_kernel(FwdP
 // resident on an XCD are 2 x 8 tiles x 2 signs: both forwards of a tile read the same activations and
 // the same codes while those are in that XCD's L2, instead of the second forward fetching everything
 // again later.  Workgroups between an entry's last tile and the next multiple of 8 have nothing to do.
-template <int WAVES_M, int WAVES_N, int WMB, int WNB, int DT, bool FUSE_LOSS, int FMT>
+// With DUAL an entry has grid_m * grid_n workgroups, each computing both forwards of a tile of half the
+// width (see linear_fwd_body); the 32 workgroups resident on an XCD are then 2 x 16 such tiles.
+template <int WAVES_M, int WAVES_N, int WMB, int WNB, int DT, bool FUSE_LOSS, int FMT, bool DUAL = false>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_table_kernel(const FwdParams* table, int n_entries) {
   constexpr int W = (int)(sizeof(FwdParams) / 4), FB = (int)(offsetof(FwdParams, first_block) / 4);
   static_assert(sizeof(FwdParams) % 4 == 0 && offsetof(FwdParams, first_block) % 4 == 0, "table entry is read as words");
@@ -812,17 +858,21 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_table_kerne
 #pragma unroll
   for (int i = 0; i < W; ++i) raw.w[i] = tab[lo * W + i];
   FwdParams p = __builtin_bit_cast(FwdParams, raw);
-  const int bid = (int)blockIdx.x - p.first_block, count = 2 * p.grid_m * p.grid_n;
+  const int bid = (int)blockIdx.x - p.first_block, count = (DUAL ? 1 : 2) * p.grid_m * p.grid_n;
   if (bid >= count) return;
   const int L = logical_block(bid, count);
   int bm, bn;
-  tile_of_logical(L >> 1, p.grid_m, p.grid_n, 2, bm, bn);
-  if (L & 1) {                                              // the -eps forward of the tile
-    p.x = p.x_minus;
-    p.partials = p.partials_minus;
-    p.signed_eps = -p.signed_eps;
+  if (DUAL) {
+    tile_of_logical(L, p.grid_m, p.grid_n, 2, bm, bn);
+  } else {
+    tile_of_logical(L >> 1, p.grid_m, p.grid_n, 2, bm, bn);
+    if (L & 1) {                                            // the -eps forward of the tile
+      p.x = p.x_minus;
+      p.partials = p.partials_minus;
+      p.signed_eps = -p.signed_eps;
+    }
   }
-  linear_fwd_body<WAVES_M, WAVES_N, WMB, WNB, DT, FUSE_LOSS, FMT>(p, bm, bn);
+  linear_fwd_body<WAVES_M, WAVES_N, WMB, WNB, DT, FUSE_LOSS, FMT, DUAL>(p, bm, bn);
 }
 
 // ---- host side -----------------------------------------------------------------------------
@@ -961,7 +1011,7 @@ static int run_forward(const szo_linear_desc* d, uint64_t seed, uint64_t step, i
 
 static double* partial_area(void* workspace) { return (double*)((char*)workspace + kWorkspaceHeader); }
 
-template <int DT, int FMT = SZO_FORMAT_UNIFORM, int TILE = 256>
+template <int DT, int FMT = SZO_FORMAT_UNIFORM, int TILE = 256, bool DUAL = false>
 static int launch_table(const FwdParams* table_dev, int entries, int64_t blocks, hipStream_t stream) {
   static_assert(TILE == 256 || TILE == 128, "two workgroup tiles exist");
   constexpr int BM = TILE, BN = TILE;
@@ -969,7 +1019,7 @@ static int launch_table(const FwdParams* table_dev, int entries, int64_t blocks,
   constexpr size_t main_bytes = 2 * (size_t)(BM + BN) * BK * sizeof(uint16_t) + (size_t)(BN / 64) * (kWindow * 6 + 128);
   constexpr size_t target_bytes = (size_t)BM * (BN * 2 + 32);
   constexpr size_t lds_bytes = main_bytes > target_bytes ? main_bytes : target_bytes;
-  auto kern = linear_fwd_table_kernel<2, WAVES_N, WMB, 2, DT, true, FMT>;
+  auto kern = linear_fwd_table_kernel<2, WAVES_N, WMB, 2, DT, true, FMT, DUAL>;
   static std::atomic<uint64_t> lds_limit_set{0};
   int rc = set_lds_limit_once(lds_limit_set, (const void*)kern, lds_bytes);
   if (rc != SZO_OK) return rc;
@@ -994,16 +1044,23 @@ static int grouped_forwards(const szo_linear_desc* descs, int n, uint64_t seed, 
   for (int i = 0; i < n; ++i) max_m = std::max<int64_t>(max_m, descs[i].N > 0 ? descs[i].M : 0);
   const bool auto_tiles = g_tile_config == 0 || g_tile_config >= 4;
   const int tile = (auto_tiles && n > 0 && descs[0].format == SZO_FORMAT_UNIFORM && max_m <= 128) ? 128 : 256;
-  int64_t T = 0;
+  // Dual-sign tiles (one workgroup computes both forwards of 256 x 128 outputs and dequantises the weights
+  // once for both) when the library chooses the tiles and no layer has a second activation set.
+  bool dual = auto_tiles && tile == 256 && n > 0 && descs[0].format == SZO_FORMAT_UNIFORM;
+  for (int i = 0; dual && i < n; ++i) dual = descs[i].x_minus == nullptr;
+  const int tile_n = dual ? tile / 2 : tile;
+  int64_t T = 0, wgs = 0;          // loss partials per sign; workgroups of the launch
   int live = 0;
   for (int i = 0; i < n; ++i) {
     const szo_linear_desc* d = &descs[i];
     if (d->M == 0 || d->N == 0) continue;
     if (d->tile_dtype != descs[0].tile_dtype || d->format != descs[0].format) return SZO_EUNSUPPORTED;
-    T += (int64_t)((d->M + tile - 1) / tile) * ((d->N + tile - 1) / tile);
+    const int64_t t = (int64_t)((d->M + tile - 1) / tile) * ((d->N + tile_n - 1) / tile_n);
+    T += t;
+    wgs += dual ? t : 2 * t;
     ++live;
   }
-  if ((T < 192 && g_tile_config != 3) || T == 0 || 2 * T > kMaxLossPartials) return SZO_EUNSUPPORTED;
+  if ((wgs < 384 && g_tile_config != 3) || T == 0 || 2 * T > kMaxLossPartials) return SZO_EUNSUPPORTED;
   if (sizeof(FwdParams) * (size_t)live > kTableBytesPerMatrix * (size_t)kMaxStepMatrices) return SZO_EUNSUPPORTED;
   static thread_local std::vector<FwdParams> table;
   table.clear();
@@ -1012,7 +1069,7 @@ static int grouped_forwards(const szo_linear_desc* descs, int n, uint64_t seed, 
     const szo_linear_desc* d = &descs[i];
     if (d->M == 0 || d->N == 0) continue;
     const double scale = 1.0 / ((double)d->M * (double)d->N);
-    const int gm = (int)((d->M + tile - 1) / tile), gn = (int)((d->N + tile - 1) / tile);
+    const int gm = (int)((d->M + tile - 1) / tile), gn = (int)((d->N + tile_n - 1) / tile_n);
     FwdParams p;
     const int rc = fill_params(p, d, seed, step, +1, eps, partials + offset, scale);
     if (rc != SZO_OK) return rc;
@@ -1022,7 +1079,7 @@ static int grouped_forwards(const szo_linear_desc* descs, int n, uint64_t seed, 
     p.y = nullptr;                                          // the step's fused path never writes y
     p.first_block = (int)first_block;
     table.push_back(p);
-    first_block += (2 * (int64_t)gm * gn + 7) & ~(int64_t)7;
+    first_block += ((dual ? 1 : 2) * (int64_t)gm * gn + 7) & ~(int64_t)7;
     if (first_block > 0x7FFFFFFF) return SZO_EUNSUPPORTED;
     offset += (int64_t)gm * gn;
   }
@@ -1035,6 +1092,11 @@ static int grouped_forwards(const szo_linear_desc* descs, int n, uint64_t seed, 
     if (descs[0].tile_dtype == SZO_TILE_F16)
       return launch_table<SZO_TILE_F16, SZO_FORMAT_UNIFORM, 128>((const FwdParams*)table_dev, (int)table.size(), first_block, stream);
     return launch_table<SZO_TILE_BF16, SZO_FORMAT_UNIFORM, 128>((const FwdParams*)table_dev, (int)table.size(), first_block, stream);
+  }
+  if (dual) {
+    if (descs[0].tile_dtype == SZO_TILE_F16)
+      return launch_table<SZO_TILE_F16, SZO_FORMAT_UNIFORM, 256, true>((const FwdParams*)table_dev, (int)table.size(), first_block, stream);
+    return launch_table<SZO_TILE_BF16, SZO_FORMAT_UNIFORM, 256, true>((const FwdParams*)table_dev, (int)table.size(), first_block, stream);
   }
   if (descs[0].tile_dtype == SZO_TILE_F16)
     return launch_table<SZO_TILE_F16>((const FwdParams*)table_dev, (int)table.size(), first_block, stream);
