@@ -34,7 +34,7 @@ inline int set_lds_limit_once(std::atomic<uint64_t>& done, const void* fn, size_
 // Loss workspace: a ticket counter (first 64 bytes) followed by one fp64 partial per
 // workgroup.  The last workgroup to finish adds the partials in index order, which makes
 // the sum independent of scheduling.
-constexpr int kMaxLossPartials = 1 << 20;
+constexpr int kMaxLossPartials = 1 << 21;       // 16 MiB: a 32-block 7B stack at 4096 tokens has 2 x 340 000 dual-sign tiles
 constexpr size_t kWorkspaceHeader = 64;
 constexpr int kMaxStepMatrices = 4096;            // descriptor table of the few-token step
 constexpr size_t kTableBytesPerMatrix = 144;

@@ -91,11 +91,17 @@ __global__ void spsa_g_kernel(const double* lp, const double* lm, float eps, dou
   *g = (eps == 0.0f) ? 0.0 : (*lp - *lm) / (2.0 * (double)eps);
 }
 
-// Sum of v[0..count) by one workgroup of 1024 threads: thread t adds elements t, t+1024, ...
-// in order, then the 1024 thread sums are combined by a fixed tree.  Bit-reproducible.
+// Sum of v[0..count) by one workgroup of 1024 threads: thread t adds elements t, t+1024, ... in four
+// interleaved chains (four loads in flight: the loop is bound by memory latency), then the chains and the
+// 1024 thread sums are combined by a fixed tree.  Bit-reproducible.
 __device__ __forceinline__ double block_sum_1024(const double* __restrict__ v, int count, double* scratch) {
-  double a = 0.0;
-  for (int i = threadIdx.x; i < count; i += 1024) a += v[i];
+  double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+  int i = threadIdx.x;
+  for (; i + 3 * 1024 < count; i += 4 * 1024) {
+    a0 += v[i]; a1 += v[i + 1024]; a2 += v[i + 2 * 1024]; a3 += v[i + 3 * 1024];
+  }
+  for (; i < count; i += 1024) a0 += v[i];
+  double a = (a0 + a1) + (a2 + a3);
   a = wave_sum(a);
   if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = a;
   __syncthreads();
