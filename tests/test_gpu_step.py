@@ -369,3 +369,52 @@ def test_step_over_layers_of_both_tile_types(cfg):
     r = ozo.zo_step([clone(o1), clone(o2)], 3, 0, 1e-3, 0.0)
     assert abs(lp - r["loss_plus"]) <= 5e-3 * r["loss_plus"] and abs(lm - r["loss_minus"]) <= 5e-3 * r["loss_minus"]
     assert abs(g - r["g"]) <= 1e-1 * max(abs(r["g"]), sigma_g([o1, o2]))       # the bf16 layer's share of g is coarse
+
+
+@pytest.mark.parametrize("dt", [szo.TILE_F16, szo.TILE_BF16])
+def test_dual_sign_tiles_of_the_grouped_launch(dt):
+    """With the library choosing the tiles, a step that fills the chip runs as one launch in which every
+    workgroup computes both forwards of a 256 x 128 tile (weights dequantised once, written to two copies
+    that differ at the sensitive entries).  Ragged shapes (M not a multiple of 256, N not of 128 or 64),
+    a mask dense enough for tiles with more than 64 entries, and a matrix without entries; compared with
+    the oracle and with the one-forward-per-workgroup launch (tile configuration 3), whose losses it must
+    reproduce up to the order of the fp64 partial sums."""
+    shapes = [(161, 2000, 3000, 256, 128, 2e-2), (162, 2048, 3104, 192, 64, 1e-3), (163, 1100, 1024, 128, 32, 0.0)]
+    results = {}
+    for cfg in (3, 0):
+        szo.szo_set_tile_config(cfg)
+        os_, ds_, base = [], [], 0
+        for (sd, M, N, K, G, dens) in shapes:
+            o, d = make_pair(sd, M, N, K, G, dens, nnz_base=base)
+            base += (o.sp_idx.size + 3) // 4 * 4
+            os_.append(o)
+            ds_.append(d)
+        ws = szo.new_workspace()
+        scal = torch.zeros(3, dtype=torch.float64, device="cuda")
+        descs = szo.desc_array([d.desc(dt, with_y=False) for d in ds_])
+        hist = []
+        szo.szo_kernel_timing(True)
+        for s in range(2):
+            szo.szo_zo_step(descs, 43, s, 1e-3, 1e-3, scal, ws, szo.STEP_FUSED_LOSS)
+            hist.append(scal.cpu().numpy().copy())
+        _, launches = szo.szo_kernel_timing_read()
+        szo.szo_kernel_timing(False)
+        assert launches == 2                                   # one grouped launch per step either way
+        results[cfg] = (hist, [d.sp_val.cpu().numpy().copy() for d in ds_])
+    szo.szo_set_tile_config(0)
+    for a, b in zip(results[3][0], results[0][0]):
+        assert abs(a[0] - b[0]) <= 1e-12 * a[0] and abs(a[1] - b[1]) <= 1e-12 * a[1], (a, b)
+    ref = [clone(o) for o in os_]
+    sg = sigma_g(os_)
+    bound = UpdateBound(sg, 1e-3)
+    for s in range(2):
+        r = ozo.zo_step(ref, 43, s, 1e-3, 1e-3)
+        bound.add(r)
+        lp, lm, g = results[0][0][s]
+        ltol, gtol = (1e-6, 1e-2) if dt == szo.TILE_F16 else (1e-4, 1e-1)
+        assert abs(lp - r["loss_plus"]) <= ltol * r["loss_plus"] and abs(lm - r["loss_minus"]) <= ltol * r["loss_minus"]
+        assert abs(g - r["g"]) <= gtol * max(abs(r["g"]), sg), (s, g, r["g"], sg)
+    if dt == szo.TILE_F16:
+        for i, (om, o) in enumerate(zip(ref, os_)):
+            if o.sp_idx.size:
+                bound.check(i, results[0][1][i], om.sp_val, o.sp_val)
