@@ -293,7 +293,9 @@ int szo_debug_zbar(uint64_t nnz_base, int64_t nnz, uint64_t seed, uint64_t step,
  * step as one grid (with 0 and 2 it does so only when the step has at least 192 tiles), 4 / 5 = as 0
  * and the few-token path takes 32 / 48 token rows per pass for every layer with more than 16 tokens
  * (by default it chooses 16, 32 or 48, the larger ones only in launches that fill the chip more than
- * twice over).
+ * twice over), 6 = as 0 and szo_zo_step always launches all forwards of a step as one grid, whatever its
+ * size (with 0 only when the grid fills the chip); that grid uses dual-sign tiles -- one workgroup computes
+ * both forwards of 256 x 128 outputs and dequantises the weights once -- unless a layer has x_minus.
  * Process-wide, not thread-safe; results do not depend on it beyond fp32 summation order. */
 int szo_set_tile_config(int config);
 

@@ -1060,7 +1060,7 @@ static int grouped_forwards(const szo_linear_desc* descs, int n, uint64_t seed, 
     wgs += dual ? t : 2 * t;
     ++live;
   }
-  if ((wgs < 384 && g_tile_config != 3) || T == 0 || 2 * T > kMaxLossPartials) return SZO_EUNSUPPORTED;
+  if ((wgs < 384 && g_tile_config != 3 && g_tile_config != 6) || T == 0 || 2 * T > kMaxLossPartials) return SZO_EUNSUPPORTED;
   if (sizeof(FwdParams) * (size_t)live > kTableBytesPerMatrix * (size_t)kMaxStepMatrices) return SZO_EUNSUPPORTED;
   static thread_local std::vector<FwdParams> table;
   table.clear();
@@ -1186,7 +1186,7 @@ int szo_zo_step_noalloc(const szo_linear_desc* descs, int n, uint64_t seed, uint
 }
 
 int szo_set_tile_config(int config) {
-  if (config < 0 || config > 5) return SZO_EINVAL;
+  if (config < 0 || config > 6) return SZO_EINVAL;
   g_tile_config = config;
   small_m_force_rblocks(config == 4 ? 2 : config == 5 ? 3 : 0);
   return SZO_OK;
