@@ -22,7 +22,8 @@ What is computed, and where the paper defines it:
   quantiser; Appendix C.5 separates uniform from non-uniform ones): uniform
   codes with group scales, and a per-row table of 16 centroids.
 
-Pins (see tests/test_oracle_*.py): Philox known-answer vectors; Gaussian
+Pins (see tests/test_oracle_*.py): Philox known-answer vectors; both synthetic masks recomputed draw by
+draw with the scalar generator; Gaussian
 moments and the two SPSA moment identities of Section 3.1 / Appendix
 (E g^2 = |m.c|^2 and E |g z|^2 = (k+2)|m.c|^2 for a linear loss); k = 0
 reduces to a textbook dequantise-then-matmul; brute-force triple loop;

@@ -54,6 +54,38 @@ def test_heavy_tail_structure():
     assert counts[hot].min() > 10 * np.median(counts)
 
 
+def test_heavy_tail_mask_by_hand_with_the_scalar_generator():
+    # ceil(N/100) hot rows from stream 1, floor(k/2) positions inside them from stream 2, the rest from
+    # stream 3 over the whole matrix skipping what is taken: every draw recomputed one by one
+    from oracle.philox import philox4x32_10_scalar
+    N, K, k, seed = 150, 8, 31, 0x1234567899
+
+    def stream(s, modulus):
+        d = 0
+        while True:
+            r = philox4x32_10_scalar([d & 0xFFFFFFFF, d >> 32, s, 0], [seed & 0xFFFFFFFF, seed >> 32])
+            yield ((r[0] << 32) | r[1]) % modulus
+            d += 1
+
+    def first_distinct(gen, want, taken=()):
+        out, seen = [], set(taken)
+        for v in gen:
+            if v not in seen:
+                seen.add(v)
+                out.append(v)
+                if len(out) == want:
+                    return out
+
+    H = 2
+    hot = sorted(first_distinct(stream(1, N), H))
+    inside = first_distinct(stream(2, H * K), k // 2)              # 15 of the 16 positions: duplicates are certain
+    flat_hot = [hot[v // K] * K + v % K for v in inside]
+    rest = first_distinct(stream(3, N * K), k - k // 2, taken=flat_hot)
+    assert mask.mask_heavy_tail(N, K, k, seed).tolist() == sorted(flat_hot + rest)
+    rows = np.array(sorted(flat_hot + rest)) // K
+    assert sum(int(r in hot) for r in rows) >= k // 2
+
+
 def test_uniform_mask_is_roughly_uniform():
     N, K = 512, 512
     f = mask.mask_uniform(N, K, 20000, 3)
