@@ -114,17 +114,18 @@ def _dual_cases(n, seed):
         dens = float(rng.choice([0.0, 1e-3, 1e-2, 5e-2]))
         kind = "heavy_tail" if (N >= 100 and dens <= 1e-2 and rng.random() < 0.5) else "uniform"
         dt = "bf16" if rng.random() < 0.25 else "f16"
-        out.append((3000 + i, M, N, K, group, dens, kind, dt))
+        fmt = "lut" if (dt == "f16" and rng.random() < 0.35) else "uniform"
+        out.append((3000 + i, M, N, K, group, dens, kind, dt, fmt))
     return out
 
 
-@pytest.mark.parametrize("case", _dual_cases(24, 777), ids=lambda c: "-".join(str(v) for v in c[1:]))
+@pytest.mark.parametrize("case", _dual_cases(32, 777), ids=lambda c: "-".join(str(v) for v in c[1:]))
 def test_random_case_dual_sign_tiles(case):
     """Tile configuration 6 runs even a one-matrix step as the grouped launch with dual-sign tiles (both
     forwards of a 256 x 128 tile in one workgroup): one fused step per case against the oracle."""
-    s, M, N, K, G, dens, kind, dtname = case
+    s, M, N, K, G, dens, kind, dtname, fmt = case
     dt = szo.TILE_BF16 if dtname == "bf16" else szo.TILE_F16
-    o, d = make_pair(s, M, N, K, G, dens, kind=kind, nnz_base=4 * (s % 5))
+    o, d = make_pair(s, M, N, K, G, dens, kind=kind, nnz_base=4 * (s % 5), fmt=fmt)
     szo.szo_set_tile_config(6)
     seed, step, eps, lr = 11 + s, s % 3, 1e-3, 1e-3
     ws = szo.new_workspace()
@@ -137,8 +138,11 @@ def test_random_case_dual_sign_tiles(case):
     assert launches == 1
     lp, lm, g = scal.cpu().numpy()
     r = ozo.zo_step([om], seed, step, eps, lr)
-    ltol, gtol = (1e-5, 1e-2) if dtname == "f16" else (5e-3, 1e-1)
-    assert abs(lp - r["loss_plus"]) <= ltol * r["loss_plus"] and abs(lm - r["loss_minus"]) <= ltol * r["loss_minus"]
+    # every output carries an independent rounding error of ~1e-4 of its size (16-bit tile), which averages
+    # down over the M N outputs of the mean
+    ltol, gtol = (max(1e-5, 2e-3 / np.sqrt(M * N)), 1e-2) if dtname == "f16" else (5e-3, 1e-1)
+    # relative to the loss's natural size (targets are N(0,1)): a 1 x 1 output can land next to its target
+    assert abs(lp - r["loss_plus"]) <= ltol * max(r["loss_plus"], 1.0) and abs(lm - r["loss_minus"]) <= ltol * max(r["loss_minus"], 1.0)
     sg = sigma_g([o])
     assert abs(g - r["g"]) <= gtol * max(abs(r["g"]), sg), (g, r["g"], sg)
     if o.sp_idx.size:

@@ -371,8 +371,8 @@ def test_step_over_layers_of_both_tile_types(cfg):
     assert abs(g - r["g"]) <= 1e-1 * max(abs(r["g"]), sigma_g([o1, o2]))       # the bf16 layer's share of g is coarse
 
 
-@pytest.mark.parametrize("dt", [szo.TILE_F16, szo.TILE_BF16])
-def test_dual_sign_tiles_of_the_grouped_launch(dt):
+@pytest.mark.parametrize("dt,fmt", [(szo.TILE_F16, "uniform"), (szo.TILE_BF16, "uniform"), (szo.TILE_F16, "lut")])
+def test_dual_sign_tiles_of_the_grouped_launch(dt, fmt):
     """With the library choosing the tiles, a step that fills the chip runs as one launch in which every
     workgroup computes both forwards of a 256 x 128 tile (weights dequantised once, written to two copies
     that differ at the sensitive entries).  Ragged shapes (M not a multiple of 256, N not of 128 or 64),
@@ -385,7 +385,7 @@ def test_dual_sign_tiles_of_the_grouped_launch(dt):
         szo.szo_set_tile_config(cfg)
         os_, ds_, base = [], [], 0
         for (sd, M, N, K, G, dens) in shapes:
-            o, d = make_pair(sd, M, N, K, G, dens, nnz_base=base)
+            o, d = make_pair(sd, M, N, K, G, dens, nnz_base=base, fmt=fmt)
             base += (o.sp_idx.size + 3) // 4 * 4
             os_.append(o)
             ds_.append(d)
