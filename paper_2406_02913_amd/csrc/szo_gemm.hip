@@ -122,8 +122,11 @@ __device__ __forceinline__ uint32_t stage_x_word(u32x4 u, int w) {
 // 0..3 under exponent pattern 0x6400 reads 1024 + code, one in bits 4..7 under 0x5400 reads
 // 64 + code; removing the offset is exact and the product with the fp16 scale is rounded once,
 // which is the rounding of the exact (code-8)*scale.  Output pairs are codes (0,4) (1,5) (2,6) (3,7).
-// (a & mask) | bits in one VALU instruction.  Written out because the compiler splits the
-// expression in two when both constants are literals; `bits` therefore lives in a VGPR.
+// (a & mask) | bits in one VALU instruction, `bits` in a VGPR.  Inline assembly keeps the instruction in
+// the slot it is written in (as plain C the tiled step measured 1 % slower).  The compiler's hazard
+// handling cannot see into it, which is safe here and only here: the result feeds packed-half arithmetic
+// and an LDS store, never a matrix instruction, whose operands all come from LDS reads
+// (tests/test_isa_hazards.py checks the generated code for exactly that).
 __device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t bits_vgpr) {
   uint32_t r;
   asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(mask), "v"(bits_vgpr));

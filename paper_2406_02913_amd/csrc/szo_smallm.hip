@@ -105,10 +105,13 @@ __device__ __forceinline__ int sm_xpos(int kk) {
   return (kk & ~7) | ((w & 3) << 1) | (w >> 2);
 }
 
+// (a & mask) | bits: one v_and_or_b32 when `bits` is in a register.  Plain C on purpose.  As inline assembly
+// the instruction is opaque to the compiler's hazard handling, which keeps two wait states between a vector
+// instruction that writes a register and a matrix instruction that reads it: here the result IS a matrix
+// operand, and with the assembly form sequences with a single wait state were generated (harmless while
+// other waves share the SIMD and issue in between, wrong products for a wave that has the SIMD to itself).
 __device__ __forceinline__ uint32_t sm_and_or(uint32_t a, uint32_t mask, uint32_t bits_vgpr) {
-  uint32_t r;
-  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(mask), "v"(bits_vgpr));
-  return r;
+  return (a & mask) | bits_vgpr;
 }
 
 // 8 codes -> 8 fp16 values in the order (0,4)(1,5)(2,6)(3,7).
