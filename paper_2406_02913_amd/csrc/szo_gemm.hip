@@ -85,20 +85,28 @@ __device__ __forceinline__ uint32_t fast_div(uint32_t v, uint32_t mul, int shift
 
 // Position of column kk (0..63) of tile row r inside the LDS tile, in 16-bit elements.
 // Rows are 64 elements (128 bytes), so two rows span the 64 four-byte banks; the eight
-// 16-byte chunks of a row are XOR-swizzled with (row / 2) so that 16 lanes reading the same
-// chunk of 16 consecutive rows touch every bank exactly once.  In f16 mode the eight elements of a chunk are stored in the order
+// 16-byte chunks of a row are XOR-swizzled with row_swizzle(row), chosen for both ways the tile is
+// accessed with 16 bytes per lane.  Reads are served 16 lanes (256 bytes) per cycle: 16 lanes reading the
+// same chunk of 16 consecutive rows must touch every bank exactly once, which (row / 2) mod 8 gives.
+// Writes are served 8 lanes (128 bytes) per cycle and conflict when two of them fall into the same 16 bytes
+// modulo 128, whatever the row's parity (measured: a weight wave writing one chunk of 64 consecutive rows
+// took 16 cycles instead of 8 with the (row / 2) swizzle alone, 15 % of all LDS cycles of the kernel);
+// the extra (row & 1) * 4 makes 8 consecutive rows distinct as well, and keeps the read property.
+// In f16 mode the eight elements of a chunk are stored in the order
 // 0,4,1,5,2,6,3,7 -- the order in which two nibbles per 16-bit lane fall out of a packed
 // word -- and the activations are stored in the same order, which leaves the dot product
 // unchanged.
+__device__ __forceinline__ int row_swizzle(int r) { return ((r >> 1) & 7) ^ ((r & 1) << 2); }
+
 template <int DT>
 __device__ __forceinline__ int lds_pos(int r, int kk) {
   const int chunk = kk >> 3, w = kk & 7;
   const int p = (DT == SZO_TILE_F16) ? (((w & 3) << 1) | (w >> 2)) : w;
-  return r * BK + (((chunk ^ ((r >> 1) & 7)) << 3) | p);
+  return r * BK + (((chunk ^ row_swizzle(r)) << 3) | p);
 }
 
 __device__ __forceinline__ int chunk_off(int r, int chunk) {   // in 16-bit elements
-  return r * BK + ((chunk ^ ((r >> 1) & 7)) << 3);
+  return r * BK + ((chunk ^ row_swizzle(r)) << 3);
 }
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -324,7 +332,7 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm
     float* const wv_minus = winVal + (wave + W_WAVES / 2) * kWindow;   // DUAL: value for the -eps copy (the idle waves' space)
     uint16_t* const wp = winPos + wave * kWindow;
     constexpr int kMinusCopy = (BN / 2) * BK;                    // DUAL: offset of the -eps copy of a tile position (128 rows:
-                                                                 // the swizzle, a function of row / 2 mod 8, is the same there)
+                                                                 // the swizzle, a function of row mod 16, is the same there)
 
     // Banded layout: the 64 rows of this wave's band, one 64-column tile, are 2 KB in a row, so the two
     // load instructions of the wave (64 rows x 16 bytes each) cover it without gaps.  Bands past N re-read the
