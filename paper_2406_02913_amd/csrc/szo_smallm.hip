@@ -402,6 +402,11 @@ __global__ void __launch_bounds__(256, R == 1 ? SM_MIN_BLOCKS : 2) small_m_kerne
     const int kc = c * SM_KC;
     const _Float16* const xc = xs + (c & 1) * ROWS * SM_XSTRIDE;
     const uint32_t tp2 = tp_at(c + 2);
+    // next chunk's x: requested before the dense part, so that it has landed when the (short) sparse part
+    // is over and store_x wants it (two blocks of rows: 64 tokens 1.547 -> 1.535 ms; one block measured no gain,
+    // and with three there are no registers to hold it that long)
+    constexpr bool EARLY_X = R == 2;
+    if (EARLY_X) load_x(min(c + 1, nchunks - 1));           // the last chunk re-reads itself; never stored
 
     // ---- dense: stream this band's codes ----
 #pragma unroll
@@ -467,7 +472,7 @@ __global__ void __launch_bounds__(256, R == 1 ? SM_MIN_BLOCKS : 2) small_m_kerne
 
     // next chunk's x and scales: requested now that this chunk's are no longer needed, landing
     // while the sparse part runs
-    load_x(min(c + 1, nchunks - 1));                        // the last chunk re-reads itself; never stored
+    if (!EARLY_X) load_x(min(c + 1, nchunks - 1));
     if (FAST) load_scales(c + 1);                           // clamped inside
 
     // ---- sparse: this band's entries inside the chunk, 16 at a time (4 per k-group of the MFMA) ----
