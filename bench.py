@@ -29,7 +29,7 @@ PEAK_HBM_GBS = 8000.0                # MI355X HBM3E
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # script scaled by a plain copy of known size (profiles/*.md give the commands and the raw readings).
 # Only valid for the unmodified workloads; anything else reports null.
-MEASURED_TRAFFIC_BYTES = {"c3": 7.44e10, "c3m16": 3.634e9}
+MEASURED_TRAFFIC_BYTES = {"c3": 7.44e10, "c3m16": 3.613e9}
 
 
 def log(*a):
