@@ -268,7 +268,7 @@ def main():
                     help="SZO_STEP_ONE_DENSE_PASS: the slicing path of the few-token case at any token count (the dense "
                          "product of a slice is computed once and serves both signs; valid because both forwards of a "
                          "layer see the same x in this benchmark).  Not the default: see include/szo.h")
-    ap.add_argument("--tile-config", type=int, default=0, choices=[0, 1, 2, 3, 4, 5, 6],
+    ap.add_argument("--tile-config", type=int, default=0, choices=[0, 1, 2, 3, 4, 5, 6, 7],
                     help="0: the library chooses (few-token path for small token counts); 1 / 2: force the tiled kernel with "
                          "128x128 / 256x256 workgroup tiles; 3: as 2, and always one grouped launch per step; 4: as 0 "
                          "with 32 token rows per pass of the few-token path wherever there are more than 16 (for comparisons)")

@@ -295,7 +295,10 @@ int szo_debug_zbar(uint64_t nnz_base, int64_t nnz, uint64_t seed, uint64_t step,
  * (by default it chooses 16, 32 or 48, the larger ones only in launches that fill the chip more than
  * twice over), 6 = as 0 and szo_zo_step always launches all forwards of a step as one grid, whatever its
  * size (with 0 only when the grid fills the chip); that grid uses dual-sign tiles -- one workgroup computes
- * both forwards of 256 x 128 outputs and dequantises the weights once -- unless a layer has x_minus.
+ * both forwards of 256 x 128 outputs and dequantises the weights once -- unless a layer has x_minus,
+ * 7 = as 0 and the few-token path loads its codes as a non-temporal stream in every launch with one slice
+ * of token rows per strip (by default only when the launch streams more codes than the last-level cache
+ * holds).
  * Process-wide, not thread-safe; results do not depend on it beyond fp32 summation order. */
 int szo_set_tile_config(int config);
 

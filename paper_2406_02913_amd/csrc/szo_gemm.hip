@@ -889,7 +889,8 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_table_kerne
 // ---- host side -----------------------------------------------------------------------------
 
 static int g_tile_config = 0;      // 0 = choose by shape, 1 = 128x128 (4 waves), 2 = 256x256 (8 waves), 3 = 2 + always group the step,
-                                   // 4, 5 = as 0 with the few-token path's 32- / 48-row passes forced (see small_m_force_rblocks)
+                                   // 4, 5 = as 0 with the few-token path's 32- / 48-row passes forced (see small_m_force_rblocks),
+                                   // 6 = as 0 + always group the step, 7 = as 0 + non-temporal code stream in every one-slice launch
 static bool few_token_enabled() { return g_tile_config == 0 || g_tile_config >= 4; }
 
 static int ilog2_exact(int v) {
@@ -1197,9 +1198,10 @@ int szo_zo_step_noalloc(const szo_linear_desc* descs, int n, uint64_t seed, uint
 }
 
 int szo_set_tile_config(int config) {
-  if (config < 0 || config > 6) return SZO_EINVAL;
+  if (config < 0 || config > 7) return SZO_EINVAL;
   g_tile_config = config;
   small_m_force_rblocks(config == 4 ? 2 : config == 5 ? 3 : 0);
+  small_m_force_stream_once(config == 7);
   return SZO_OK;
 }
 

@@ -64,6 +64,7 @@ int small_m_blocks(const szo_linear_desc* d);
 int small_m_slices(const szo_linear_desc* d);              // passes over the weights: 16 or 32 token rows each
 bool small_m_shape_eligible(const szo_linear_desc* d);     // the same without looking at the token count
 void small_m_force_rblocks(int r);                         // testing hook: 0 = choose; 2, 3 = 32 / 48 token rows per pass wherever M > 16
+void small_m_force_stream_once(bool on);                    // testing hook: non-temporal code stream in every one-slice launch
 size_t small_m_table_bytes(int n);
 int small_m_launch_one(const szo_linear_desc* d, uint64_t seed, uint64_t step, float eps, int sign, bool loss_mode,
                        double* partial_plus, double* partial_minus, hipStream_t stream);

@@ -85,6 +85,7 @@ struct SmallArgs {
   SmallMat one;
   int n_mats;
   int slices;               // slices of token rows per strip in this launch (the longest matrix's count)
+  int stream_once;          // host's choice: load the codes as a non-temporal stream (see small_m_kernel, ONCE)
   int store_sign;           // store mode: which forward to write (-1, 0, +1); loss mode: unused
   int loss_mode;            // 1: write loss partials for both signs, 0: store y
   uint64_t seed, step;
@@ -179,13 +180,15 @@ constexpr int SM_PLAIN = 0, SM_FAST = 1, SM_LUT = 2;
 // DUAL (R = 2 only): the two forwards read different activations (x for +eps, x2 for -eps).  Block 0 then
 // holds 16 token rows of x and block 1 the same rows of x2: still one pass over the weights for both
 // signs, but nothing else is shared, and y(+) = acc[0] + eps accz[0], y(-) = acc[1] - eps accz[1].
-// ONCE: the launch has one slice per strip, so every byte of the codes is read exactly once by the whole
-// launch, and they are loaded as a non-temporal stream: they then do not displace what IS re-read -- the
-// activations (by every strip of a matrix), the sparse values (by the update that follows).  Measured on a
-// 32-block 7B-shaped stack at 16 tokens: 625 -> 592 us per launch, update 23.3 -> 21.3 us.  With several
-// slices the slices of a strip share the codes through the L2, and the hint costs 2 % (64 tokens) to 10 %
-// (224 tokens): plain loads there.  (A run-time choice between the two loads is folded into one plain load
-// by the compiler, hence a template parameter.)
+// ONCE: the codes are loaded as a non-temporal stream.  The host chooses it for launches that read every byte of
+// their codes exactly once (one slice per strip) and stream more of them than the chip's last-level cache
+// holds: they then do not displace what IS re-read -- the activations (by every strip of a matrix), the sparse
+// values (by the update that follows).  Measured on a 32-block 7B-shaped stack at 16 tokens: 625 -> 592 us per
+// launch, update 23.3 -> 21.3 us.  With several slices the slices of a strip share the codes through the L2
+// and the hint costs 2 % (64 tokens) to 10 % (224 tokens); a stack that fits the last-level cache (one or two
+// decoder blocks) is re-read from there step after step and loses 6 % with the hint: plain loads in both
+// cases.  (A run-time choice between the two loads is folded into one plain load by the compiler, hence a
+// template parameter.)
 template <int MODE, int R, bool DUAL = false, bool ONCE = false>
 __global__ void __launch_bounds__(256, R == 1 ? SM_MIN_BLOCKS : 2) small_m_kernel(SmallArgs a) {
   static_assert(R >= 1 && R <= 3, "one to three blocks of 16 token rows");
@@ -670,7 +673,7 @@ static int class_rblocks(int cls) { return class_dual(cls) ? 2 : cls % 3 + 1; }
 template <int MODE, int R, bool DUAL>
 static void launch_variant(dim3 blocks, const SmallArgs& a, hipStream_t stream) {
   const size_t lds = small_lds_bytes(R);
-  if (a.slices == 1) small_m_kernel<MODE, R, DUAL, true><<<blocks, 256, lds, stream>>>(a);
+  if (a.stream_once) small_m_kernel<MODE, R, DUAL, true><<<blocks, 256, lds, stream>>>(a);
   else small_m_kernel<MODE, R, DUAL, false><<<blocks, 256, lds, stream>>>(a);
 }
 template <int R, bool DUAL>
@@ -679,6 +682,16 @@ static void launch_mode(int mode, dim3 blocks, const SmallArgs& a, hipStream_t s
   else if (mode == SM_LUT) launch_variant<SM_LUT, R, DUAL>(blocks, a, stream);
   else launch_variant<SM_PLAIN, R, DUAL>(blocks, a, stream);
 }
+// Codes of a matrix in bytes, and the rule for the non-temporal stream: one slice per strip and more codes in
+// the launch than the 256 MB last-level (memory-side) cache of the chip keeps from one step to the next.
+constexpr int64_t kLastLevelCacheBytes = 256ll << 20;
+static int64_t code_bytes(const szo_linear_desc* d) { return (int64_t)((d->N + 63) / 64 * 64) * (d->K / 2); }
+static bool g_force_stream_once = false;                    // testing hook: the stream for every one-slice launch
+void small_m_force_stream_once(bool on) { g_force_stream_once = on; }
+static int stream_once_rule(int slices, int64_t launch_code_bytes) {
+  return slices == 1 && (g_force_stream_once || launch_code_bytes > kLastLevelCacheBytes);
+}
+
 static void small_m_launch(int mode, int r, bool dual, dim3 blocks, const SmallArgs& a, hipStream_t stream) {
   if (dual) launch_mode<2, true>(mode, blocks, a, stream);
   else if (r == 1) launch_mode<1, false>(mode, blocks, a, stream);
@@ -781,6 +794,7 @@ int small_m_launch_one(const szo_linear_desc* d, uint64_t seed, uint64_t step, f
   const int trc = timing_begin(stream);
   if (trc != SZO_OK) return trc;
   a.slices = slices;
+  a.stream_once = stream_once_rule(slices, code_bytes(d));
   small_m_launch(small_m_mode(d), rblocks, false, dim3((unsigned)(blocks * slices)), a, stream);
   SZO_LAUNCH_CHECK();
   const int erc = timing_end(stream);
@@ -829,6 +843,7 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
   // workgroups (those past a matrix's last slice return at once), and slice i of a matrix writes its
   // loss partials behind those of slice i - 1.
   int class_entries[kSmallClasses] = {}, class_blocks[kSmallClasses] = {}, class_slices[kSmallClasses] = {}, entries = 0;
+  int64_t class_code_bytes[kSmallClasses] = {};
   int64_t quads = 0, partials = 0;
   for (int r = 0; r < n; ++r) {
     const szo_linear_desc* d = &descs[order[r]];
@@ -844,6 +859,7 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
     m.first_quad = quads;
     class_blocks[cls] += b;
     class_slices[cls] = std::max(class_slices[cls], slices);
+    if (live) class_code_bytes[cls] += code_bytes(d);
     ++class_entries[cls];
     partials += (int64_t)b * slices;
     quads += (((int64_t)d->nnz + 3) / 4 + 63) & ~(int64_t)63;      // a wave of the update serves one matrix
@@ -862,6 +878,7 @@ int small_m_step(const szo_linear_desc* descs, int n, uint64_t seed, uint64_t st
     if (do_forward && class_blocks[cls] > 0 && class_slices[cls] > 0) {
       a.table = tdev + first_entry; a.n_mats = class_entries[cls];
       a.slices = class_slices[cls];
+      a.stream_once = stream_once_rule(a.slices, class_code_bytes[cls]);
       if ((rc = timing_begin(stream)) != SZO_OK) return rc;
       small_m_launch(class_mode(cls), class_rblocks(cls), class_dual(cls), dim3((unsigned)(class_blocks[cls] * class_slices[cls])), a, stream);
       SZO_LAUNCH_CHECK();

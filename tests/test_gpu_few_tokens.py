@@ -33,8 +33,9 @@ SHAPES = [
 ]
 
 
-# configurations 4 and 5: 32 / 48 token rows per pass wherever there are more than 16 (otherwise only in large launches)
-@pytest.mark.parametrize("shape,cfg", [(sh, 0) for sh in SHAPES] + [(sh, c) for sh in SHAPES if sh[1] > 16 for c in (4, 5)])
+# configurations 4 and 5: 32 / 48 token rows per pass wherever there are more than 16 (otherwise only in large launches);
+# configuration 7: the codes as a non-temporal stream (otherwise only in launches beyond the last-level cache)
+@pytest.mark.parametrize("shape,cfg", [(sh, 0) for sh in SHAPES] + [(sh, c) for sh in SHAPES if sh[1] > 16 for c in (4, 5)] + [(sh, 7) for sh in SHAPES if sh[1] <= 16])
 def test_few_token_forward_matches_oracle(shape, cfg):
     s, M, N, K, G, dens = shape
     szo.szo_set_tile_config(cfg)
@@ -137,6 +138,31 @@ def test_few_token_step_is_bit_reproducible():
             szo.szo_zo_step([d.desc(with_y=False)], 8, s, 1e-3, 1e-3, scal, ws, szo.STEP_FUSED_LOSS)
         outs.append((scal.cpu().numpy().copy(), d.sp_val.cpu().numpy().copy()))
     assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
+
+
+def test_non_temporal_code_stream_changes_no_bit():
+    """Large one-slice launches load their codes with the non-temporal hint (a cache policy, not arithmetic);
+    configuration 7 takes that instantiation at any size.  A step over three matrices (group 128, group 64,
+    table format aside) must give the same scalars and the same updated values bit for bit either way."""
+    outs = []
+    for cfg in (0, 7):
+        szo.szo_set_tile_config(cfg)
+        ds_, base = [], 0
+        for (sd, M, N, K, G, dens) in [(51, 16, 512, 1024, 128, 5e-3), (52, 9, 320, 768, 64, 1e-2), (53, 1, 200, 256, 128, 2e-2)]:
+            o, d = make_pair(sd, M, N, K, G, dens, nnz_base=base)
+            base += (o.sp_idx.size + 3) // 4 * 4
+            ds_.append(d)
+        ws = szo.new_workspace()
+        scal = torch.zeros(3, dtype=torch.float64, device="cuda")
+        descs = szo.desc_array([d.desc(with_y=False) for d in ds_])
+        hist = []
+        for s in range(3):
+            szo.szo_zo_step(descs, 8, s, 1e-3, 1e-3, scal, ws, szo.STEP_FUSED_LOSS)
+            hist.append(scal.cpu().numpy().copy())
+        outs.append((np.array(hist), [d.sp_val.cpu().numpy().copy() for d in ds_]))
+    szo.szo_set_tile_config(0)
+    assert np.array_equal(outs[0][0], outs[1][0])
+    assert all(np.array_equal(a, b) for a, b in zip(outs[0][1], outs[1][1]))
 
 
 def test_one_full_size_block_at_16_tokens_two_steps():

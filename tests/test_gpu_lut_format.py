@@ -117,8 +117,9 @@ FEW = [
 ]
 
 
-# configurations 4 and 5: 32 / 48 token rows per pass wherever there are more than 16 (otherwise only in large launches)
-@pytest.mark.parametrize("shape,cfg", [(sh, 0) for sh in FEW] + [(sh, c) for sh in FEW if sh[1] > 16 for c in (4, 5)])
+# configurations 4 and 5: 32 / 48 token rows per pass wherever there are more than 16 (otherwise only in large launches);
+# configuration 7: the codes as a non-temporal stream (otherwise only in launches beyond the last-level cache)
+@pytest.mark.parametrize("shape,cfg", [(sh, 0) for sh in FEW] + [(sh, c) for sh in FEW if sh[1] > 16 for c in (4, 5)] + [(sh, 7) for sh in FEW if sh[1] <= 16])
 def test_few_token_forward_matches_oracle(shape, cfg):
     s, M, N, K, dens = shape
     szo.szo_set_tile_config(cfg)
