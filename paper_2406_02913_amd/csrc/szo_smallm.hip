@@ -51,7 +51,8 @@ constexpr int SM_XSTRIDE = SM_KC + 8;   // LDS row stride of x in fp16 elements 
 constexpr int SM_WIN = 256;             // sensitive entries computed per refill (4 per lane)
 constexpr int SM_CAP = 512;             // entries held per band (ring)
 #ifndef SM_MIN_BLOCKS
-#define SM_MIN_BLOCKS 3                 // workgroups per CU the register budget is set for (~150 registers, no spills)
+#define SM_MIN_BLOCKS 4                 // workgroups per CU the register budget of a 16-row pass is set for (<= 128 registers, no spills;
+                                        // the table format keeps its tables in 32 more registers: three workgroups)
 #endif
 
 struct SmallMat {
@@ -190,7 +191,7 @@ constexpr int SM_PLAIN = 0, SM_FAST = 1, SM_LUT = 2;
 // cases.  (A run-time choice between the two loads is folded into one plain load by the compiler, hence a
 // template parameter.)
 template <int MODE, int R, bool DUAL = false, bool ONCE = false>
-__global__ void __launch_bounds__(256, R == 1 ? SM_MIN_BLOCKS : 2) small_m_kernel(SmallArgs a) {
+__global__ void __launch_bounds__(256, R == 1 ? (MODE == SM_LUT ? 3 : SM_MIN_BLOCKS) : 2) small_m_kernel(SmallArgs a) {
   static_assert(R >= 1 && R <= 3, "one to three blocks of 16 token rows");
   static_assert(!DUAL || R == 2, "two activation sets: one block of rows each");
   constexpr bool FAST = MODE == SM_FAST, LUT = MODE == SM_LUT;
@@ -423,12 +424,20 @@ __global__ void __launch_bounds__(256, R == 1 ? SM_MIN_BLOCKS : 2) small_m_kerne
 #pragma unroll
     for (int kbl = 0; kbl < 2; ++kbl) {
       // blocks past the end of K multiply clamped codes with the zeros staged for x: no branch needed
-      half8_t af[R][4];
+      // R = 1: the activation operands are read from LDS where they are used (16 registers less, which is
+      // what lets four workgroups share a CU); with more blocks of rows they are read once per block.
+      constexpr bool AF_LATE = R == 1;
+      auto read_af = [&](int rb, int t) {
+        return *reinterpret_cast<const half8_t*>(xc + (16 * rb + nn) * SM_XSTRIDE + kbl * 128 + 32 * jj + 8 * t);
+      };
+      half8_t af[AF_LATE ? 1 : R][AF_LATE ? 1 : 4];
+      if (!AF_LATE) {
 #pragma unroll
-      for (int rb = 0; rb < R; ++rb)
+        for (int rb = 0; rb < R; ++rb)
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
-          af[rb][t] = *reinterpret_cast<const half8_t*>(xc + (16 * rb + nn) * SM_XSTRIDE + kbl * 128 + 32 * jj + 8 * t);
+          for (int t = 0; t < 4; ++t) af[rb][t] = read_af(rb, t);
+      }
+      auto af_of = [&](int rb, int t) { return AF_LATE ? read_af(rb, t) : af[AF_LATE ? 0 : rb][AF_LATE ? 0 : t]; };
       // FAST: minus the constant part of the un-centred codes, sum_k x[m,k] (1032 | 72) over the block, from
       // one more MFMA chain against a constant operand; it seeds the four subtiles' chains.
       float4_t init[R];
@@ -437,7 +446,7 @@ __global__ void __launch_bounds__(256, R == 1 ? SM_MIN_BLOCKS : 2) small_m_kerne
         init[rb] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
         if (FAST) {
 #pragma unroll
-          for (int t = 0; t < 4; ++t) init[rb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[rb][t], minus_offsets, init[rb], 0, 0, 0);
+          for (int t = 0; t < 4; ++t) init[rb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af_of(rb, t), minus_offsets, init[rb], 0, 0, 0);
         }
       }
 #pragma unroll
@@ -462,7 +471,7 @@ __global__ void __launch_bounds__(256, R == 1 ? SM_MIN_BLOCKS : 2) small_m_kerne
         for (int t = 0; t < 4; ++t) {
           const half8_t b = LUT ? sm_lut_word(q[t], tb[LUT ? s : 0]) : sm_dequant_word<FAST>(q[t], magic_lo, magic_hi, s2);
 #pragma unroll
-          for (int rb = 0; rb < R; ++rb) tmp[rb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[rb][t], b, tmp[rb], 0, 0, 0);
+          for (int rb = 0; rb < R; ++rb) tmp[rb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af_of(rb, t), b, tmp[rb], 0, 0, 0);
         }
 #pragma unroll
         for (int rb = 0; rb < R; ++rb) {
