@@ -165,11 +165,14 @@ def test_non_temporal_code_stream_changes_no_bit():
     assert all(np.array_equal(a, b) for a, b in zip(outs[0][1], outs[1][1]))
 
 
-def test_one_full_size_block_at_16_tokens_two_steps():
+@pytest.mark.parametrize("cfg", [0, 7])
+def test_one_full_size_block_at_16_tokens_two_steps(cfg):
     """The seven matrices of one Llama-2-7B block at their real sizes, in the grouped launch
-    bench.py times (one forward launch, one update launch per step)."""
+    bench.py times (one forward launch, one update launch per step).  A whole stack streams more codes
+    than the last-level cache holds and therefore runs the instantiation with the non-temporal code
+    stream; configuration 7 selects it for this one block as well."""
     from paper_2406_02913_amd import synth
-    szo.szo_set_tile_config(0)
+    szo.szo_set_tile_config(cfg)
     cfg = synth.WORKLOADS["c3m16"]
     os_, ds_, base = [], [], 0
     for i, (name, N, K) in enumerate(cfg["block"]):
