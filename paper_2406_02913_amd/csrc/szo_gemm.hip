@@ -223,7 +223,8 @@ __device__ __forceinline__ void tile_of_logical(int L, int grid_m, int grid_n, i
 // wave row compute the +eps forward, the others the -eps forward; every MFMA of both forwards is
 // executed, only the staging of the weights is shared.  The MFMA loop is the same as without DUAL.
 template <int WAVES_M, int WAVES_N, int WMB, int WNB, int DT, bool FUSE_LOSS, int FMT, bool DUAL = false>
-__device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm, const int bn) {
+__device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm, const int bn,
+                                                const uint32_t __attribute__((address_space(4)))* entry = nullptr) {
   constexpr int NWAVES = WAVES_M * WAVES_N;
   constexpr int BM = 32 * WMB * WAVES_M, BN = 32 * WNB * WAVES_N;
   constexpr int TN = DUAL ? BN / 2 : BN;           // output columns of the tile
@@ -258,6 +259,20 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
   const int m0 = bm * BM, n0 = bn * TN;
   const int nk = p.ktiles;
+  // Fields that are only needed now and then (a window refill every ~64 K steps, the loss epilogue) are read
+  // again from the table entry where they are used instead of occupying scalar registers for the whole
+  // tile; the pointer is laundered so that the loads stay where they are written.  Only with dual-sign
+  // tiles: otherwise the grouped launch has changed `p` for the -eps forward.
+  auto cold = [&]() -> FwdParams {
+    if (!DUAL || entry == nullptr) return p;
+    constexpr int W = (int)(sizeof(FwdParams) / 4);
+    const uint32_t __attribute__((address_space(4)))* e = entry;
+    asm volatile("" : "+s"(e));
+    struct Words { uint32_t w[W]; } raw;
+#pragma unroll
+    for (int i = 0; i < W; ++i) raw.w[i] = e[i];
+    return __builtin_bit_cast(FwdParams, raw);
+  };
 
   float16_t acc[WMB][WNB];
 #pragma unroll
@@ -367,38 +382,39 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm
     // ---- sensitive entries -------------------------------------------------------------------
     // Computes entries [s, s+256) of the band (s a multiple of 4) into the window.
     auto refill = [&](uint32_t s) {
+      const FwdParams pr = cold();
       const uint32_t j = s + 4u * lane;
       if (j < band_end) {
         uint32_t idx[4];
         float val[4];
-        if (j + 3 < p.nnz) {
-          const uint4 iv = *reinterpret_cast<const uint4*>(p.sp_idx + j);
-          const float4 vv = *reinterpret_cast<const float4*>(p.sp_val + j);
+        if (j + 3 < pr.nnz) {
+          const uint4 iv = *reinterpret_cast<const uint4*>(pr.sp_idx + j);
+          const float4 vv = *reinterpret_cast<const float4*>(pr.sp_val + j);
           idx[0] = iv.x; idx[1] = iv.y; idx[2] = iv.z; idx[3] = iv.w;
           val[0] = vv.x; val[1] = vv.y; val[2] = vv.z; val[3] = vv.w;
         } else {
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
-            const bool ok = j + c < p.nnz;
-            idx[c] = ok ? p.sp_idx[j + c] : 0xFFFFFFFFu;
-            val[c] = ok ? p.sp_val[j + c] : 0.0f;
+            const bool ok = j + c < pr.nnz;
+            idx[c] = ok ? pr.sp_idx[j + c] : 0xFFFFFFFFu;
+            val[c] = ok ? pr.sp_val[j + c] : 0.0f;
           }
         }
         float val_minus[4] = {val[0], val[1], val[2], val[3]};
-        if (p.signed_eps != 0.0f) {
+        if (pr.signed_eps != 0.0f) {
           float z[4];
-          zbar_quad((p.nnz_base + j) >> 2, p.seed, p.step, z);
+          zbar_quad((pr.nnz_base + j) >> 2, pr.seed, pr.step, z);
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
-            if (DUAL) val_minus[c] = fmaf(-p.signed_eps, z[c], val[c]);
-            val[c] = fmaf(p.signed_eps, z[c], val[c]);
+            if (DUAL) val_minus[c] = fmaf(-pr.signed_eps, z[c], val[c]);
+            val[c] = fmaf(pr.signed_eps, z[c], val[c]);
           }
         }
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-          const uint32_t n = fast_div(idx[c], p.div_mul, p.div_shift);
+          const uint32_t n = fast_div(idx[c], pr.div_mul, pr.div_shift);
           const uint32_t r = n - (uint32_t)(band * 64);                   // row inside the band
-          const uint32_t kk = (idx[c] - n * (uint32_t)p.K) & 63u;
+          const uint32_t kk = (idx[c] - n * (uint32_t)pr.K) & 63u;
           wp[4 * lane + c] = (r < 64u) ? (uint16_t)lds_pos<DT>(wave * 64 + (int)r, (int)kk) : (uint16_t)0xFFFFu;
           wv[4 * lane + c] = val[c];
           if (DUAL) wv_minus[4 * lane + c] = val_minus[c];
@@ -438,7 +454,7 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm
       if (!band_ok || kt >= nk) return;
       if ((kt & 63) == 0 && kt > 0) {                        // the first 64 boundaries were loaded with tile_lo
         const uint32_t t = tp_base + (uint32_t)kt + 1u + lane;
-        tp_reg = (t <= tp_base + (uint32_t)nk) ? p.tile_ptr[t] : band_end;
+        tp_reg = (t <= tp_base + (uint32_t)nk) ? cold().tile_ptr[t] : band_end;
         asm volatile("" : "+v"(tp_reg));       // consume the load here, so that no wait on it is needed later
       }
       const uint32_t hi = __builtin_amdgcn_readlane(tp_reg, kt & 63), lo = tile_lo;
@@ -735,9 +751,10 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm
   // every such partial is added in fp64 (the loss difference of the two passes is ~1e-6 of the
   // loss, far below fp32 resolution of a long sum).
   constexpr int TROW = TN * 2 + 32;               // LDS row stride of the target tile in bytes
+  const FwdParams pe = cold();
   bool staged = false;
   if (FUSE_LOSS) {
-    staged = ((p.N & 7) == 0) && ((reinterpret_cast<uintptr_t>(p.target) & 15) == 0);
+    staged = ((pe.N & 7) == 0) && ((reinterpret_cast<uintptr_t>(pe.target) & 15) == 0);
     if (staged) {
       constexpr int CPR = TN / 8;                 // 16-byte chunks per tile row
       constexpr int ROWS_PER_PASS = 64 * NWAVES / CPR;
@@ -751,14 +768,14 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm
       // the matrix re-read its last row / last 8 columns; those LDS entries are never looked at.
       constexpr int PASSES = BM / ROWS_PER_PASS, BATCH = 4;
       static_assert(PASSES % BATCH == 0, "whole batches");
-      const int ncl = min(n0 + 8 * c, p.N - 8);
+      const int ncl = min(n0 + 8 * c, pe.N - 8);
 #pragma unroll
       for (int b = 0; b < PASSES; b += BATCH) {
         uint4 t[BATCH];
 #pragma unroll
         for (int i = 0; i < BATCH; ++i) {
-          const int m = min(m0 + r0 + ROWS_PER_PASS * (b + i), p.M - 1);
-          t[i] = *reinterpret_cast<const uint4*>(p.target + (size_t)m * p.N + ncl);
+          const int m = min(m0 + r0 + ROWS_PER_PASS * (b + i), pe.M - 1);
+          t[i] = *reinterpret_cast<const uint4*>(pe.target + (size_t)m * pe.N + ncl);
         }
 #pragma unroll
         for (int i = 0; i < BATCH; ++i)
@@ -778,7 +795,7 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm
   auto finish = [&](auto full_tag, auto staged_tag, auto store_tag) {
     constexpr bool FULL = decltype(full_tag)::value, STAGED = decltype(staged_tag)::value,
                    STORE = decltype(store_tag)::value;
-    const uint32_t ybase = (uint32_t)(m0 + ml0) * (uint32_t)p.N + (uint32_t)(n0 + nl0);   // M*N < 2^32 checked on the host
+    const uint32_t ybase = (uint32_t)(m0 + ml0) * (uint32_t)pe.N + (uint32_t)(n0 + nl0);   // M*N < 2^32 checked on the host
 #pragma unroll
     for (int i = 0; i < WMB; ++i) {
 #pragma unroll
@@ -787,14 +804,14 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int dm = 32 * i + 8 * (r >> 2) + (r & 3), dn = 32 * j;
-          if (FULL || (m0 + ml0 + dm < p.M && n0 + nl0 + dn < p.N)) {
+          if (FULL || (m0 + ml0 + dm < pe.M && n0 + nl0 + dn < pe.N)) {
             const float v = acc[i][j][r];
-            const uint32_t off = ybase + (uint32_t)dm * (uint32_t)p.N + (uint32_t)dn;
-            if (STORE) p.y[off] = v;
+            const uint32_t off = ybase + (uint32_t)dm * (uint32_t)pe.N + (uint32_t)dn;
+            if (STORE) pe.y[off] = v;
             if (FUSE_LOSS) {
               uint32_t tb;
               if (STAGED) tb = *reinterpret_cast<const uint16_t*>(trow + dm * TROW + dn * 2);
-              else tb = p.target[off];
+              else tb = pe.target[off];
               const float d = v - __uint_as_float(tb << 16);
               part = fmaf(d, d, part);
             }
@@ -807,11 +824,11 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm
   {
     using T = std::true_type;
     using F = std::false_type;
-    const bool full = m0 + BM <= p.M && n0 + TN <= p.N;
+    const bool full = m0 + BM <= pe.M && n0 + TN <= pe.N;
     if (FUSE_LOSS) {
-      if (full && staged && !p.y) finish(T{}, T{}, F{});            // the step's path
-      else if (staged) { if (p.y) finish(F{}, T{}, T{}); else finish(F{}, T{}, F{}); }
-      else { if (p.y) finish(F{}, F{}, T{}); else finish(F{}, F{}, F{}); }
+      if (full && staged && !pe.y) finish(T{}, T{}, F{});            // the step's path
+      else if (staged) { if (pe.y) finish(F{}, T{}, T{}); else finish(F{}, T{}, F{}); }
+      else { if (pe.y) finish(F{}, F{}, T{}); else finish(F{}, F{}, F{}); }
     } else {
       if (full) finish(T{}, F{}, T{});
       else finish(F{}, F{}, T{});
@@ -831,8 +848,8 @@ __device__ __forceinline__ void linear_fwd_body(const FwdParams& p, const int bm
         if (DUAL && (i % WAVES_N) >= WAVES_N / 2) b_minus += wave_part[i];
         else b += wave_part[i];
       }
-      p.partials[bm * p.grid_n + bn] = b * p.loss_scale;       // indexed by tile: the sum does not depend on the launch order
-      if (DUAL) p.partials_minus[bm * p.grid_n + bn] = b_minus * p.loss_scale;
+      pe.partials[bm * pe.grid_n + bn] = b * pe.loss_scale;       // indexed by tile: the sum does not depend on the launch order
+      if (DUAL) pe.partials_minus[bm * pe.grid_n + bn] = b_minus * pe.loss_scale;
     }
   }
 }
@@ -883,7 +900,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) linear_fwd_table_kerne
       p.signed_eps = -p.signed_eps;
     }
   }
-  linear_fwd_body<WAVES_M, WAVES_N, WMB, WNB, DT, FUSE_LOSS, FMT, DUAL>(p, bm, bn);
+  linear_fwd_body<WAVES_M, WAVES_N, WMB, WNB, DT, FUSE_LOSS, FMT, DUAL>(p, bm, bn, tab + lo * W);
 }
 
 // ---- host side -----------------------------------------------------------------------------
