@@ -29,7 +29,10 @@ PEAK_HBM_GBS = 8000.0                # MI355X HBM3E
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # script scaled by a plain copy of known size (profiles/*.md give the commands and the raw readings).
 # Only valid for the unmodified workloads; anything else reports null.
-MEASURED_TRAFFIC_BYTES = {"c3": 7.44e10, "c3m16": 3.613e9}
+MEASURED_TRAFFIC_BYTES = {"c3": 7.44e10, "c3m16": 3.613e9,
+                          # the extra legs of the default run (one Mistral block by density, 32 OPT blocks by token count)
+                          "c4:0.0001": 4.329e9, "c4:0.001": 4.358e9, "c4:0.01": 4.604e9,
+                          "c5:1": 3.447e9, "c5:16": 3.586e9, "c5:64": 4.237e9}
 
 
 def log(*a):
@@ -140,7 +143,8 @@ def extra_workload(szo, torch, stack, name, seed, data_seed, dt, variants, steps
         descs = descs_for(szo, mats, M, dt, with_y=False)
         t = time_steps(szo, torch, descs, seed, cfg["eps"], cfg["lr"], szo.STEP_FUSED_LOSS,
                        steps or (200 if few else 20), warmup if warmup is not None else (30 if few else 5))
-        roof, upd, step_flops = rooflines(mats, M, t, few, True)
+        traffic = MEASURED_TRAFFIC_BYTES.get(f"{name}:{v['density']:g}" if "density" in v else f"{name}:{M}") if dt == szo.TILE_F16 else None
+        roof, upd, step_flops = rooflines(mats, M, t, few, True, traffic)
         row = {"M": M, "density": v.get("density", cfg["density"]), "matrices": len(mats),
                "ms_per_step": round(t["ms_per_step"], 4), "steps": t["steps"], "warmup": t["warmup"],
                "step_tflops": round(step_flops / (t["ms_per_step"] * 1e-3) / 1e12, 2),
